@@ -1,0 +1,147 @@
+/*
+ * lg.h -- C ABI of liblg: the paper's dense structured tensor ops on one AMD
+ * MI355X (gfx950), fp32, row-major.
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - Every data pointer is a DEVICE pointer to fp32 elements owned by the
+ *    caller.  The library never allocates, frees or retains device memory and
+ *    keeps no state between calls.
+ *  - Extents, strides and leading dimensions are in ELEMENTS (int64_t).  A
+ *    tensor is row-major: the last index is contiguous.  Operands follow the
+ *    memref convention of Section 2.3 (pointer + sizes + strides); only the
+ *    row stride of 2-D operands is free, N-D convolution operands are dense.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    A call only enqueues work on it and returns; it never synchronises.
+ *  - Outputs are destination-passing operands (Section 3.4): with
+ *    `accumulate` == 0 the output is overwritten and never read; with
+ *    `accumulate` != 0 the computed value is added to what it holds.
+ *  - Inputs must not overlap outputs.
+ *  - Return value: LG_OK or a negative LG_ERR_* code.  Nothing is enqueued
+ *    when an error is returned.  The library never aborts, throws or prints.
+ *  - An output with a zero extent is a successful no-op.  A zero REDUCTION
+ *    extent yields the neutral element 0 (or leaves an accumulated output
+ *    unchanged), cf. the neutral padding value of Section 3.2.
+ *  - `workspace` is caller-provided device scratch, 256-byte aligned, of at
+ *    least the byte count the matching *_workspace_bytes() call returns (which
+ *    may be 0, in which case NULL is accepted).  Its contents on entry are
+ *    irrelevant and it may be reused once the stream has passed the call.
+ *  - Fast paths need 16-byte aligned base pointers and row lengths / leading
+ *    dimensions that are multiples of 4 elements; anything else is handled by
+ *    slower element-wise kernels with identical results, not rejected.
+ */
+#ifndef LG_H
+#define LG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LG_OK 0
+#define LG_ERR_INVALID_ARG (-1) /* null pointer, negative extent, ld < row length, stride/dilation < 1,
+                                   window larger than the input, input overlapping output */
+#define LG_ERR_UNSUPPORTED (-2) /* valid problem outside what the kernels index (an operand with
+                                   2^31 or more elements in a dimension product the kernels
+                                   address with 32 bits, or a grid beyond launch limits) */
+#define LG_ERR_WORKSPACE (-3)   /* workspace missing, misaligned or too small */
+#define LG_ERR_RUNTIME (-4)     /* the HIP runtime refused the launch */
+
+/* Version of this ABI (major * 100 + minor). */
+int lg_version(void);
+
+/* Static, human-readable name of a status code. */
+const char *lg_status_string(int status);
+
+/*
+ * Matrix multiplication, Section 4.6.1 equation (AB):
+ *     C[m,n] (+)= sum_k A[m,k] * B[k,n]
+ * A is M x K with row stride lda >= K, B is K x N with row stride ldb >= N,
+ * C is M x N with row stride ldc >= N.  Products and sums are fp32 (matrix-core
+ * FMA); the order of the k-sum is unspecified but fixed for a given shape, so
+ * repeated calls give identical bits.
+ * Workspace: lg_matmul_workspace_bytes(M, N, K); used to combine partial sums
+ * when the k-range is split across workgroups.
+ */
+int lg_matmul(const float *A, const float *B, float *C,
+              int64_t M, int64_t N, int64_t K,
+              int64_t lda, int64_t ldb, int64_t ldc,
+              int accumulate, void *workspace, size_t workspace_bytes, void *stream);
+size_t lg_matmul_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
+/*
+ * 2-D convolution, Section 4.6.2 equation (2-D), NHWC input, HWCF filter:
+ *     O[n,h,w,f] (+)= sum_{kh,kw,c} I[n, h*SH + kh*DH, w*SW + kw*DW, c] * Kf[kh,kw,c,f]
+ * (cross-correlation: the filter is not flipped).  I is dense [N,H,W,C], Kf is
+ * dense [KH,KW,C,F], O is dense [N,OH,OW,F] with the "valid" extents
+ *     OH = (H - DH*(KH-1) - 1) / SH + 1,   OW = (W - DW*(KW-1) - 1) / SW + 1
+ * (floor division); there is no padding.  LG_ERR_INVALID_ARG when the dilated
+ * window does not fit in the input.  The 1-D op of the same section is the case
+ * H = KH = 1.  Computed as an implicit GEMM of size (N*OH*OW) x F x (KH*KW*C).
+ */
+int lg_conv2d_nhwc_hwcf(const float *I, const float *Kf, float *O,
+                        int64_t N, int64_t H, int64_t W, int64_t C,
+                        int64_t KH, int64_t KW, int64_t F,
+                        int64_t SH, int64_t SW, int64_t DH, int64_t DW,
+                        int accumulate, void *workspace, size_t workspace_bytes, void *stream);
+size_t lg_conv2d_workspace_bytes(int64_t N, int64_t H, int64_t W, int64_t C,
+                                 int64_t KH, int64_t KW, int64_t F,
+                                 int64_t SH, int64_t SW, int64_t DH, int64_t DW);
+
+/* Output extent used above for one spatial dimension; 0 when the window does not fit. */
+int64_t lg_conv_out_extent(int64_t in, int64_t k, int64_t stride, int64_t dilation);
+
+/*
+ * Depthwise convolutions, Section 4.7:
+ *   1-D  O[n,w,c]   (+)= sum_kw      I[n, w*SW + kw*DW, c] * Kf[kw,c]
+ *   2-D  O[n,h,w,c] (+)= sum_{kh,kw} I[n, h*SH + kh*DH, w*SW + kw*DW, c] * Kf[kh,kw,c]
+ * I dense [N,W,C] / [N,H,W,C]; Kf dense [KW,C] / [KH,KW,C]; O dense with the
+ * same "valid" output extents as lg_conv2d_nhwc_hwcf.
+ */
+int lg_dwconv1d_nwc_wc(const float *I, const float *Kf, float *O,
+                       int64_t N, int64_t W, int64_t C, int64_t KW,
+                       int64_t SW, int64_t DW, int accumulate, void *stream);
+int lg_dwconv2d_nhwc_hwc(const float *I, const float *Kf, float *O,
+                         int64_t N, int64_t H, int64_t W, int64_t C,
+                         int64_t KH, int64_t KW,
+                         int64_t SH, int64_t SW, int64_t DH, int64_t DW,
+                         int accumulate, void *stream);
+
+/*
+ * Reductions of a 2-D tensor to a 1-D tensor, Section 4.4 (RowRed2D, ColRed2D):
+ *   lg_reduce_rows:  out[i] (+)= sum_j in[i,j]   out has R  entries
+ *   lg_reduce_cols:  out[j] (+)= sum_i in[i,j]   out has Cn entries
+ * `in` is R x Cn with row stride ld >= Cn.  Sums are fp32, formed as short
+ * per-lane partial sums combined by trees (never one long running sum).
+ * lg_reduce_cols splits the rows across workgroups and combines the partial
+ * vectors from the workspace.
+ */
+int lg_reduce_rows(const float *in, float *out, int64_t R, int64_t Cn, int64_t ld,
+                   int accumulate, void *stream);
+int lg_reduce_cols(const float *in, float *out, int64_t R, int64_t Cn, int64_t ld,
+                   int accumulate, void *workspace, size_t workspace_bytes, void *stream);
+size_t lg_reduce_cols_workspace_bytes(int64_t R, int64_t Cn);
+
+/*
+ * 2-D transpose, Section 4.4 (Transpose2D):   out[j,i] = in[i,j]
+ * `in` is R x Cn with row stride ld_in >= Cn; `out` is Cn x R with row stride
+ * ld_out >= R.  Bit patterns are moved untouched (NaN payloads, signed zeros
+ * and denormals survive).  In-place operation is rejected.
+ */
+int lg_transpose(const float *in, float *out, int64_t R, int64_t Cn,
+                 int64_t ld_in, int64_t ld_out, void *stream);
+
+/*
+ * 2-D copy, Section 4.4 (Copy2D):   out[i,j] = in[i,j]
+ * The paper's bandwidth yardstick; here the measured HBM ceiling the
+ * memory-bound ops are quoted against.
+ */
+int lg_copy2d(const float *in, float *out, int64_t R, int64_t Cn,
+              int64_t ld_in, int64_t ld_out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LG_H */
