@@ -1,0 +1,480 @@
+// Matmul (Section 4.6.1, equation AB) and conv_2d_nhwc_hwcf (Section 4.6.2) on the fp32 matrix
+// cores of gfx950.  One kernel template serves both: the convolution is the same contraction with
+// M = N*OH*OW, N = F, K = KH*KW*C, whose A operand is gathered from the NHWC input on the fly
+// (implicit GEMM; the HWCF filter already is a row-major [K, F] matrix).
+//
+// Decomposition (the hardware counterpart of the paper's tile / pack / vectorise / contract steps):
+//   grid      -> BM x BN output tiles, dealt so that each XCD's L2 sees a compact block of tiles
+//   workgroup -> stages A[BM x 16] and B[16 x BN] k-slices global -> registers -> LDS, double buffered,
+//                with the next slice's global loads in flight while the current one is multiplied
+//   wavefront -> WM x WN register tile of 32x32 fp32 accumulators, v_mfma_f32_32x32x2_f32
+//   epilogue  -> accumulators (+ C) straight to global memory with 128-bit stores
+//
+// Operand placement tricks that rely only on the sum over k and the set of columns being
+// order-free:
+//   * k-permutation: the two half-waves of an MFMA hold k and k' of a pair; a lane reads FOUR
+//     consecutive k of its A row with one ds_read_b128 and feeds them to four MFMAs, while the B
+//     rows are picked to match (half h of step 4j+i uses k = 8j + 4h + i).
+//   * n-interleave: column block nb of a wave tile holds columns NB*c + nb (c = lane % 32), so one
+//     ds_read_b{32*NB} fetches the B values of all NB blocks and the epilogue finds NB adjacent
+//     columns of one row in one lane -> 128-bit stores when NB = 4.
+#include "lg_common.hpp"
+
+namespace lg {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int BK = 16;   // k-slice staged per main-loop step
+
+struct ConvGeom {        // implicit-GEMM A operand: row m -> (n, oh, ow), column k -> (kh, kw, c)
+    int64_t H, W, C, KW, SH, SW, DH, DW, OH, OW;
+};
+
+struct GemmArgs {
+    const float* A;      // matmul: M x K, row stride lda.  conv: NHWC input
+    const float* B;      // K x N, row stride ldb
+    float* C;            // M x N, row stride ldc (or split-k partials: slab z at C + z*M*ldc)
+    int64_t M, N, K;
+    int64_t lda, ldb, ldc;
+    int64_t k_per_split; // multiple of BK; slab z covers k in [z*k_per_split, min(K, (z+1)*k_per_split))
+    int accumulate;      // only honoured when the grid has one k-slab
+    unsigned tiles_m, tiles_n;
+    ConvGeom g;
+};
+
+template <int BM_, int BN_, int WM_, int WN_>
+struct Tile {
+    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
+    static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN;
+    static constexpr int WAVES = WAVES_M * WAVES_N;
+    static constexpr int THREADS = WAVES * kWave;
+    static constexpr int MB = WM / 32;              // accumulator blocks along m per wave
+    static constexpr int NB = WN / 32;              // along n (1, 2 or 4: lanes hold NB adjacent columns)
+    static constexpr int A_QUADS = BM * BK / 4;     // float4s in an A slice
+    static constexpr int B_QUADS = BK * BN / 4;
+    static constexpr int A_PER_T = A_QUADS / THREADS;
+    static constexpr int B_PER_T = B_QUADS / THREADS;
+    static constexpr int LDS_FLOATS = 2 * (BM * BK + BK * BN);
+    static_assert(NB == 1 || NB == 2 || NB == 4, "wave tile width must be 32, 64 or 128");
+    static_assert(A_QUADS % THREADS == 0 && B_QUADS % THREADS == 0, "slice must divide over the workgroup");
+};
+
+// LDS position (in floats) of the float4 holding A[m][4q .. 4q+3] of a slice.  Rows are 16 floats;
+// the quad index is XOR-swizzled with bits of m so that 8 consecutive rows reading the same
+// logical quad touch 8 distinct 4-bank groups.
+__device__ __forceinline__ int a_lds_off(int m, int q) { return m * BK + ((q ^ ((m >> 1) & 3)) << 2); }
+
+template <class T, bool VEC, bool CONV>
+__global__ __launch_bounds__(T::THREADS) void gemm_kernel(const GemmArgs p) {
+    constexpr int BM = T::BM, BN = T::BN, MB = T::MB, NB = T::NB;
+    extern __shared__ __align__(16) float lds[];
+    float* As = lds;                        // [2][BM*BK]
+    float* Bs = lds + 2 * BM * BK;          // [2][BK*BN]
+
+    // ---- which tile ------------------------------------------------------------------------
+    const unsigned ntiles = p.tiles_m * p.tiles_n;
+    const unsigned L = xcd_contiguous_id(blockIdx.x, ntiles);
+    constexpr unsigned GM = 4;              // tile rows per panel: an XCD's share is ~GM x (32/GM) tiles
+    const unsigned panel = L / (GM * p.tiles_n);
+    const unsigned first_m = panel * GM;
+    const unsigned gsz = (p.tiles_m - first_m < GM) ? p.tiles_m - first_m : GM;
+    const unsigned in_panel = L - panel * GM * p.tiles_n;
+    const int64_t m0 = (int64_t)(first_m + in_panel % gsz) * BM;
+    const int64_t n0 = (int64_t)(in_panel / gsz) * BN;
+    const int64_t kbeg = (int64_t)blockIdx.y * p.k_per_split;
+    const int64_t kend = (kbeg + p.k_per_split < p.K) ? kbeg + p.k_per_split : p.K;
+    const int nslices = (int)((kend - kbeg + BK - 1) / BK);
+
+    const int t = threadIdx.x;
+    const int lane = t % kWave, wave = t / kWave;
+    const int wm0 = (wave / T::WAVES_N) * T::WM;   // wave tile origin inside the block tile
+    const int wn0 = (wave % T::WAVES_N) * T::WN;
+    const int c32 = lane % 32, h = lane / 32;
+
+    // ---- global -> register staging ------------------------------------------------------------
+    // A slice: thread owns float4 (row ar[i], quad aq) for i < A_PER_T; B slice: (row bk[i], float4 column bq[i]).
+    const int aq = t % 4;
+    int64_t a_rowbase[T::A_PER_T];          // element offset of A[m][0]; -1 when the row is outside M
+#pragma unroll
+    for (int i = 0; i < T::A_PER_T; ++i) {
+        const int r = t / 4 + i * (T::THREADS / 4);
+        const int64_t m = m0 + r;
+        if (m >= p.M) { a_rowbase[i] = -1; continue; }
+        if constexpr (CONV) {
+            const int64_t ow = m % p.g.OW, oh = (m / p.g.OW) % p.g.OH, n = m / (p.g.OW * p.g.OH);
+            a_rowbase[i] = ((n * p.g.H + oh * p.g.SH) * p.g.W + ow * p.g.SW) * p.g.C;
+        } else {
+            a_rowbase[i] = m * p.lda;
+        }
+    }
+    float4 ra[T::A_PER_T], rb[T::B_PER_T];
+
+    auto a_koff = [&](int64_t k) -> int64_t {      // offset of column k relative to the row base
+        if constexpr (CONV) {
+            const int64_t c = k % p.g.C, kk = k / p.g.C;
+            const int64_t kw = kk % p.g.KW, kh = kk / p.g.KW;
+            return (kh * p.g.DH * p.g.W + kw * p.g.DW) * p.g.C + c;
+        } else {
+            return k;
+        }
+    };
+
+    auto load_slice = [&](int64_t k0) {
+        // A
+        if constexpr (VEC) {
+            const int64_t k = k0 + 4 * aq;
+            const bool kin = k < kend;             // K % 4 == 0 on this path: a quad is all in or all out
+            const int64_t ko = kin ? a_koff(k) : 0;
+#pragma unroll
+            for (int i = 0; i < T::A_PER_T; ++i) {
+                ra[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (kin && a_rowbase[i] >= 0) ra[i] = *reinterpret_cast<const float4*>(p.A + a_rowbase[i] + ko);
+            }
+        } else {
+            int64_t ko[4];
+            bool kin[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int64_t k = k0 + 4 * aq + e;
+                kin[e] = k < kend;
+                ko[e] = kin[e] ? a_koff(k) : 0;
+            }
+#pragma unroll
+            for (int i = 0; i < T::A_PER_T; ++i) {
+                float v[4] = {0.f, 0.f, 0.f, 0.f};
+                if (a_rowbase[i] >= 0) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (kin[e]) v[e] = p.A[a_rowbase[i] + ko[e]];
+                }
+                ra[i] = make_float4(v[0], v[1], v[2], v[3]);
+            }
+        }
+        // B
+#pragma unroll
+        for (int i = 0; i < T::B_PER_T; ++i) {
+            const int q = t + i * T::THREADS;
+            const int kr = q / (BN / 4), nq = q % (BN / 4);
+            const int64_t k = k0 + kr, n = n0 + 4 * nq;
+            rb[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (k < kend) {
+                const float* bp = p.B + k * p.ldb + n;
+                if constexpr (VEC) {
+                    if (n < p.N) rb[i] = *reinterpret_cast<const float4*>(bp);   // N % 4 == 0 here
+                } else {
+                    if (n + 0 < p.N) rb[i].x = bp[0];
+                    if (n + 1 < p.N) rb[i].y = bp[1];
+                    if (n + 2 < p.N) rb[i].z = bp[2];
+                    if (n + 3 < p.N) rb[i].w = bp[3];
+                }
+            }
+        }
+    };
+
+    auto store_slice = [&](int buf) {
+        float* as = As + buf * (BM * BK);
+        float* bs = Bs + buf * (BK * BN);
+#pragma unroll
+        for (int i = 0; i < T::A_PER_T; ++i) {
+            const int r = t / 4 + i * (T::THREADS / 4);
+            *reinterpret_cast<float4*>(as + a_lds_off(r, aq)) = ra[i];
+        }
+#pragma unroll
+        for (int i = 0; i < T::B_PER_T; ++i) {
+            const int q = t + i * T::THREADS;
+            *reinterpret_cast<float4*>(bs + 4 * q) = rb[i];      // row-major [BK][BN]
+        }
+    };
+
+    // ---- accumulators ------------------------------------------------------------------------
+    floatx16 acc[MB][NB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
+
+    auto compute_slice = [&](int buf) {
+        const float* as = As + buf * (BM * BK);
+        const float* bs = Bs + buf * (BK * BN) + wn0 + NB * c32;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            float4 a[MB];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+                a[mb] = *reinterpret_cast<const float4*>(as + a_lds_off(wm0 + mb * 32 + c32, 2 * j + h));
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float* brow = bs + (8 * j + 4 * h + i) * BN;
+                float b[NB];
+                if constexpr (NB == 4) {
+                    const float4 v = *reinterpret_cast<const float4*>(brow);
+                    b[0] = v.x; b[1] = v.y; b[2] = v.z; b[3] = v.w;
+                } else if constexpr (NB == 2) {
+                    const float2 v = *reinterpret_cast<const float2*>(brow);
+                    b[0] = v.x; b[1] = v.y;
+                } else {
+                    b[0] = *brow;
+                }
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    const float av = (i == 0) ? a[mb].x : (i == 1) ? a[mb].y : (i == 2) ? a[mb].z : a[mb].w;
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+                        acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, b[nb], acc[mb][nb], 0, 0, 0);
+                }
+            }
+        }
+    };
+
+    // ---- main loop -----------------------------------------------------------------------------
+    if (nslices > 0) {
+        load_slice(kbeg);
+        store_slice(0);
+        __syncthreads();
+        for (int s = 0; s < nslices; ++s) {
+            const bool more = s + 1 < nslices;
+            if (more) load_slice(kbeg + (int64_t)(s + 1) * BK);
+            compute_slice(s & 1);
+            if (more) store_slice((s + 1) & 1);
+            __syncthreads();
+        }
+    }
+
+    // ---- epilogue ------------------------------------------------------------------------------
+    // accumulator register r of block (mb, nb): row = 32*mb + 8*(r/4) + 4*h + r%4, column = NB*c32 + nb
+    float* Cz = p.C + (int64_t)blockIdx.y * p.M * p.ldc;
+    const int64_t ncol = n0 + wn0 + NB * c32;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t m = m0 + wm0 + mb * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+            if (m >= p.M) continue;
+            float* cp = Cz + m * p.ldc + ncol;
+            float v[NB];
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) v[nb] = acc[mb][nb][r];
+            if constexpr (VEC && NB == 4) {
+                if (ncol < p.N) {
+                    float4 o = make_float4(v[0], v[1], v[2], v[3]);
+                    if (p.accumulate) {
+                        const float4 c = *reinterpret_cast<const float4*>(cp);
+                        o.x += c.x; o.y += c.y; o.z += c.z; o.w += c.w;
+                    }
+                    *reinterpret_cast<float4*>(cp) = o;
+                }
+            } else if constexpr (VEC && NB == 2) {
+                if (ncol < p.N) {
+                    float2 o = make_float2(v[0], v[1]);
+                    if (p.accumulate) {
+                        const float2 c = *reinterpret_cast<const float2*>(cp);
+                        o.x += c.x; o.y += c.y;
+                    }
+                    *reinterpret_cast<float2*>(cp) = o;
+                }
+            } else {
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    if (ncol + nb < p.N) cp[nb] = p.accumulate ? cp[nb] + v[nb] : v[nb];
+            }
+        }
+    }
+}
+
+// out[m,n] (+)= sum_z partial[z][m,n]; slabs are dense M x N.  Fixed order: z ascending.
+__global__ __launch_bounds__(256) void splitk_combine_kernel(
+    const float* __restrict__ partial, float* __restrict__ C,
+    int64_t M, int64_t N, int64_t ldc, int splits, int accumulate) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= M * N) return;
+    const int64_t m = idx / N, n = idx - m * N;
+    float s = 0.f;
+    for (int z = 0; z < splits; ++z) s += partial[(int64_t)z * M * N + idx];
+    float* cp = C + m * ldc + n;
+    *cp = accumulate ? *cp + s : s;
+}
+
+__global__ __launch_bounds__(256) void fill_zero_2d_kernel(float* C, int64_t M, int64_t N, int64_t ldc) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= M * N) return;
+    const int64_t m = idx / N;
+    C[m * ldc + (idx - m * N)] = 0.f;
+}
+
+// ---- host side ---------------------------------------------------------------------------------
+
+using TileBig = Tile<256, 256, 64, 128>;   // 8 waves, 2 per SIMD, 128 accumulator registers per lane
+using TileMid = Tile<128, 128, 64, 64>;    // 4 waves
+using TileSmall = Tile<64, 64, 32, 32>;    // 4 waves
+
+struct Plan {
+    int tile;          // 0 big, 1 mid, 2 small
+    int64_t tiles_m, tiles_n, splits, k_per_split;
+};
+
+constexpr int kCUs = 256;
+
+static Plan make_plan(int64_t M, int64_t N, int64_t K) {
+    Plan pl;
+    const int bm[3] = {256, 128, 64};
+    // largest tile that still gives every CU a workgroup; otherwise the smallest and split k
+    int tile = 2;
+    for (int c = 0; c < 3; ++c) {
+        if (cdiv(M, bm[c]) * cdiv(N, bm[c]) >= kCUs) { tile = c; break; }
+    }
+    pl.tile = tile;
+    pl.tiles_m = cdiv(M, bm[tile]);
+    pl.tiles_n = cdiv(N, bm[tile]);
+    const int64_t tiles = pl.tiles_m * pl.tiles_n;
+    int64_t splits = 1;
+    const int64_t slices = cdiv(K, BK);
+    if (tiles < kCUs && slices >= 8) {
+        splits = cdiv(2 * kCUs, tiles);                      // aim at ~2 workgroups per CU
+        const int64_t max_splits = slices / 4 > 0 ? slices / 4 : 1;   // at least 4 slices (64 k) per slab
+        if (splits > max_splits) splits = max_splits;
+        if (splits > 64) splits = 64;
+    }
+    int64_t slices_per = cdiv(slices, splits);
+    pl.k_per_split = slices_per * BK;
+    pl.splits = cdiv(K, pl.k_per_split);
+    if (pl.splits < 1) pl.splits = 1;
+    return pl;
+}
+
+static size_t plan_workspace(const Plan& pl, int64_t M, int64_t N) {
+    return pl.splits > 1 ? (size_t)(pl.splits * M * N) * sizeof(float) : 0;
+}
+
+template <class T, bool VEC, bool CONV>
+static void launch_gemm(const GemmArgs& a, unsigned splits, hipStream_t s) {
+    static bool configured = false;
+    const size_t lds_bytes = T::LDS_FLOATS * sizeof(float);
+    if (!configured) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<T, VEC, CONV>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        configured = true;
+    }
+    hipLaunchKernelGGL((gemm_kernel<T, VEC, CONV>), dim3(a.tiles_m * a.tiles_n, splits), dim3(T::THREADS),
+                       lds_bytes, s, a);
+}
+
+template <bool CONV>
+static int run_gemm(GemmArgs a, bool vec, int user_accumulate, void* workspace, size_t workspace_bytes,
+                    hipStream_t s) {
+    const Plan pl = make_plan(a.M, a.N, a.K);
+    const size_t need = plan_workspace(pl, a.M, a.N);
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+            return LG_ERR_WORKSPACE;
+    }
+    if (pl.tiles_m * pl.tiles_n > kMaxGrid || pl.splits > 65535) return LG_ERR_UNSUPPORTED;
+    float* Cfinal = a.C;
+    const int64_t ldc_final = a.ldc;
+    a.tiles_m = (unsigned)pl.tiles_m;
+    a.tiles_n = (unsigned)pl.tiles_n;
+    a.k_per_split = pl.k_per_split;
+    if (pl.splits > 1) {
+        a.C = static_cast<float*>(workspace);
+        a.ldc = a.N;
+        a.accumulate = 0;
+    } else {
+        a.accumulate = user_accumulate;
+    }
+    const unsigned z = (unsigned)pl.splits;
+#define LG_LAUNCH(TILE)                                                   \
+    do {                                                                  \
+        if (vec) launch_gemm<TILE, true, CONV>(a, z, s);                  \
+        else     launch_gemm<TILE, false, CONV>(a, z, s);                 \
+    } while (0)
+    if (pl.tile == 0) LG_LAUNCH(TileBig);
+    else if (pl.tile == 1) LG_LAUNCH(TileMid);
+    else LG_LAUNCH(TileSmall);
+#undef LG_LAUNCH
+    if (launch_status() != LG_OK) return LG_ERR_RUNTIME;
+    if (pl.splits > 1) {
+        const int64_t blocks = cdiv(a.M * a.N, 256);
+        if (blocks > kMaxGrid) return LG_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(splitk_combine_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
+                           static_cast<const float*>(workspace), Cfinal, a.M, a.N, ldc_final, (int)pl.splits,
+                           user_accumulate);
+        return launch_status();
+    }
+    return LG_OK;
+}
+
+static int zero_output(float* C, int64_t M, int64_t N, int64_t ldc, hipStream_t s) {
+    const int64_t blocks = cdiv(M * N, 256);
+    if (blocks > kMaxGrid) return LG_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(fill_zero_2d_kernel, dim3((unsigned)blocks), dim3(256), 0, s, C, M, N, ldc);
+    return launch_status();
+}
+
+}  // namespace lg
+
+extern "C" size_t lg_matmul_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+    using namespace lg;
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    return plan_workspace(make_plan(M, N, K), M, N);
+}
+
+extern "C" int lg_matmul(const float* A, const float* B, float* C,
+                         int64_t M, int64_t N, int64_t K,
+                         int64_t lda, int64_t ldb, int64_t ldc,
+                         int accumulate, void* workspace, size_t workspace_bytes, void* stream) {
+    using namespace lg;
+    if (M < 0 || N < 0 || K < 0 || lda < K || ldb < N || ldc < N) return LG_ERR_INVALID_ARG;
+    if (M == 0 || N == 0) return LG_OK;
+    if (!C || (K > 0 && (!A || !B))) return LG_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t c_bytes = ((M - 1) * ldc + N) * 4;
+    if (K == 0) return accumulate ? LG_OK : zero_output(C, M, N, ldc, s);
+    if (overlaps(A, ((M - 1) * lda + K) * 4, C, c_bytes) || overlaps(B, ((K - 1) * ldb + N) * 4, C, c_bytes))
+        return LG_ERR_INVALID_ARG;
+    if (M >= (int64_t)1 << 31 || N >= (int64_t)1 << 31 || K >= (int64_t)1 << 31) return LG_ERR_UNSUPPORTED;
+    const bool vec = (K % 4 == 0) && (N % 4 == 0) && (lda % 4 == 0) && (ldb % 4 == 0) && (ldc % 4 == 0) &&
+                     aligned16(A) && aligned16(B) && aligned16(C);
+    GemmArgs a{};
+    a.A = A; a.B = B; a.C = C;
+    a.M = M; a.N = N; a.K = K;
+    a.lda = lda; a.ldb = ldb; a.ldc = ldc;
+    return run_gemm<false>(a, vec, accumulate, workspace, workspace_bytes, s);
+}
+
+extern "C" size_t lg_conv2d_workspace_bytes(int64_t N, int64_t H, int64_t W, int64_t C,
+                                            int64_t KH, int64_t KW, int64_t F,
+                                            int64_t SH, int64_t SW, int64_t DH, int64_t DW) {
+    using namespace lg;
+    const int64_t OH = lg_conv_out_extent(H, KH, SH, DH), OW = lg_conv_out_extent(W, KW, SW, DW);
+    if (N <= 0 || C <= 0 || F <= 0 || OH <= 0 || OW <= 0) return 0;
+    const int64_t M = N * OH * OW;
+    return plan_workspace(make_plan(M, F, KH * KW * C), M, F);
+}
+
+extern "C" int lg_conv2d_nhwc_hwcf(const float* I, const float* Kf, float* O,
+                                   int64_t N, int64_t H, int64_t W, int64_t C,
+                                   int64_t KH, int64_t KW, int64_t F,
+                                   int64_t SH, int64_t SW, int64_t DH, int64_t DW,
+                                   int accumulate, void* workspace, size_t workspace_bytes, void* stream) {
+    using namespace lg;
+    if (N < 0 || H < 0 || W < 0 || C < 0 || KH < 1 || KW < 1 || F < 0) return LG_ERR_INVALID_ARG;
+    if (SH < 1 || SW < 1 || DH < 1 || DW < 1) return LG_ERR_INVALID_ARG;
+    if (N == 0 || F == 0) return LG_OK;
+    const int64_t OH = lg_conv_out_extent(H, KH, SH, DH), OW = lg_conv_out_extent(W, KW, SW, DW);
+    if (OH == 0 || OW == 0) return LG_ERR_INVALID_ARG;
+    if (!O || (C > 0 && (!I || !Kf))) return LG_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t M = N * OH * OW, Kg = KH * KW * C;
+    if (Kg == 0) return accumulate ? LG_OK : zero_output(O, M, F, F, s);
+    if (overlaps(I, N * H * W * C * 4, O, M * F * 4) || overlaps(Kf, Kg * F * 4, O, M * F * 4))
+        return LG_ERR_INVALID_ARG;
+    if (M >= (int64_t)1 << 31 || F >= (int64_t)1 << 31 || Kg >= (int64_t)1 << 31) return LG_ERR_UNSUPPORTED;
+    const bool vec = (C % 4 == 0) && (F % 4 == 0) && aligned16(I) && aligned16(Kf) && aligned16(O);
+    GemmArgs a{};
+    a.A = I; a.B = Kf; a.C = O;
+    a.M = M; a.N = F; a.K = Kg;
+    a.lda = 0; a.ldb = F; a.ldc = F;
+    a.g = ConvGeom{H, W, C, KW, SH, SW, DH, DW, OH, OW};
+    return run_gemm<true>(a, vec, accumulate, workspace, workspace_bytes, s);
+}

@@ -1,0 +1,41 @@
+// Shared host/device helpers of liblg (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "lg.h"
+
+namespace lg {
+
+constexpr int kWave = 64;          // CDNA wavefront width
+constexpr int kXcds = 8;           // MI355X: 8 accelerator dies, workgroups are dealt to them round-robin
+constexpr int64_t kMaxGrid = 0x7FFFFFFF;
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// [a, a+na) and [b, b+nb) byte ranges overlap?
+inline bool overlaps(const void* a, int64_t na, const void* b, int64_t nb) {
+    if (na <= 0 || nb <= 0) return false;
+    uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + static_cast<uintptr_t>(nb) && b0 < a0 + static_cast<uintptr_t>(na);
+}
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? LG_OK : LG_ERR_RUNTIME; }
+
+// Workgroups are handed to the 8 XCDs round-robin (hardware id i runs on XCD i % 8) and each XCD
+// has a private L2.  This turns a hardware workgroup id into a logical one such that each XCD works
+// on one contiguous range of logical ids, so neighbouring tiles share an L2.
+__device__ __forceinline__ unsigned xcd_contiguous_id(unsigned bid, unsigned nblocks) {
+    const unsigned per = nblocks / kXcds, rem = nblocks % kXcds;
+    const unsigned x = bid % kXcds, l = bid / kXcds;
+    return x * per + (x < rem ? x : rem) + l;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+}  // namespace lg

@@ -1,0 +1,245 @@
+// RowRed2D and ColRed2D (Section 4.4): HBM-bound read streams.
+//
+// Both keep every fp32 running sum short: a lane adds at most a few dozen values before its
+// partial enters a tree (cross-lane for rows, cross-wave / cross-workgroup for columns).
+#include "lg_common.hpp"
+
+namespace lg {
+
+constexpr int kRThreads = 256;
+constexpr int kRWaves = kRThreads / kWave;
+
+// out[i] = sum_j in[i,j].  One workgroup per row when rows are long (WG_PER_ROW), one wavefront
+// per row otherwise.  Each lane owns 128-bit columns strided by the group width; four loads are
+// in flight per lane before the adds.
+template <bool VEC, bool WG_PER_ROW>
+__global__ __launch_bounds__(kRThreads) void reduce_rows_kernel(
+    const float* __restrict__ in, float* __restrict__ out,
+    int64_t R, int64_t Cn, int64_t ld, int accumulate) {
+    __shared__ float part[kRWaves];
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    const int64_t row = WG_PER_ROW ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * kRWaves + wave;
+    const int width = WG_PER_ROW ? kRThreads : kWave;
+    const int pos = WG_PER_ROW ? (int)threadIdx.x : lane;
+    float s = 0.f;
+    if (row < R) {
+        const float* p = in + row * ld;
+        if constexpr (VEC) {
+            const int64_t n4 = Cn / 4;
+            float4 a0 = make_float4(0, 0, 0, 0), a1 = a0, a2 = a0, a3 = a0;
+            int64_t j = pos;
+            for (; j + 3 * width < n4; j += 4 * width) {
+                const float4 v0 = *reinterpret_cast<const float4*>(p + 4 * j);
+                const float4 v1 = *reinterpret_cast<const float4*>(p + 4 * (j + width));
+                const float4 v2 = *reinterpret_cast<const float4*>(p + 4 * (j + 2 * width));
+                const float4 v3 = *reinterpret_cast<const float4*>(p + 4 * (j + 3 * width));
+                a0.x += v0.x; a0.y += v0.y; a0.z += v0.z; a0.w += v0.w;
+                a1.x += v1.x; a1.y += v1.y; a1.z += v1.z; a1.w += v1.w;
+                a2.x += v2.x; a2.y += v2.y; a2.z += v2.z; a2.w += v2.w;
+                a3.x += v3.x; a3.y += v3.y; a3.z += v3.z; a3.w += v3.w;
+            }
+            for (; j < n4; j += width) {
+                const float4 v0 = *reinterpret_cast<const float4*>(p + 4 * j);
+                a0.x += v0.x; a0.y += v0.y; a0.z += v0.z; a0.w += v0.w;
+            }
+            s = ((a0.x + a1.x) + (a2.x + a3.x)) + ((a0.y + a1.y) + (a2.y + a3.y)) +
+                (((a0.z + a1.z) + (a2.z + a3.z)) + ((a0.w + a1.w) + (a2.w + a3.w)));
+        } else {
+            float b0 = 0.f, b1 = 0.f, b2 = 0.f, b3 = 0.f;
+            int64_t j = pos;
+            for (; j + 3 * width < Cn; j += 4 * width) {
+                b0 += p[j]; b1 += p[j + width]; b2 += p[j + 2 * width]; b3 += p[j + 3 * width];
+            }
+            for (; j < Cn; j += width) b0 += p[j];
+            s = (b0 + b1) + (b2 + b3);
+        }
+    }
+    s = wave_sum(s);
+    if constexpr (WG_PER_ROW) {
+        if (lane == 0) part[wave] = s;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float tot = (part[0] + part[1]) + (part[2] + part[3]);
+            if (accumulate) tot += out[row];
+            out[row] = tot;
+        }
+    } else {
+        if (lane == 0 && row < R) {
+            if (accumulate) s += out[row];
+            out[row] = s;
+        }
+    }
+}
+
+constexpr int kCRowsPerWave = 32;   // rows one lane adds sequentially (at most)
+constexpr int kCMaxSplit = 1024;
+
+// Stage 1 of out[j] = sum_i in[i,j]: workgroup (bx, by) sums rows [by*rows_per_wg, ...) of the
+// 64*W columns starting at bx*64*W.  Each lane owns W adjacent columns; the four wavefronts take
+// interleaved rows and are combined through LDS.  dst is the partial buffer (row by of width
+// ldp) or the final output when the row range is not split.
+template <bool VEC>
+__global__ __launch_bounds__(kRThreads) void reduce_cols_kernel(
+    const float* __restrict__ in, float* __restrict__ dst,
+    int64_t R, int64_t Cn, int64_t ld, int64_t rows_per_wg, int64_t ldp, int final_accumulate) {
+    constexpr int W = VEC ? 4 : 1;
+    __shared__ float part[kRWaves][kWave * W];
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    const int64_t col = ((int64_t)blockIdx.x * kWave + lane) * W;
+    const int64_t r0 = (int64_t)blockIdx.y * rows_per_wg;
+    const int64_t r1 = (r0 + rows_per_wg < R) ? r0 + rows_per_wg : R;
+    float acc[2][W];
+#pragma unroll
+    for (int w = 0; w < W; ++w) acc[0][w] = acc[1][w] = 0.f;
+    if (col < Cn) {
+        const float* p = in + col;
+        int64_t r = r0 + wave;
+        if constexpr (VEC) {
+            for (; r + 3 * kRWaves < r1; r += 4 * kRWaves) {
+                const float4 v0 = *reinterpret_cast<const float4*>(p + r * ld);
+                const float4 v1 = *reinterpret_cast<const float4*>(p + (r + kRWaves) * ld);
+                const float4 v2 = *reinterpret_cast<const float4*>(p + (r + 2 * kRWaves) * ld);
+                const float4 v3 = *reinterpret_cast<const float4*>(p + (r + 3 * kRWaves) * ld);
+                acc[0][0] += v0.x; acc[0][1] += v0.y; acc[0][2] += v0.z; acc[0][3] += v0.w;
+                acc[1][0] += v1.x; acc[1][1] += v1.y; acc[1][2] += v1.z; acc[1][3] += v1.w;
+                acc[0][0] += v2.x; acc[0][1] += v2.y; acc[0][2] += v2.z; acc[0][3] += v2.w;
+                acc[1][0] += v3.x; acc[1][1] += v3.y; acc[1][2] += v3.z; acc[1][3] += v3.w;
+            }
+            for (; r < r1; r += kRWaves) {
+                const float4 v0 = *reinterpret_cast<const float4*>(p + r * ld);
+                acc[0][0] += v0.x; acc[0][1] += v0.y; acc[0][2] += v0.z; acc[0][3] += v0.w;
+            }
+        } else {
+            for (; r + kRWaves < r1; r += 2 * kRWaves) {
+                acc[0][0] += p[r * ld];
+                acc[1][0] += p[(r + kRWaves) * ld];
+            }
+            for (; r < r1; r += kRWaves) acc[0][0] += p[r * ld];
+        }
+    }
+#pragma unroll
+    for (int w = 0; w < W; ++w) part[wave][lane * W + w] = acc[0][w] + acc[1][w];
+    __syncthreads();
+    // 64*W columns, 256 threads: thread t finishes column t (and t+256.. when W == 4 -> exactly W/ (256/64)=1 pass)
+    for (int c = threadIdx.x; c < kWave * W; c += kRThreads) {
+        const int64_t gc = (int64_t)blockIdx.x * kWave * W + c;
+        if (gc < Cn) {
+            float tot = (part[0][c] + part[1][c]) + (part[2][c] + part[3][c]);
+            float* o = dst + (int64_t)blockIdx.y * ldp + gc;
+            if (final_accumulate) tot += *o;
+            *o = tot;
+        }
+    }
+}
+
+// Stage 2: out[j] (+)= sum_s partial[s][j], in a fixed order (pairwise over four running sums).
+__global__ __launch_bounds__(kRThreads) void reduce_cols_combine_kernel(
+    const float* __restrict__ partial, float* __restrict__ out,
+    int64_t Cn, int64_t ldp, int splits, int accumulate) {
+    const int64_t j = (int64_t)blockIdx.x * kRThreads + threadIdx.x;
+    if (j >= Cn) return;
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    int s = 0;
+    for (; s + 3 < splits; s += 4) {
+        a0 += partial[(int64_t)s * ldp + j];
+        a1 += partial[(int64_t)(s + 1) * ldp + j];
+        a2 += partial[(int64_t)(s + 2) * ldp + j];
+        a3 += partial[(int64_t)(s + 3) * ldp + j];
+    }
+    for (; s < splits; ++s) a0 += partial[(int64_t)s * ldp + j];
+    float tot = (a0 + a1) + (a2 + a3);
+    if (accumulate) tot += out[j];
+    out[j] = tot;
+}
+
+__global__ void fill_zero_kernel(float* out, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = 0.f;
+}
+
+struct ColPlan { int64_t splits, rows_per_wg, ldp; };
+
+static ColPlan plan_cols(int64_t R, int64_t Cn) {
+    ColPlan p;
+    const int64_t rows_per_wg_min = (int64_t)kCRowsPerWave * kRWaves;   // 128 rows per workgroup
+    int64_t splits = cdiv(R, rows_per_wg_min);
+    if (splits > kCMaxSplit) splits = kCMaxSplit;
+    if (splits < 1) splits = 1;
+    p.rows_per_wg = cdiv(R, splits);
+    p.splits = cdiv(R, p.rows_per_wg);
+    p.ldp = cdiv(Cn, 64) * 64;
+    return p;
+}
+
+}  // namespace lg
+
+extern "C" int lg_reduce_rows(const float* in, float* out, int64_t R, int64_t Cn, int64_t ld,
+                              int accumulate, void* stream) {
+    using namespace lg;
+    if (R < 0 || Cn < 0 || ld < Cn) return LG_ERR_INVALID_ARG;
+    if (R == 0) return LG_OK;
+    if (!out || (Cn > 0 && !in)) return LG_ERR_INVALID_ARG;
+    if (Cn > 0 && overlaps(in, ((R - 1) * ld + Cn) * 4, out, R * 4)) return LG_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool vec = Cn > 0 && (Cn % 4 == 0) && (ld % 4 == 0) && aligned16(in);
+    const bool wg_per_row = Cn >= 4096;
+    const int64_t blocks = wg_per_row ? R : cdiv(R, kRWaves);
+    if (blocks > kMaxGrid) return LG_ERR_UNSUPPORTED;
+    const dim3 g((unsigned)blocks), b(kRThreads);
+    if (vec && wg_per_row)       hipLaunchKernelGGL((reduce_rows_kernel<true, true>), g, b, 0, s, in, out, R, Cn, ld, accumulate);
+    else if (vec)                hipLaunchKernelGGL((reduce_rows_kernel<true, false>), g, b, 0, s, in, out, R, Cn, ld, accumulate);
+    else if (wg_per_row)         hipLaunchKernelGGL((reduce_rows_kernel<false, true>), g, b, 0, s, in, out, R, Cn, ld, accumulate);
+    else                         hipLaunchKernelGGL((reduce_rows_kernel<false, false>), g, b, 0, s, in, out, R, Cn, ld, accumulate);
+    return launch_status();
+}
+
+extern "C" size_t lg_reduce_cols_workspace_bytes(int64_t R, int64_t Cn) {
+    using namespace lg;
+    if (R <= 0 || Cn <= 0) return 0;
+    const ColPlan p = plan_cols(R, Cn);
+    return p.splits > 1 ? (size_t)(p.splits * p.ldp) * sizeof(float) : 0;
+}
+
+extern "C" int lg_reduce_cols(const float* in, float* out, int64_t R, int64_t Cn, int64_t ld,
+                              int accumulate, void* workspace, size_t workspace_bytes, void* stream) {
+    using namespace lg;
+    if (R < 0 || Cn < 0 || ld < Cn) return LG_ERR_INVALID_ARG;
+    if (Cn == 0) return LG_OK;
+    if (!out || (R > 0 && !in)) return LG_ERR_INVALID_ARG;
+    if (R > 0 && overlaps(in, ((R - 1) * ld + Cn) * 4, out, Cn * 4)) return LG_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (R == 0) {
+        if (!accumulate) {
+            const int64_t blocks = cdiv(Cn, 256);
+            if (blocks > kMaxGrid) return LG_ERR_UNSUPPORTED;
+            hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s, out, Cn);
+            return launch_status();
+        }
+        return LG_OK;
+    }
+    const ColPlan p = plan_cols(R, Cn);
+    const size_t need = p.splits > 1 ? (size_t)(p.splits * p.ldp) * sizeof(float) : 0;
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+            return LG_ERR_WORKSPACE;
+        if (overlaps(workspace, (int64_t)need, out, Cn * 4) ||
+            overlaps(workspace, (int64_t)need, in, ((R - 1) * ld + Cn) * 4))
+            return LG_ERR_INVALID_ARG;
+    }
+    const bool vec = (Cn % 4 == 0) && (ld % 4 == 0) && aligned16(in);
+    const int64_t bx = cdiv(Cn, vec ? 256 : 64);
+    if (bx > kMaxGrid || p.splits > 65535) return LG_ERR_UNSUPPORTED;
+    const dim3 g((unsigned)bx, (unsigned)p.splits), b(kRThreads);
+    float* dst = p.splits > 1 ? static_cast<float*>(workspace) : out;
+    const int64_t ldp = p.splits > 1 ? p.ldp : 0;
+    const int facc = p.splits > 1 ? 0 : accumulate;
+    if (vec) hipLaunchKernelGGL(reduce_cols_kernel<true>, g, b, 0, s, in, dst, R, Cn, ld, p.rows_per_wg, ldp, facc);
+    else     hipLaunchKernelGGL(reduce_cols_kernel<false>, g, b, 0, s, in, dst, R, Cn, ld, p.rows_per_wg, ldp, facc);
+    if (launch_status() != LG_OK) return LG_ERR_RUNTIME;
+    if (p.splits > 1) {
+        hipLaunchKernelGGL(reduce_cols_combine_kernel, dim3((unsigned)cdiv(Cn, kRThreads)), b, 0, s,
+                           static_cast<const float*>(workspace), out, Cn, p.ldp, (int)p.splits, accumulate);
+        return launch_status();
+    }
+    return LG_OK;
+}

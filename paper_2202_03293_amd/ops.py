@@ -1,0 +1,228 @@
+"""ctypes binding of liblg.so on torch device tensors (argument marshalling only)."""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblg.so")
+
+_i64 = ctypes.c_int64
+_vp = ctypes.c_void_p
+_int = ctypes.c_int
+_sz = ctypes.c_size_t
+
+_SIGNATURES = {
+    "lg_version": (_int, []),
+    "lg_status_string": (ctypes.c_char_p, [_int]),
+    "lg_conv_out_extent": (_i64, [_i64] * 4),
+    "lg_matmul": (_int, [_vp, _vp, _vp] + [_i64] * 6 + [_int, _vp, _sz, _vp]),
+    "lg_matmul_workspace_bytes": (_sz, [_i64] * 3),
+    "lg_conv2d_nhwc_hwcf": (_int, [_vp, _vp, _vp] + [_i64] * 11 + [_int, _vp, _sz, _vp]),
+    "lg_conv2d_workspace_bytes": (_sz, [_i64] * 11),
+    "lg_dwconv1d_nwc_wc": (_int, [_vp, _vp, _vp] + [_i64] * 6 + [_int, _vp]),
+    "lg_dwconv2d_nhwc_hwc": (_int, [_vp, _vp, _vp] + [_i64] * 10 + [_int, _vp]),
+    "lg_reduce_rows": (_int, [_vp, _vp] + [_i64] * 3 + [_int, _vp]),
+    "lg_reduce_cols": (_int, [_vp, _vp] + [_i64] * 3 + [_int, _vp, _sz, _vp]),
+    "lg_reduce_cols_workspace_bytes": (_sz, [_i64] * 2),
+    "lg_transpose": (_int, [_vp, _vp] + [_i64] * 4 + [_vp]),
+    "lg_copy2d": (_int, [_vp, _vp] + [_i64] * 4 + [_vp]),
+}
+
+_lib = None
+
+
+class LgError(RuntimeError):
+    def __init__(self, name, status):
+        self.status = status
+        super().__init__(f"{name} failed: {lg_status_string(status)} ({status})")
+
+
+def lib():
+    """The loaded liblg.so; raises when it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2202_03293_amd.build` "
+                              "(or __graft_entry__.build()) first")
+        L = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def exported_symbols():
+    return sorted(_SIGNATURES)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not (t.is_cuda and t.dtype == torch.float32):
+        raise TypeError("liblg takes float32 tensors in device memory")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise TypeError("workspace must be a contiguous device tensor")
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size()
+
+
+def _ld(t):
+    """Row stride of a 2-D row-major tensor (last stride must be 1)."""
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError("expected a 2-D tensor with unit stride in the last dimension")
+    return t.stride(0) if t.shape[0] > 1 else t.shape[1]
+
+
+def _dense(t):
+    if not t.is_contiguous():
+        raise ValueError("convolution operands must be dense")
+
+
+def _check(name, status):
+    if status != 0:
+        raise LgError(name, status)
+
+
+def lg_version():
+    return lib().lg_version()
+
+
+def lg_status_string(status):
+    return lib().lg_status_string(status).decode()
+
+
+def lg_conv_out_extent(n_in, k, stride, dilation):
+    return lib().lg_conv_out_extent(n_in, k, stride, dilation)
+
+
+def lg_matmul_workspace_bytes(M, N, K):
+    return lib().lg_matmul_workspace_bytes(M, N, K)
+
+
+def lg_matmul(A, B, C, accumulate=False, workspace=None, stream=None):
+    """C[M,N] (+)= A[M,K] @ B[K,N] on the device, in place in C."""
+    M, K = A.shape
+    K2, N = B.shape
+    if K != K2 or tuple(C.shape) != (M, N):
+        raise ValueError("matmul shapes do not agree")
+    wp, wb = _ws(workspace)
+    _check("lg_matmul", lib().lg_matmul(_ptr(A), _ptr(B), _ptr(C), M, N, K, _ld(A), _ld(B), _ld(C),
+                                        int(accumulate), wp, wb, _stream(stream)))
+    return C
+
+
+def lg_conv2d_workspace_bytes(N, H, W, C, KH, KW, F, SH=1, SW=1, DH=1, DW=1):
+    return lib().lg_conv2d_workspace_bytes(N, H, W, C, KH, KW, F, SH, SW, DH, DW)
+
+
+def lg_conv2d_nhwc_hwcf(I, Kf, O, stride=(1, 1), dilation=(1, 1), accumulate=False, workspace=None,
+                        stream=None):
+    """O[N,OH,OW,F] (+)= conv(I[N,H,W,C], Kf[KH,KW,C,F]), no padding."""
+    N, H, W, C = I.shape
+    KH, KW, C2, F = Kf.shape
+    if C != C2:
+        raise ValueError("channel extents do not agree")
+    for t in (I, Kf, O):
+        _dense(t)
+    OH = lg_conv_out_extent(H, KH, stride[0], dilation[0])
+    OW = lg_conv_out_extent(W, KW, stride[1], dilation[1])
+    if tuple(O.shape) != (N, OH, OW, F):
+        raise ValueError(f"output must have shape {(N, OH, OW, F)}")
+    wp, wb = _ws(workspace)
+    _check("lg_conv2d_nhwc_hwcf",
+           lib().lg_conv2d_nhwc_hwcf(_ptr(I), _ptr(Kf), _ptr(O), N, H, W, C, KH, KW, F,
+                                     stride[0], stride[1], dilation[0], dilation[1],
+                                     int(accumulate), wp, wb, _stream(stream)))
+    return O
+
+
+def lg_dwconv1d_nwc_wc(I, Kf, O, stride=1, dilation=1, accumulate=False, stream=None):
+    """O[N,OW,C] (+)= depthwise conv(I[N,W,C], Kf[KW,C])."""
+    N, W, C = I.shape
+    KW, C2 = Kf.shape
+    if C != C2:
+        raise ValueError("channel extents do not agree")
+    for t in (I, Kf, O):
+        _dense(t)
+    OW = lg_conv_out_extent(W, KW, stride, dilation)
+    if tuple(O.shape) != (N, OW, C):
+        raise ValueError(f"output must have shape {(N, OW, C)}")
+    _check("lg_dwconv1d_nwc_wc",
+           lib().lg_dwconv1d_nwc_wc(_ptr(I), _ptr(Kf), _ptr(O), N, W, C, KW, stride, dilation,
+                                    int(accumulate), _stream(stream)))
+    return O
+
+
+def lg_dwconv2d_nhwc_hwc(I, Kf, O, stride=(1, 1), dilation=(1, 1), accumulate=False, stream=None):
+    """O[N,OH,OW,C] (+)= depthwise conv(I[N,H,W,C], Kf[KH,KW,C])."""
+    N, H, W, C = I.shape
+    KH, KW, C2 = Kf.shape
+    if C != C2:
+        raise ValueError("channel extents do not agree")
+    for t in (I, Kf, O):
+        _dense(t)
+    OH = lg_conv_out_extent(H, KH, stride[0], dilation[0])
+    OW = lg_conv_out_extent(W, KW, stride[1], dilation[1])
+    if tuple(O.shape) != (N, OH, OW, C):
+        raise ValueError(f"output must have shape {(N, OH, OW, C)}")
+    _check("lg_dwconv2d_nhwc_hwc",
+           lib().lg_dwconv2d_nhwc_hwc(_ptr(I), _ptr(Kf), _ptr(O), N, H, W, C, KH, KW,
+                                      stride[0], stride[1], dilation[0], dilation[1],
+                                      int(accumulate), _stream(stream)))
+    return O
+
+
+def lg_reduce_rows(x, out, accumulate=False, stream=None):
+    """out[R] (+)= sum over the last dimension of x[R,Cn]."""
+    R, Cn = x.shape
+    if tuple(out.shape) != (R,) or not out.is_contiguous():
+        raise ValueError("out must be a dense vector with one entry per row")
+    _check("lg_reduce_rows", lib().lg_reduce_rows(_ptr(x), _ptr(out), R, Cn, _ld(x), int(accumulate),
+                                                  _stream(stream)))
+    return out
+
+
+def lg_reduce_cols_workspace_bytes(R, Cn):
+    return lib().lg_reduce_cols_workspace_bytes(R, Cn)
+
+
+def lg_reduce_cols(x, out, accumulate=False, workspace=None, stream=None):
+    """out[Cn] (+)= sum over the first dimension of x[R,Cn]."""
+    R, Cn = x.shape
+    if tuple(out.shape) != (Cn,) or not out.is_contiguous():
+        raise ValueError("out must be a dense vector with one entry per column")
+    wp, wb = _ws(workspace)
+    _check("lg_reduce_cols", lib().lg_reduce_cols(_ptr(x), _ptr(out), R, Cn, _ld(x), int(accumulate),
+                                                  wp, wb, _stream(stream)))
+    return out
+
+
+def lg_transpose(x, out, stream=None):
+    """out[Cn,R] = x[R,Cn] transposed, bit for bit."""
+    R, Cn = x.shape
+    if tuple(out.shape) != (Cn, R):
+        raise ValueError("out must have the transposed shape")
+    _check("lg_transpose", lib().lg_transpose(_ptr(x), _ptr(out), R, Cn, _ld(x), _ld(out), _stream(stream)))
+    return out
+
+
+def lg_copy2d(x, out, stream=None):
+    """out[R,Cn] = x[R,Cn], bit for bit."""
+    R, Cn = x.shape
+    if tuple(out.shape) != (R, Cn):
+        raise ValueError("out must have the same shape")
+    _check("lg_copy2d", lib().lg_copy2d(_ptr(x), _ptr(out), R, Cn, _ld(x), _ld(out), _stream(stream)))
+    return out

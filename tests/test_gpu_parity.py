@@ -1,0 +1,401 @@
+"""GPU parity: every liblg entry point against the CPU oracle on identical seeded inputs.
+
+fp32 ops: max |err| <= 1e-4*sqrt(K) (K = reduction length of one output element) and relative
+Frobenius error <= 1e-5.  Transpose / copy: bit-exact.  All calls go through the C ABI via the
+thin ctypes binding; outputs sit between canary guard bands.
+"""
+import numpy as np
+import pytest
+import torch
+
+import seeded_inputs as si
+from gpu_util import Guarded, assert_close, bits, dev, workspace
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lg():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2202_03293_amd as lg_
+    lg_.lib()
+    return lg_
+
+
+def sync():
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------------------- matmul
+
+def run_matmul(lg, A, B, C0=None, accumulate=False):
+    M, K = A.shape
+    N = B.shape[1]
+    out = Guarded((M, N), init=C0 if C0 is not None else np.full((M, N), np.nan, np.float32))
+    ws = workspace(lg.lg_matmul_workspace_bytes(M, N, K))
+    lg.lg_matmul(dev(A), dev(B), out.t, accumulate=accumulate, workspace=ws)
+    sync()
+    out.check()
+    return out.host()
+
+
+MATMUL_SHAPES = [
+    (256, 256, 256),        # benchmark config 0
+    (1, 1, 1), (3, 5, 7), (64, 64, 16), (65, 63, 17), (100, 36, 52),
+    (128, 128, 128), (257, 255, 129), (300, 520, 40), (512, 768, 64),
+    (1000, 24, 2000),       # split-k, ragged everywhere
+    (2048, 2048, 96), (4100, 4104, 36),   # big tile with ragged edges
+    (33, 4096, 8),
+]
+
+
+@pytest.mark.parametrize("M,N,K", MATMUL_SHAPES)
+def test_matmul_matches_oracle(lg, lgo, M, N, K):
+    A, B = si.matmul_inputs(0 if (M, N, K) == (256, 256, 256) else 100 + M % 7, M, N, K)
+    C = run_matmul(lg, A, B)
+    assert_close(C, lgo.matmul(A, B), K, f"matmul {M}x{N}x{K}")
+
+
+@pytest.mark.parametrize("M,N,K", [(129, 67, 45), (256, 256, 64), (520, 516, 132)])
+def test_matmul_accumulate(lg, lgo, M, N, K):
+    A, B = si.matmul_inputs(111, M, N, K)
+    C0 = si.uniform(111, 7, (M, N), -1, 1)
+    C = run_matmul(lg, A, B, C0=C0, accumulate=True)
+    ref = C0.copy()
+    lgo.matmul(A, B, ref, accumulate=True)
+    assert_close(C, ref, K, "matmul accumulate")
+
+
+def test_matmul_exact_cases(lg, lgo):
+    # integer-valued operands: every product and partial sum is exact in fp32, any order
+    A = si.small_integers(112, 0, (200, 96))
+    B = si.small_integers(112, 1, (96, 136))
+    assert np.array_equal(run_matmul(lg, A, B), lgo.matmul(A, B))
+    # identity and permutation: one non-zero term per sum -> bit-exact
+    X = si.uniform(113, 0, (192, 192), -1, 1)
+    eye = np.eye(192, dtype=np.float32)
+    assert np.array_equal(bits(run_matmul(lg, X, eye)), bits(X))
+    assert np.array_equal(bits(run_matmul(lg, eye, X)), bits(X))
+    perm = np.random.default_rng(3).permutation(192)
+    assert np.array_equal(bits(run_matmul(lg, eye[perm], X)), bits(X[perm]))
+    # the paper's all-ones example: every entry equals K
+    assert np.all(run_matmul(lg, np.ones((70, 300), np.float32), np.ones((300, 50), np.float32)) == 300)
+
+
+def test_matmul_leading_dimensions(lg, lgo):
+    M, N, K = 150, 200, 72
+    A, B = si.matmul_inputs(114, M, N, K)
+    ref = lgo.matmul(A, B)
+    for pa, pb, pc in [(8, 4, 12), (3, 5, 1)]:      # aligned (vector path) and odd (scalar path)
+        Ad = torch.full((M, K + pa), float("nan"), device="cuda"); Ad[:, :K] = dev(A)
+        Bd = torch.full((K, N + pb), float("nan"), device="cuda"); Bd[:, :N] = dev(B)
+        Cd = torch.full((M, N + pc), 7.0, device="cuda")
+        lg.lg_matmul(Ad[:, :K], Bd[:, :N], Cd[:, :N], workspace=workspace(lg.lg_matmul_workspace_bytes(M, N, K)))
+        sync()
+        Ch = Cd.cpu().numpy()
+        assert_close(Ch[:, :N], ref, K, "matmul ld")
+        assert np.all(Ch[:, N:] == 7.0)
+
+
+def test_matmul_zero_extents(lg):
+    C = Guarded((5, 6), init=np.full((5, 6), 3.0, np.float32))
+    lg.lg_matmul(torch.empty((5, 0), device="cuda"), torch.empty((0, 6), device="cuda"), C.t)
+    sync(); C.check()
+    assert np.all(C.host() == 0)
+    C = Guarded((5, 6), init=np.full((5, 6), 3.0, np.float32))
+    lg.lg_matmul(torch.empty((5, 0), device="cuda"), torch.empty((0, 6), device="cuda"), C.t, accumulate=True)
+    sync(); C.check()
+    assert np.all(C.host() == 3.0)
+    lg.lg_matmul(torch.empty((0, 4), device="cuda"), torch.empty((4, 6), device="cuda"), torch.empty((0, 6), device="cuda"))
+
+
+def test_matmul_is_deterministic(lg):
+    A, B = si.matmul_inputs(115, 384, 640, 1000)
+    c1 = run_matmul(lg, A, B)
+    c2 = run_matmul(lg, A, B)
+    assert np.array_equal(bits(c1), bits(c2))
+
+
+def test_matmul_workspace_errors(lg):
+    M, N, K = 256, 256, 4096
+    need = lg.lg_matmul_workspace_bytes(M, N, K)
+    if need == 0:
+        pytest.skip("this shape is not split")
+    A = torch.zeros((M, K), device="cuda"); B = torch.zeros((K, N), device="cuda"); C = torch.zeros((M, N), device="cuda")
+    with pytest.raises(lg.LgError) as e:
+        lg.lg_matmul(A, B, C)
+    assert e.value.status == -3
+    with pytest.raises(lg.LgError):
+        lg.lg_matmul(A, B, C, workspace=workspace(need - 4))
+
+
+@pytest.mark.parametrize("case,shape", list(enumerate(si.MATMUL_SWEEP)))
+def test_matmul_full_size_sampled(lg, lgo, case, shape):
+    """Benchmark sweep shapes, in the launch configuration the benchmark times.  The oracle checks
+    row blocks that straddle tile boundaries (all N columns) element by element."""
+    M, N, K = shape
+    A, B = si.matmul_inputs(2, M, N, K, case=case)
+    Cd = torch.full((M, N), float("nan"), device="cuda")
+    ws = workspace(lg.lg_matmul_workspace_bytes(M, N, K))
+    lg.lg_matmul(dev(A), dev(B), Cd, workspace=ws)
+    sync()
+    starts = sorted({0, 252, M // 2 - 4, M - 8} if M >= 512 else {0})
+    for r0 in starts:
+        rows = slice(r0, min(M, r0 + 8))
+        ref = lgo.matmul(np.ascontiguousarray(A[rows]), B)
+        assert_close(Cd[rows].cpu().numpy(), ref, K, f"matmul {shape} rows {r0}")
+    # every element is finite and the column blocks are consistent with a column-sampled oracle
+    cols = np.arange(0, N, max(1, N // 16))[:16]
+    ref = lgo.matmul(A, np.ascontiguousarray(B[:, cols])) if M * len(cols) * K <= 3e9 else None
+    if ref is not None:
+        assert_close(Cd[:, torch.from_numpy(cols).cuda()].cpu().numpy(), ref, K, f"matmul {shape} cols")
+    assert bool(torch.isfinite(Cd).all())
+
+
+# ------------------------------------------------------------------------------- conv2d
+
+def run_conv(lg, I, Kf, stride=(1, 1), dilation=(1, 1), O0=None, accumulate=False):
+    N, H, W, C = I.shape
+    KH, KW, _, F = Kf.shape
+    OH = lg.lg_conv_out_extent(H, KH, stride[0], dilation[0])
+    OW = lg.lg_conv_out_extent(W, KW, stride[1], dilation[1])
+    out = Guarded((N, OH, OW, F), init=O0 if O0 is not None else np.full((N, OH, OW, F), np.nan, np.float32))
+    ws = workspace(lg.lg_conv2d_workspace_bytes(N, H, W, C, KH, KW, F, *stride, *dilation))
+    lg.lg_conv2d_nhwc_hwcf(dev(I), dev(Kf), out.t, stride=stride, dilation=dilation,
+                           accumulate=accumulate, workspace=ws)
+    sync()
+    out.check()
+    return out.host()
+
+
+CONV_SMALL = [
+    # N, H, W, C, F, KH, KW, stride, dilation
+    (2, 12, 14, 8, 16, 3, 3, (1, 1), (1, 1)),
+    (1, 9, 9, 3, 5, 3, 2, (1, 1), (1, 1)),          # C, F not multiples of 4 -> scalar path
+    (2, 20, 17, 12, 20, 2, 3, (2, 1), (1, 2)),
+    (3, 15, 15, 4, 8, 3, 3, (1, 3), (2, 1)),
+    (1, 30, 30, 20, 72, 1, 1, (2, 2), (1, 1)),
+    (2, 1, 40, 8, 12, 1, 5, (1, 2), (1, 3)),        # 1-D convolution as H = KH = 1
+    (4, 18, 18, 32, 64, 3, 3, (1, 1), (1, 1)),      # the paper's channel/filter counts (C, F) = (32, 64)
+    (1, 40, 40, 16, 136, 3, 3, (1, 1), (1, 1)),
+]
+
+
+@pytest.mark.parametrize("case", CONV_SMALL)
+def test_conv2d_matches_oracle(lg, lgo, case):
+    N, H, W, C, F, KH, KW, st, dl = case
+    I, Kf = si.conv2d_inputs(120, N, H, W, C, F, KH, KW)
+    O = run_conv(lg, I, Kf, st, dl)
+    assert_close(O, lgo.conv2d_nhwc_hwcf(I, Kf, stride=st, dilation=dl), KH * KW * C, f"conv {case}")
+
+
+def test_conv2d_accumulate_and_exact(lg, lgo):
+    N, H, W, C, F, KH, KW = 2, 10, 11, 8, 12, 3, 3
+    I, Kf = si.conv2d_inputs(121, N, H, W, C, F, KH, KW)
+    O0 = si.uniform(121, 9, (N, H - 2, W - 2, F), -1, 1)
+    O = run_conv(lg, I, Kf, O0=O0, accumulate=True)
+    ref = O0.copy()
+    lgo.conv2d_nhwc_hwcf(I, Kf, ref, accumulate=True)
+    assert_close(O, ref, KH * KW * C, "conv accumulate")
+    Ii = si.small_integers(122, 0, (2, 9, 9, 8))
+    Ki = si.small_integers(122, 1, (3, 3, 8, 8))
+    assert np.array_equal(run_conv(lg, Ii, Ki, (2, 1), (1, 2)), lgo.conv2d_nhwc_hwcf(Ii, Ki, stride=(2, 1), dilation=(1, 2)))
+    # delta filter: the output is a strided crop of the input, bit for bit
+    Kd = np.zeros((3, 3, 8, 8), np.float32)
+    Kd[2, 1] = np.eye(8, dtype=np.float32)
+    X = si.uniform(123, 0, (1, 12, 12, 8), -1, 1)
+    assert np.array_equal(bits(run_conv(lg, X, Kd)), bits(X[:, 2:12, 1:11, :]))
+
+
+@pytest.mark.parametrize("case,shape", list(enumerate(si.CONV2D_SHAPES)))
+def test_conv2d_full_size(lg, lgo, case, shape):
+    N, H, W, C, F, KH, KW, s = shape
+    I, Kf = si.conv2d_inputs(3, N, H, W, C, F, KH, KW, case=case)
+    O = run_conv(lg, I, Kf, (s, s))
+    # the oracle covers the first and last image completely (each ~0.25 GFLOP)
+    for n in (0, N - 1):
+        ref = lgo.conv2d_nhwc_hwcf(np.ascontiguousarray(I[n:n + 1]), Kf, stride=(s, s))
+        assert_close(O[n:n + 1], ref, KH * KW * C, f"conv {shape} image {n}")
+    assert np.all(np.isfinite(O))
+
+
+# ------------------------------------------------------------------------------- depthwise
+
+def run_dw1(lg, I, Kf, s=1, d=1, O0=None, accumulate=False):
+    N, W, C = I.shape
+    OW = lg.lg_conv_out_extent(W, Kf.shape[0], s, d)
+    out = Guarded((N, OW, C), init=O0 if O0 is not None else np.full((N, OW, C), np.nan, np.float32))
+    lg.lg_dwconv1d_nwc_wc(dev(I), dev(Kf), out.t, stride=s, dilation=d, accumulate=accumulate)
+    sync(); out.check()
+    return out.host()
+
+
+def run_dw2(lg, I, Kf, st=(1, 1), dl=(1, 1), O0=None, accumulate=False):
+    N, H, W, C = I.shape
+    OH = lg.lg_conv_out_extent(H, Kf.shape[0], st[0], dl[0])
+    OW = lg.lg_conv_out_extent(W, Kf.shape[1], st[1], dl[1])
+    out = Guarded((N, OH, OW, C), init=O0 if O0 is not None else np.full((N, OH, OW, C), np.nan, np.float32))
+    lg.lg_dwconv2d_nhwc_hwc(dev(I), dev(Kf), out.t, stride=st, dilation=dl, accumulate=accumulate)
+    sync(); out.check()
+    return out.host()
+
+
+@pytest.mark.parametrize("N,W,C,KW,s,d", [
+    (1, 40, 32, 3, 1, 1),          # the paper's (N, C, K_w) = (1, 32, 3)
+    (3, 100, 64, 3, 1, 1), (2, 19, 8, 3, 1, 1), (2, 3, 4, 3, 1, 1),
+    (2, 50, 12, 3, 2, 1), (2, 50, 12, 3, 1, 2), (1, 64, 20, 5, 2, 2),
+    (2, 33, 7, 3, 1, 1), (1, 17, 1, 2, 1, 1), (4, 1000, 512, 3, 1, 1),
+])
+def test_dwconv1d_matches_oracle(lg, lgo, N, W, C, KW, s, d):
+    I, Kf = si.dwconv1d_inputs(130, N, W, C, KW)
+    assert_close(run_dw1(lg, I, Kf, s, d), lgo.dwconv1d_nwc_wc(I, Kf, stride=s, dilation=d), KW, "dwconv1d")
+
+
+@pytest.mark.parametrize("N,H,W,C,KH,KW,st,dl", [
+    (1, 20, 20, 32, 3, 3, (1, 1), (1, 1)),      # the paper's (N, C, K_h, K_w) = (1, 32, 3, 3)
+    (2, 11, 13, 8, 3, 3, (1, 1), (1, 1)), (1, 3, 3, 4, 3, 3, (1, 1), (1, 1)),
+    (2, 35, 37, 96, 3, 3, (1, 1), (1, 1)), (2, 14, 15, 12, 3, 3, (2, 1), (1, 2)),
+    (1, 16, 16, 6, 2, 4, (1, 2), (2, 1)), (2, 10, 9, 5, 3, 3, (1, 1), (1, 1)),
+    (2, 1, 30, 8, 1, 3, (1, 1), (1, 1)),
+])
+def test_dwconv2d_matches_oracle(lg, lgo, N, H, W, C, KH, KW, st, dl):
+    I, Kf = si.dwconv2d_inputs(131, N, H, W, C, KH, KW)
+    assert_close(run_dw2(lg, I, Kf, st, dl), lgo.dwconv2d_nhwc_hwc(I, Kf, stride=st, dilation=dl), KH * KW, "dwconv2d")
+
+
+def test_dwconv_accumulate_and_delta(lg, lgo):
+    I, Kf = si.dwconv1d_inputs(132, 2, 50, 16, 3)
+    O0 = si.uniform(132, 9, (2, 48, 16), -1, 1)
+    ref = O0.copy(); lgo.dwconv1d_nwc_wc(I, Kf, ref, accumulate=True)
+    assert_close(run_dw1(lg, I, Kf, O0=O0, accumulate=True), ref, 3, "dwconv1d accumulate")
+    I2, K2 = si.dwconv2d_inputs(133, 2, 12, 12, 8, 3, 3)
+    O0 = si.uniform(133, 9, (2, 10, 10, 8), -1, 1)
+    ref = O0.copy(); lgo.dwconv2d_nhwc_hwc(I2, K2, ref, accumulate=True)
+    assert_close(run_dw2(lg, I2, K2, O0=O0, accumulate=True), ref, 9, "dwconv2d accumulate")
+    Kd = np.zeros((3, 3, 8), np.float32); Kd[1, 2] = 1
+    assert np.array_equal(bits(run_dw2(lg, I2, Kd)), bits(I2[:, 1:11, 2:12, :]))
+    K1 = np.zeros((3, 16), np.float32); K1[2] = 1
+    assert np.array_equal(bits(run_dw1(lg, I, K1)), bits(I[:, 2:50]))
+
+
+def test_dwconv_full_size(lg, lgo):
+    N, W, C, KW = si.DWCONV1D_SHAPE
+    I, Kf = si.dwconv1d_inputs(4, N, W, C, KW)
+    O = run_dw1(lg, I, Kf)
+    for n in (0, N // 2, N - 1):
+        assert_close(O[n:n + 1], lgo.dwconv1d_nwc_wc(np.ascontiguousarray(I[n:n + 1]), Kf), KW, "dwconv1d full")
+    assert np.all(np.isfinite(O))
+    N, H, W, C, KH, KW = si.DWCONV2D_SHAPE
+    I, Kf = si.dwconv2d_inputs(4, N, H, W, C, KH, KW)
+    O = run_dw2(lg, I, Kf)
+    assert_close(O, lgo.dwconv2d_nhwc_hwc(I, Kf), KH * KW, "dwconv2d full")
+
+
+# ------------------------------------------------------------------------------- reductions
+
+def run_rows(lg, x, out0=None, accumulate=False):
+    out = Guarded((x.shape[0],), init=out0 if out0 is not None else np.full(x.shape[0], np.nan, np.float32))
+    lg.lg_reduce_rows(dev(x), out.t, accumulate=accumulate)
+    sync(); out.check()
+    return out.host()
+
+
+def run_cols(lg, x, out0=None, accumulate=False):
+    out = Guarded((x.shape[1],), init=out0 if out0 is not None else np.full(x.shape[1], np.nan, np.float32))
+    ws = workspace(lg.lg_reduce_cols_workspace_bytes(*x.shape))
+    lg.lg_reduce_cols(dev(x), out.t, accumulate=accumulate, workspace=ws)
+    sync(); out.check()
+    return out.host()
+
+
+RED_SHAPES = [(250, 960), (1, 1), (7, 5), (64, 4096), (100, 4100), (33, 8191), (513, 64),
+              (1000, 3), (5, 20000), (300, 1024), (4096, 8), (129, 260)]
+
+
+@pytest.mark.parametrize("R,Cn", RED_SHAPES)
+def test_reductions_match_oracle(lg, lgo, R, Cn):
+    x = si.uniform(1, 5, (R, Cn), 0, 1)
+    assert_close(run_rows(lg, x), lgo.reduce_rows(x), Cn, f"reduce_rows {R}x{Cn}")
+    assert_close(run_cols(lg, x), lgo.reduce_cols(x), R, f"reduce_cols {R}x{Cn}")
+
+
+def test_reductions_all_ones_accumulate_ld_and_empty(lg, lgo):
+    ones = np.ones((300, 4096), np.float32)
+    assert np.all(run_rows(lg, ones) == 4096) and np.all(run_cols(lg, ones) == 300)
+    x = si.uniform(1, 6, (260, 520), 0, 1)
+    r0 = si.uniform(1, 7, (260,), -1, 1); c0 = si.uniform(1, 8, (520,), -1, 1)
+    rr = r0.copy(); lgo.reduce_rows(x, rr, accumulate=True)
+    cc = c0.copy(); lgo.reduce_cols(x, cc, accumulate=True)
+    assert_close(run_rows(lg, x, r0, True), rr, 520, "rows accumulate")
+    assert_close(run_cols(lg, x, c0, True), cc, 260, "cols accumulate")
+    for pad in (4, 3):
+        xd = torch.full((260, 520 + pad), float("nan"), device="cuda"); xd[:, :520] = dev(x)
+        o = torch.empty(260, device="cuda"); lg.lg_reduce_rows(xd[:, :520], o)
+        oc = torch.empty(520, device="cuda")
+        lg.lg_reduce_cols(xd[:, :520], oc, workspace=workspace(lg.lg_reduce_cols_workspace_bytes(260, 520)))
+        sync()
+        assert_close(o.cpu().numpy(), lgo.reduce_rows(x), 520, "rows ld")
+        assert_close(oc.cpu().numpy(), lgo.reduce_cols(x), 260, "cols ld")
+    e = torch.full((4,), 5.0, device="cuda")
+    lg.lg_reduce_rows(torch.empty((4, 0), device="cuda"), e); sync()
+    assert np.all(e.cpu().numpy() == 0)
+    e = torch.full((4,), 5.0, device="cuda")
+    lg.lg_reduce_cols(torch.empty((0, 4), device="cuda"), e); sync()
+    assert np.all(e.cpu().numpy() == 0)
+
+
+def test_reductions_full_size(lg, lgo):
+    x = si.uniform(1, 0, si.REDUCE_SHAPE, 0, 1)
+    assert_close(run_rows(lg, x), lgo.reduce_rows(x), x.shape[1], "reduce_rows full")
+    assert_close(run_cols(lg, x), lgo.reduce_cols(x), x.shape[0], "reduce_cols full")
+
+
+# ------------------------------------------------------------------------------- transpose / copy
+
+def special_bits(shape, seed):
+    n = int(np.prod(shape))
+    b = (si.bits24(seed, 0, n) << np.uint32(8)) | (si.bits24(seed, 1, n) & np.uint32(0xFF))
+    sp = np.array([0x80000000, 0x7F800000, 0xFF800000, 0x7FC00001, 0xFFC12345, 0x7F800001,
+                   0x00000001, 0x807FFFFF, 0x00800000], np.uint32)
+    k = min(len(sp), len(b[::2]))
+    b[::2][:k] = sp[:k]
+    return b.reshape(shape)
+
+
+@pytest.mark.parametrize("R,Cn", [(64, 64), (1, 1), (1, 19), (19, 1), (37, 53), (128, 256), (100, 260),
+                                  (250, 960), (1000, 1000), (1027, 765), (4, 4096), (4096, 4)])
+def test_transpose_and_copy_bit_exact(lg, lgo, R, Cn):
+    xb = special_bits((R, Cn), 140)
+    x = xb.view(np.float32)
+    out = Guarded((Cn, R))
+    lg.lg_transpose(dev(x), out.t); sync(); out.check()
+    assert np.array_equal(bits(out.host()), bits(lgo.transpose(x)))
+    back = Guarded((R, Cn))
+    lg.lg_transpose(out.t, back.t); sync(); back.check()
+    assert np.array_equal(bits(back.host()), xb)                 # transpose twice = identity
+    cp = Guarded((R, Cn))
+    lg.lg_copy2d(dev(x), cp.t); sync(); cp.check()
+    assert np.array_equal(bits(cp.host()), bits(lgo.copy2d(x)))
+
+
+def test_transpose_copy_leading_dims(lg, lgo):
+    R, Cn = 130, 200
+    xb = special_bits((R, Cn), 141)
+    for pi, po in [(8, 4), (3, 5)]:
+        xd = torch.zeros((R, Cn + pi), dtype=torch.int32, device="cuda").view(torch.float32)
+        xd[:, :Cn] = dev(xb.view(np.float32))
+        od = torch.full((Cn, R + po), 0x5EADBEEF, dtype=torch.int32, device="cuda").view(torch.float32)
+        lg.lg_transpose(xd[:, :Cn], od[:, :R]); sync()
+        oh = od.view(torch.int32).cpu().numpy().view(np.uint32)
+        assert np.array_equal(oh[:, :R], xb.T) and np.all(oh[:, R:] == 0x5EADBEEF)
+        cd = torch.full((R, Cn + po), 0x5EADBEEF, dtype=torch.int32, device="cuda").view(torch.float32)
+        lg.lg_copy2d(xd[:, :Cn], cd[:, :Cn]); sync()
+        ch = cd.view(torch.int32).cpu().numpy().view(np.uint32)
+        assert np.array_equal(ch[:, :Cn], xb) and np.all(ch[:, Cn:] == 0x5EADBEEF)
+
+
+def test_transpose_full_size(lg, lgo):
+    x = si.uniform(1, 1, si.TRANSPOSE_SHAPE, 0, 1)
+    od = torch.empty((x.shape[1], x.shape[0]), device="cuda")
+    lg.lg_transpose(dev(x), od); sync()
+    assert np.array_equal(bits(od.cpu().numpy()), bits(lgo.transpose(x)))
