@@ -1,0 +1,234 @@
+#!/usr/bin/env python3
+"""Benchmark of liblg on one MI355X.
+
+One "step" is one pass of the whole hot path: every op of the library at every shape of the
+benchmark configurations 1..4 (memory-bound ops, matmul sweep, conv2d, depthwise conv) on
+seeded synthetic inputs already resident in HBM.  Ops are ordered so that each memory-bound
+launch finds its operands cold (several hundred MiB of other traffic since they were last
+touched, more than the 256 MiB Infinity Cache).
+
+Prints ONE JSON line.  `value` is the contraction throughput of the whole step (matmul + conv
+FLOPs divided by the full step time, memory-bound ops included in the time); per-op figures
+against their own rooflines are under `ops`; `roofline` describes the dominant kernel (the
+256x256 MFMA GEMM tile) and `cpu_baseline` the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_FP32_PEAK = 157.3e12      # 256 CU x 4 SIMD x 64 FLOP/clk x 2.4 GHz
+HBM_PEAK = 8.0e12              # bytes/s
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives are part of it); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2202_03293_amd as lg
+    import seeded_inputs as si
+
+    lg.lib()                                  # fail loudly when the HIP library is not built
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+
+    def dev(a):
+        return torch.from_numpy(a).cuda()
+
+    def ws(nbytes):
+        return torch.empty(nbytes // 4, device="cuda") if nbytes else None
+
+    # ------------------------------------------------------------------ build the op list
+    ops = []      # dicts: name, call, flops, bytes, bound, kernel
+
+    def add(name, call, flops, nbytes, bound, kernel):
+        ops.append(dict(name=name, call=call, flops=float(flops), bytes=float(nbytes), bound=bound,
+                        kernel=kernel))
+
+    def gemm_kernel_name(M, N, K):
+        bm, bn, sp = lg.lg_matmul_plan(M, N, K)
+        return f"gemm_{bm}x{bn}" + (f"_splitk{sp}" if sp > 1 else "")
+
+    host_keep = {}
+    mm = {}
+    for case, (M, N, K) in enumerate(si.MATMUL_SWEEP):
+        A, B = si.matmul_inputs(2, M, N, K, case=case)
+        if (M, N, K) == (8192, 8192, 8192):
+            host_keep["mm8192"] = (A[:128].copy(), B)
+        Ad, Bd = dev(A), dev(B)
+        Cd = torch.zeros((M, N), device="cuda")
+        w = ws(lg.lg_matmul_workspace_bytes(M, N, K))
+        mm[(M, N, K)] = dict(name=f"matmul_{M}x{N}x{K}",
+                             call=(lambda Ad=Ad, Bd=Bd, Cd=Cd, w=w: lg.lg_matmul(Ad, Bd, Cd, workspace=w)),
+                             flops=2.0 * M * N * K, nbytes=4.0 * (M * K + K * N + M * N),
+                             kernel=gemm_kernel_name(M, N, K))
+        del A, B
+
+    # the row and the column reduction get their own tensor of the configured shape, so the second
+    # one cannot be served from what the first left in the 256 MiB Infinity Cache
+    R, Cn = si.REDUCE_SHAPE
+    x_rows = dev(si.uniform(1, 0, si.REDUCE_SHAPE, 0, 1))
+    x_cols = dev(si.uniform(1, 2, si.REDUCE_SHAPE, 0, 1))
+    out_rows = torch.empty(R, device="cuda")
+    out_cols = torch.empty(Cn, device="cuda")
+    ws_cols = ws(lg.lg_reduce_cols_workspace_bytes(R, Cn))
+    x_tr = dev(si.uniform(1, 1, si.TRANSPOSE_SHAPE, 0, 1))
+    y_tr = torch.empty((si.TRANSPOSE_SHAPE[1], si.TRANSPOSE_SHAPE[0]), device="cuda")
+    x_cp = dev(si.uniform(1, 3, si.TRANSPOSE_SHAPE, 0, 1))
+    y_cp = torch.empty_like(x_cp)
+
+    n1, w1, c1, k1 = si.DWCONV1D_SHAPE
+    I1h, K1h = si.dwconv1d_inputs(4, n1, w1, c1, k1)
+    I1, K1 = dev(I1h), dev(K1h)
+    O1 = torch.empty((n1, w1 - k1 + 1, c1), device="cuda")
+    del I1h
+    n2, h2, w2, c2, kh2, kw2 = si.DWCONV2D_SHAPE
+    I2h, K2h = si.dwconv2d_inputs(4, n2, h2, w2, c2, kh2, kw2)
+    I2, K2 = dev(I2h), dev(K2h)
+    O2 = torch.empty((n2, h2 - kh2 + 1, w2 - kw2 + 1, c2), device="cuda")
+
+    convs = []
+    for case, (N, H, W, C, F, KH, KW, s) in enumerate(si.CONV2D_SHAPES):
+        Ih, Kh = si.conv2d_inputs(3, N, H, W, C, F, KH, KW, case=case)
+        Id, Kd = dev(Ih), dev(Kh)
+        OH, OW = (H - KH) // s + 1, (W - KW) // s + 1
+        Od = torch.empty((N, OH, OW, F), device="cuda")
+        w = ws(lg.lg_conv2d_workspace_bytes(N, H, W, C, KH, KW, F, s, s, 1, 1))
+        # input elements that take part in at least one output (a 1x1 stride-2 filter skips 3/4)
+        touched_in = N * OH * OW * C if (KH == 1 and KW == 1) else N * H * W * C
+        convs.append(dict(name=f"conv2d_n{N}h{H}c{C}f{F}k{KH}s{s}",
+                          call=(lambda Id=Id, Kd=Kd, Od=Od, w=w, s=s:
+                                lg.lg_conv2d_nhwc_hwcf(Id, Kd, Od, stride=(s, s), workspace=w)),
+                          flops=2.0 * N * OH * OW * F * KH * KW * C,
+                          nbytes=4.0 * (touched_in + KH * KW * C * F + N * OH * OW * F),
+                          kernel="conv_" + gemm_kernel_name(N * OH * OW, F, KH * KW * C)))
+
+    def add_mm(shape):
+        d = mm[shape]
+        add(d["name"], d["call"], d["flops"], d["nbytes"], "mfma", d["kernel"])
+
+    # Order.  Writes of one kernel linger dirty in the Infinity Cache and are paid for by the next
+    # kernel, so (a) the write-heavy memory-bound ops run as one chain, each preceded by another
+    # write-heavy op as in a steady state (copy2d, the bandwidth yardstick, heads the chain and is the
+    # only one that starts from clean caches), (b) a compute-bound GEMM follows the chain and absorbs
+    # its write-back, (c) the read-only reductions follow GEMMs with small outputs.  Every operand was
+    # last touched > 1 GiB of traffic ago, i.e. it is cold in L2 and in the Infinity Cache.
+    add("copy2d_8192x8192", lambda: lg.lg_copy2d(x_cp, y_cp), 0, 8.0 * x_cp.numel(), "hbm", "copy2d")
+    add("transpose_8192x8192", lambda: lg.lg_transpose(x_tr, y_tr), 0, 8.0 * x_tr.numel(), "hbm", "transpose")
+    # depthwise bytes follow the paper's accounting: output written, filter read, input read once
+    add("dwconv1d_n32w4098c512k3", lambda: lg.lg_dwconv1d_nwc_wc(I1, K1, O1), 2.0 * O1.numel() * k1,
+        4.0 * (O1.numel() + K1.numel() + I1.numel()), "hbm", "dwconv1d")
+    add("dwconv2d_n8h114c96k3", lambda: lg.lg_dwconv2d_nhwc_hwc(I2, K2, O2), 2.0 * O2.numel() * kh2 * kw2,
+        4.0 * (O2.numel() + K2.numel() + I2.numel()), "hbm", "dwconv2d")
+    add_mm((4096, 4096, 4096))
+    add_mm((16384, 512, 2048))
+    for c in convs:
+        add(c["name"], c["call"], c["flops"], c["nbytes"], "mfma", c["kernel"])
+    add("reduce_rows_4096x16384", lambda: lg.lg_reduce_rows(x_rows, out_rows), R * Cn, 4.0 * (R * Cn + R), "hbm",
+        "reduce_rows")
+    add("reduce_cols_4096x16384", lambda: lg.lg_reduce_cols(x_cols, out_cols, workspace=ws_cols), R * Cn,
+        4.0 * (R * Cn + Cn), "hbm", "reduce_cols")
+    add_mm((8192, 8192, 8192))
+    add_mm((1024, 1024, 1024))
+    add_mm((4096, 4096, 64))
+
+    # ------------------------------------------------------------------ run
+    def step(events=None):
+        for i, op in enumerate(ops):
+            if events is not None:
+                events[i][0].record(stream)
+            op["call"]()
+            if events is not None:
+                events[i][1].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    all_events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                   for _ in ops] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(all_events[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    per_op = []
+    for i, op in enumerate(ops):
+        ts = np.array([a.elapsed_time(b) for a, b in (ev[i] for ev in all_events)]) * 1e-3
+        mean, med = float(ts.mean()), float(np.median(ts))
+        rec = dict(op=op["name"], kernel=op["kernel"], bound=op["bound"], us_mean=mean * 1e6, us_median=med * 1e6,
+                   us_p25=float(np.percentile(ts, 25)) * 1e6, us_p75=float(np.percentile(ts, 75)) * 1e6)
+        if op["bound"] == "mfma":
+            rec.update(gflops=op["flops"] / mean / 1e9, frac_mfma_peak=op["flops"] / mean / MFMA_FP32_PEAK)
+        else:
+            rec.update(gbps=op["bytes"] / mean / 1e9, frac_hbm_peak=op["bytes"] / mean / HBM_PEAK)
+        op["mean_s"] = mean
+        per_op.append(rec)
+
+    contraction_flops = sum(op["flops"] for op in ops if op["bound"] == "mfma")
+    value = contraction_flops / (ms_per_step * 1e-3) / 1e9
+
+    # dominant kernel: the 256x256 GEMM tile (all launches that share that kernel, like a
+    # kernel-trace summary groups them)
+    dom = [op for op in ops if op["kernel"] == "gemm_256x256"]
+    dom_flops = sum(op["flops"] for op in dom) / max(len(dom), 1)
+    dom_dur = sum(op["mean_s"] for op in dom) / max(len(dom), 1)
+    roofline = dict(bound="mfma", kernel="gemm_kernel<Tile<256,256,64,128>,vec,matmul>",
+                    launches_per_step=len(dom), flops_per_launch=dom_flops, avg_launch_us=dom_dur * 1e6,
+                    achieved=dom_flops / dom_dur / 1e12, peak=MFMA_FP32_PEAK / 1e12, unit="TFLOP/s",
+                    frac=dom_flops / dom_dur / MFMA_FP32_PEAK, traffic=None)
+
+    out = dict(metric="matmul/conv GFLOP/s (% fp32 MFMA peak); reduce/transpose GB/s (% HBM peak)",
+               value=value, unit="GFLOP/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
+               ms_per_step=ms_per_step, higher_is_better=True, scaling="weak", vs_baseline=None,
+               dtype="f32", data="synthetic",
+               config=dict(workload="configs[1..4]: reduce_rows/cols 4096x16384, transpose (+copy) 8192^2, matmul sweep "
+                                    "(1024^3, 4096^3, 8192^3, 16384x512x2048, 4096x4096x64), conv2d x3, "
+                                    "dwconv1d, dwconv2d; one launch of each per step"),
+               frac_mfma_peak=value * 1e9 / MFMA_FP32_PEAK, roofline=roofline, ops=per_op)
+
+    # ------------------------------------------------------------------ CPU oracle baseline
+    if not args.no_cpu_baseline:
+        from oracle import lgo
+        A128, B = host_keep["mm8192"]
+        t = time.perf_counter()
+        lgo.matmul(A128, B)
+        dt = time.perf_counter() - t
+        others = {}
+        xs = si.uniform(1, 0, (1024, 16384), 0, 1)
+        t = time.perf_counter(); lgo.reduce_rows(xs); d = time.perf_counter() - t
+        others["reduce_rows_GBps"] = xs.nbytes / d / 1e9
+        t = time.perf_counter(); lgo.reduce_cols(xs); d = time.perf_counter() - t
+        others["reduce_cols_GBps"] = xs.nbytes / d / 1e9
+        xt = si.uniform(1, 1, (2048, 8192), 0, 1)
+        t = time.perf_counter(); lgo.transpose(xt); d = time.perf_counter() - t
+        others["transpose_GBps"] = 2 * xt.nbytes / d / 1e9
+        t = time.perf_counter(); lgo.dwconv2d_nhwc_hwc(I2h, K2h); d = time.perf_counter() - t
+        others["dwconv2d_GBps"] = 4.0 * (O2.numel() + K2.numel() + I2.numel()) / d / 1e9
+        out["cpu_baseline"] = dict(value=2.0 * 128 * 8192 * 8192 / dt / 1e9, unit="GFLOP/s",
+                                   cores=lgo.num_threads(), kind="oracle",
+                                   sample="rows 0..127 of the 8192^3 matmul (naive fp64-accumulate loop nest, "
+                                          f"{dt:.1f} s); other ops on slices: {json.dumps(others)}")
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

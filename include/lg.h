@@ -72,6 +72,14 @@ int lg_matmul(const float *A, const float *B, float *C,
 size_t lg_matmul_workspace_bytes(int64_t M, int64_t N, int64_t K);
 
 /*
+ * Which decomposition lg_matmul (and lg_conv2d_nhwc_hwcf, for its implicit GEMM extents
+ * M = N*OH*OW, N = F, K = KH*KW*C) picks for a shape: the workgroup tile block_m x block_n
+ * and the number of k-slabs (1 = no split, no workspace).  Host-only query for tools that
+ * attribute kernel time to shapes; any of the three output pointers may be NULL.
+ */
+int lg_matmul_plan(int64_t M, int64_t N, int64_t K, int *block_m, int *block_n, int *k_splits);
+
+/*
  * 2-D convolution, Section 4.6.2 equation (2-D), NHWC input, HWCF filter:
  *     O[n,h,w,f] (+)= sum_{kh,kw,c} I[n, h*SH + kh*DH, w*SW + kw*DW, c] * Kf[kh,kw,c,f]
  * (cross-correlation: the filter is not flipped).  I is dense [N,H,W,C], Kf is

@@ -32,8 +32,22 @@
 #include <stdint.h>
 #include <string.h>
 
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
 #define LGO_OK 0
 #define LGO_ERR_INVALID_ARG (-1)
+
+/* Number of host threads the parallel-for loops below use. */
+int lgo_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 /* Output extent of a strided, dilated window over an input extent with no
  * padding: the largest extent for which every access in*S + k*D stays inside

@@ -46,6 +46,10 @@ def _check(rc, name):
         raise ValueError(f"{name}: oracle rejected the arguments (status {rc})")
 
 
+def num_threads():
+    return int(lib().lgo_num_threads())
+
+
 def conv_out_extent(n_in, k, s, d):
     return int(lib().lgo_conv_out_extent(n_in, k, s, d))
 

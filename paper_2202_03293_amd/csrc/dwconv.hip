@@ -151,7 +151,7 @@ static int dwconv_dispatch(const float* I, const float* Kf, float* O,
     const bool unit = SH == 1 && SW == 1 && DH == 1 && DW == 1;
     const bool vec = (C % 4 == 0) && aligned16(I) && aligned16(Kf) && aligned16(O);
     if (unit && vec && KH == 1 && KW == 3) {
-        constexpr int TW = 16;
+        constexpr int TW = 4;    // measured best: short runs, many lanes in flight
         // H rows of a 1-D problem are independent images: fold them into N
         const int64_t NN = N * H;
         const int64_t items = NN * cdiv(OW, TW) * (C / 4);
@@ -162,7 +162,7 @@ static int dwconv_dispatch(const float* I, const float* Kf, float* O,
         return launch_status();
     }
     if (unit && vec && KH == 3 && KW == 3) {
-        constexpr int TH = 8, TW = 4;
+        constexpr int TH = 4, TW = 2;   // small patches: the problem must fill 256 CUs
         const int64_t items = N * cdiv(OH, TH) * cdiv(OW, TW) * (C / 4);
         const int64_t blocks = cdiv(items, kDThreads);
         if (blocks > kMaxGrid) return LG_ERR_UNSUPPORTED;

@@ -413,6 +413,17 @@ static int zero_output(float* C, int64_t M, int64_t N, int64_t ldc, hipStream_t 
 
 }  // namespace lg
 
+extern "C" int lg_matmul_plan(int64_t M, int64_t N, int64_t K, int* block_m, int* block_n, int* k_splits) {
+    using namespace lg;
+    if (M <= 0 || N <= 0 || K <= 0) return LG_ERR_INVALID_ARG;
+    const Plan pl = make_plan(M, N, K);
+    const int edge[3] = {TileBig::BM, TileMid::BM, TileSmall::BM};
+    if (block_m) *block_m = edge[pl.tile];
+    if (block_n) *block_n = edge[pl.tile];
+    if (k_splits) *k_splits = (int)pl.splits;
+    return LG_OK;
+}
+
 extern "C" size_t lg_matmul_workspace_bytes(int64_t M, int64_t N, int64_t K) {
     using namespace lg;
     if (M <= 0 || N <= 0 || K <= 0) return 0;

@@ -3,10 +3,13 @@
 
 namespace lg {
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
 constexpr int kCopyThreads = 256;
 constexpr int kCopyUnroll = 4;   // 128-bit accesses in flight per lane
 
-// out[i,j] = in[i,j].  VEC: rows are whole uint4s and everything is 16-byte aligned.
+// out[i,j] = in[i,j].  VEC: rows are whole 128-bit words and everything is 16-byte aligned; the
+// stream is marked non-temporal on both sides (nothing is reused, keep it out of the caches).
 template <bool VEC>
 __global__ __launch_bounds__(kCopyThreads) void copy2d_kernel(
     const uint32_t* __restrict__ in, uint32_t* __restrict__ out,
@@ -16,7 +19,7 @@ __global__ __launch_bounds__(kCopyThreads) void copy2d_kernel(
     const int64_t total = R * per_row;
     const int64_t base = (int64_t)blockIdx.x * (kCopyThreads * kCopyUnroll) + threadIdx.x;
     if constexpr (VEC) {
-        uint4 v[kCopyUnroll];
+        u32x4 v[kCopyUnroll];
         int64_t dst[kCopyUnroll];
 #pragma unroll
         for (int u = 0; u < kCopyUnroll; ++u) {
@@ -24,13 +27,13 @@ __global__ __launch_bounds__(kCopyThreads) void copy2d_kernel(
             dst[u] = -1;
             if (idx < total) {
                 const int64_t r = idx / per_row, c = idx - r * per_row;
-                v[u] = *reinterpret_cast<const uint4*>(in + r * ld_in + 4 * c);
+                v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(in + r * ld_in + 4 * c));
                 dst[u] = r * ld_out + 4 * c;
             }
         }
 #pragma unroll
         for (int u = 0; u < kCopyUnroll; ++u)
-            if (dst[u] >= 0) *reinterpret_cast<uint4*>(out + dst[u]) = v[u];
+            if (dst[u] >= 0) __builtin_nontemporal_store(v[u], reinterpret_cast<u32x4*>(out + dst[u]));
     } else {
 #pragma unroll
         for (int u = 0; u < kCopyUnroll; ++u) {
@@ -43,66 +46,95 @@ __global__ __launch_bounds__(kCopyThreads) void copy2d_kernel(
     }
 }
 
-constexpr int kTT = 64;          // transpose tile edge
-constexpr int kTThreads = 256;
-
-// out[j,i] = in[i,j] through a 64x64 LDS tile.  Row stride 65 words keeps both the row-wise
-// writes and the column-wise reads of a wavefront on 32 distinct banks twice (the minimum for
-// 64 lanes).  Global accesses are 128-bit on both sides when VEC.
-template <bool VEC>
-__global__ __launch_bounds__(kTThreads) void transpose_kernel(
+// out[j,i] = in[i,j] through a TS x TS LDS tile (TS = 64 or 128) by THREADS lanes.
+//
+// Global side: lanes cover 16 adjacent 128-bit words (256 B) of THREADS/16 rows per pass, and a
+// tile reads/writes TS*4 contiguous bytes per row on both sides (512 B for TS = 128, which is what
+// gets a read+write stream close to the plain copy rate).  LDS side: row stride TS+1 words keeps
+// the row-wise writes and the column-wise reads of a wavefront on 32 distinct banks twice, the
+// minimum for 64 lanes.  Tiles are visited along diagonals so that workgroups running together
+// differ in both row and column block: their strided accesses then do not pile onto the same
+// memory channels.  The XCD-contiguous id order is deliberately NOT used here (measured slower:
+// nothing is shared between tiles, and spreading neighbours over all L2s is what helps).
+template <int TS, int THREADS, bool VEC>
+__global__ __launch_bounds__(THREADS) void transpose_kernel(
     const uint32_t* __restrict__ in, uint32_t* __restrict__ out,
-    int64_t R, int64_t Cn, int64_t ld_in, int64_t ld_out, unsigned tiles_j, unsigned ntiles) {
-    __shared__ uint32_t tile[kTT][kTT + 1];
-    const unsigned id = xcd_contiguous_id(blockIdx.x, ntiles);
-    const int64_t i0 = (int64_t)(id / tiles_j) * kTT;   // first input row of the tile
-    const int64_t j0 = (int64_t)(id % tiles_j) * kTT;   // first input column
+    int64_t R, int64_t Cn, int64_t ld_in, int64_t ld_out, unsigned tiles_j) {
+    extern __shared__ uint32_t tile[];              // [TS][TS + 1]
+    constexpr int S = TS + 1;
+    const unsigned ti = blockIdx.x / tiles_j;
+    const unsigned tj = (blockIdx.x % tiles_j + ti) % tiles_j;
+    const int64_t i0 = (int64_t)ti * TS;            // first input row of the tile
+    const int64_t j0 = (int64_t)tj * TS;            // first input column
     const int t = threadIdx.x;
     if constexpr (VEC) {
+        constexpr int RP = THREADS / 16;            // rows per pass
+        constexpr int NL = (TS / RP) * (TS / 64);   // 128-bit words per lane
         const int c4 = t % 16, rr = t / 16;
-        uint4 v[4];
+        u32x4 v[NL];
+        int k = 0;
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            const int r = it * 16 + rr;
-            v[it] = make_uint4(0, 0, 0, 0);
-            if (i0 + r < R && j0 + 4 * c4 < Cn)
-                v[it] = *reinterpret_cast<const uint4*>(in + (i0 + r) * ld_in + j0 + 4 * c4);
-        }
+        for (int rp = 0; rp < TS / RP; ++rp)
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            const int r = it * 16 + rr;
-            tile[r][4 * c4 + 0] = v[it].x;
-            tile[r][4 * c4 + 1] = v[it].y;
-            tile[r][4 * c4 + 2] = v[it].z;
-            tile[r][4 * c4 + 3] = v[it].w;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            const int orow = it * 16 + rr;     // column of the input tile = row of the output tile
-            if (j0 + orow < Cn && i0 + 4 * c4 < R) {
-                uint4 w;
-                w.x = tile[4 * c4 + 0][orow];
-                w.y = tile[4 * c4 + 1][orow];
-                w.z = tile[4 * c4 + 2][orow];
-                w.w = tile[4 * c4 + 3][orow];
-                *reinterpret_cast<uint4*>(out + (j0 + orow) * ld_out + i0 + 4 * c4) = w;
+            for (int cc = 0; cc < TS / 64; ++cc) {
+                const int64_t gi = i0 + rp * RP + rr, gj = j0 + cc * 64 + 4 * c4;
+                v[k] = u32x4{0, 0, 0, 0};
+                if (gi < R && gj < Cn) v[k] = *reinterpret_cast<const u32x4*>(in + gi * ld_in + gj);
+                ++k;
             }
-        }
+        k = 0;
+#pragma unroll
+        for (int rp = 0; rp < TS / RP; ++rp)
+#pragma unroll
+            for (int cc = 0; cc < TS / 64; ++cc) {
+                uint32_t* p = tile + (rp * RP + rr) * S + cc * 64 + 4 * c4;
+                p[0] = v[k].x; p[1] = v[k].y; p[2] = v[k].z; p[3] = v[k].w;
+                ++k;
+            }
+        __syncthreads();
+#pragma unroll
+        for (int rp = 0; rp < TS / RP; ++rp)
+#pragma unroll
+            for (int cc = 0; cc < TS / 64; ++cc) {
+                const int orow = rp * RP + rr;      // column of the input tile = row of the output tile
+                const int ic = cc * 64 + 4 * c4;    // row of the input tile = column of the output tile
+                if (j0 + orow < Cn && i0 + ic < R) {
+                    u32x4 w;
+                    w.x = tile[(ic + 0) * S + orow];
+                    w.y = tile[(ic + 1) * S + orow];
+                    w.z = tile[(ic + 2) * S + orow];
+                    w.w = tile[(ic + 3) * S + orow];
+                    *reinterpret_cast<u32x4*>(out + (j0 + orow) * ld_out + i0 + ic) = w;
+                }
+            }
     } else {
-        const int c = t % 64, rr = t / 64;
+        constexpr int RP = THREADS / TS;
+        const int c = t % TS, rr = t / TS;
 #pragma unroll 4
-        for (int it = 0; it < 16; ++it) {
-            const int r = it * 4 + rr;
-            if (i0 + r < R && j0 + c < Cn) tile[r][c] = in[(i0 + r) * ld_in + j0 + c];
-        }
+        for (int r = rr; r < TS; r += RP)
+            if (i0 + r < R && j0 + c < Cn) tile[r * S + c] = in[(i0 + r) * ld_in + j0 + c];
         __syncthreads();
 #pragma unroll 4
-        for (int it = 0; it < 16; ++it) {
-            const int orow = it * 4 + rr;
-            if (j0 + orow < Cn && i0 + c < R) out[(j0 + orow) * ld_out + i0 + c] = tile[c][orow];
-        }
+        for (int orow = rr; orow < TS; orow += RP)
+            if (j0 + orow < Cn && i0 + c < R) out[(j0 + orow) * ld_out + i0 + c] = tile[c * S + orow];
     }
+}
+
+template <int TS, int THREADS, bool VEC>
+static int launch_transpose(const uint32_t* in, uint32_t* out, int64_t R, int64_t Cn,
+                            int64_t ld_in, int64_t ld_out, hipStream_t s) {
+    const int64_t ti = cdiv(R, TS), tj = cdiv(Cn, TS);
+    if (ti * tj > kMaxGrid) return LG_ERR_UNSUPPORTED;
+    constexpr size_t lds = (size_t)TS * (TS + 1) * sizeof(uint32_t);
+    static bool configured = false;
+    if (!configured) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&transpose_kernel<TS, THREADS, VEC>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        configured = true;
+    }
+    hipLaunchKernelGGL((transpose_kernel<TS, THREADS, VEC>), dim3((unsigned)(ti * tj)), dim3(THREADS), lds, s,
+                       in, out, R, Cn, ld_in, ld_out, (unsigned)tj);
+    return launch_status();
 }
 
 }  // namespace lg
@@ -136,15 +168,14 @@ extern "C" int lg_transpose(const float* in, float* out, int64_t R, int64_t Cn,
     if (R == 0 || Cn == 0) return LG_OK;
     if (!in || !out) return LG_ERR_INVALID_ARG;
     if (overlaps(in, ((R - 1) * ld_in + Cn) * 4, out, ((Cn - 1) * ld_out + R) * 4)) return LG_ERR_INVALID_ARG;
-    const int64_t ti = cdiv(R, kTT), tj = cdiv(Cn, kTT);
-    if (ti * tj > kMaxGrid || tj > kMaxGrid) return LG_ERR_UNSUPPORTED;
     const bool vec = (Cn % 4 == 0) && (R % 4 == 0) && (ld_in % 4 == 0) && (ld_out % 4 == 0) &&
                      aligned16(in) && aligned16(out);
     hipStream_t s = static_cast<hipStream_t>(stream);
     auto* i32 = reinterpret_cast<const uint32_t*>(in);
     auto* o32 = reinterpret_cast<uint32_t*>(out);
-    const unsigned nt = (unsigned)(ti * tj);
-    if (vec) hipLaunchKernelGGL(transpose_kernel<true>, dim3(nt), dim3(kTThreads), 0, s, i32, o32, R, Cn, ld_in, ld_out, (unsigned)tj, nt);
-    else     hipLaunchKernelGGL(transpose_kernel<false>, dim3(nt), dim3(kTThreads), 0, s, i32, o32, R, Cn, ld_in, ld_out, (unsigned)tj, nt);
-    return launch_status();
+    // 128x128 tiles once they still give every CU several workgroups, 64x64 below that
+    const bool big = cdiv(R, 128) * cdiv(Cn, 128) >= 1024;
+    if (vec && big) return launch_transpose<128, 1024, true>(i32, o32, R, Cn, ld_in, ld_out, s);
+    if (vec)        return launch_transpose<64, 256, true>(i32, o32, R, Cn, ld_in, ld_out, s);
+    return launch_transpose<64, 256, false>(i32, o32, R, Cn, ld_in, ld_out, s);
 }

@@ -18,6 +18,7 @@ _SIGNATURES = {
     "lg_conv_out_extent": (_i64, [_i64] * 4),
     "lg_matmul": (_int, [_vp, _vp, _vp] + [_i64] * 6 + [_int, _vp, _sz, _vp]),
     "lg_matmul_workspace_bytes": (_sz, [_i64] * 3),
+    "lg_matmul_plan": (_int, [_i64] * 3 + [ctypes.POINTER(_int)] * 3),
     "lg_conv2d_nhwc_hwcf": (_int, [_vp, _vp, _vp] + [_i64] * 11 + [_int, _vp, _sz, _vp]),
     "lg_conv2d_workspace_bytes": (_sz, [_i64] * 11),
     "lg_dwconv1d_nwc_wc": (_int, [_vp, _vp, _vp] + [_i64] * 6 + [_int, _vp]),
@@ -110,6 +111,13 @@ def lg_conv_out_extent(n_in, k, stride, dilation):
 
 def lg_matmul_workspace_bytes(M, N, K):
     return lib().lg_matmul_workspace_bytes(M, N, K)
+
+
+def lg_matmul_plan(M, N, K):
+    """(block_m, block_n, k_splits) the library picks for an M x N x K contraction."""
+    bm, bn, sp = _int(), _int(), _int()
+    _check("lg_matmul_plan", lib().lg_matmul_plan(M, N, K, ctypes.byref(bm), ctypes.byref(bn), ctypes.byref(sp)))
+    return bm.value, bn.value, sp.value
 
 
 def lg_matmul(A, B, C, accumulate=False, workspace=None, stream=None):
