@@ -24,8 +24,6 @@ namespace lg {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int BK = 16;   // k-slice staged per main-loop step
-
 struct ConvGeom {        // implicit-GEMM A operand: row m -> (n, oh, ow), column k -> (kh, kw, c)
     int64_t H, W, C, KW, SH, SW, DH, DW, OH, OW;
 };
@@ -36,37 +34,46 @@ struct GemmArgs {
     float* C;            // M x N, row stride ldc (or split-k partials: slab z at C + z*M*ldc)
     int64_t M, N, K;
     int64_t lda, ldb, ldc;
-    int64_t k_per_split; // multiple of BK; slab z covers k in [z*k_per_split, min(K, (z+1)*k_per_split))
+    int64_t k_per_split; // multiple of the tile's BK; slab z covers k in [z*k_per_split, min(K, (z+1)*k_per_split))
     int accumulate;      // only honoured when the grid has one k-slab
     unsigned tiles_m, tiles_n;
     ConvGeom g;
 };
 
-template <int BM_, int BN_, int WM_, int WN_>
+// BM x BN output tile per workgroup, BK-deep k-slices, WM x WN register tile per wavefront.
+// MINW = wavefronts per SIMD the register allocation must leave room for.
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int MINW_>
 struct Tile {
-    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MINW = MINW_;
     static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN;
     static constexpr int WAVES = WAVES_M * WAVES_N;
     static constexpr int THREADS = WAVES * kWave;
     static constexpr int MB = WM / 32;              // accumulator blocks along m per wave
     static constexpr int NB = WN / 32;              // along n (1, 2 or 4: lanes hold NB adjacent columns)
+    static constexpr int QPR = BK / 4;              // float4s per A row of a slice
     static constexpr int A_QUADS = BM * BK / 4;     // float4s in an A slice
     static constexpr int B_QUADS = BK * BN / 4;
     static constexpr int A_PER_T = A_QUADS / THREADS;
     static constexpr int B_PER_T = B_QUADS / THREADS;
+    static constexpr int A_ROW_STEP = THREADS / QPR;
     static constexpr int LDS_FLOATS = 2 * (BM * BK + BK * BN);
+    static_assert(BK == 16 || BK == 32, "k-slice depth");
     static_assert(NB == 1 || NB == 2 || NB == 4, "wave tile width must be 32, 64 or 128");
     static_assert(A_QUADS % THREADS == 0 && B_QUADS % THREADS == 0, "slice must divide over the workgroup");
+    static_assert(THREADS % QPR == 0, "A staging layout");
+
+    // LDS position (in floats) of the float4 holding A[m][4q .. 4q+3] of a slice.  Rows are BK floats;
+    // the quad index is XOR-swizzled with bits of m so that 8 consecutive rows reading the same
+    // logical quad touch 8 distinct 4-bank groups (and so do the 8 lanes that write a row pair / row).
+    __device__ static __forceinline__ int a_off(int m, int q) {
+        constexpr int SH = (QPR == 4) ? 1 : 0;
+        return m * BK + ((q ^ ((m >> SH) & (QPR - 1))) << 2);
+    }
 };
 
-// LDS position (in floats) of the float4 holding A[m][4q .. 4q+3] of a slice.  Rows are 16 floats;
-// the quad index is XOR-swizzled with bits of m so that 8 consecutive rows reading the same
-// logical quad touch 8 distinct 4-bank groups.
-__device__ __forceinline__ int a_lds_off(int m, int q) { return m * BK + ((q ^ ((m >> 1) & 3)) << 2); }
-
 template <class T, bool VEC, bool CONV>
-__global__ __launch_bounds__(T::THREADS) void gemm_kernel(const GemmArgs p) {
-    constexpr int BM = T::BM, BN = T::BN, MB = T::MB, NB = T::NB;
+__global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArgs p) {
+    constexpr int BM = T::BM, BN = T::BN, BK = T::BK, MB = T::MB, NB = T::NB;
     extern __shared__ __align__(16) float lds[];
     float* As = lds;                        // [2][BM*BK]
     float* Bs = lds + 2 * BM * BK;          // [2][BK*BN]
@@ -91,14 +98,15 @@ __global__ __launch_bounds__(T::THREADS) void gemm_kernel(const GemmArgs p) {
     const int wn0 = (wave % T::WAVES_N) * T::WN;
     const int c32 = lane % 32, h = lane / 32;
 
-    // ---- global -> register staging ------------------------------------------------------------
-    // A slice: thread owns float4 (row ar[i], quad aq) for i < A_PER_T; B slice: (row bk[i], float4 column bq[i]).
-    const int aq = t % 4;
+    // ---- global -> register staging coordinates ---------------------------------------------------
+    // A slice: this lane owns the float4 (row t/QPR + i*A_ROW_STEP, quad aq); B slice: float4 number
+    // t + i*THREADS of the row-major [BK][BN] slice.
+    const int aq = t % T::QPR;
+    const int ar0 = t / T::QPR;
     int64_t a_rowbase[T::A_PER_T];          // element offset of A[m][0]; -1 when the row is outside M
 #pragma unroll
     for (int i = 0; i < T::A_PER_T; ++i) {
-        const int r = t / 4 + i * (T::THREADS / 4);
-        const int64_t m = m0 + r;
+        const int64_t m = m0 + ar0 + i * T::A_ROW_STEP;
         if (m >= p.M) { a_rowbase[i] = -1; continue; }
         if constexpr (CONV) {
             const int64_t ow = m % p.g.OW, oh = (m / p.g.OW) % p.g.OH, n = m / (p.g.OW * p.g.OH);
@@ -119,8 +127,8 @@ __global__ __launch_bounds__(T::THREADS) void gemm_kernel(const GemmArgs p) {
         }
     };
 
-    auto load_slice = [&](int64_t k0) {
-        // A
+    // General slice load: every access predicated (edge tiles, k tails, unaligned operands).
+    auto load_slice_edge = [&](int64_t k0) {
         if constexpr (VEC) {
             const int64_t k = k0 + 4 * aq;
             const bool kin = k < kend;             // K % 4 == 0 on this path: a quad is all in or all out
@@ -150,7 +158,6 @@ __global__ __launch_bounds__(T::THREADS) void gemm_kernel(const GemmArgs p) {
                 ra[i] = make_float4(v[0], v[1], v[2], v[3]);
             }
         }
-        // B
 #pragma unroll
         for (int i = 0; i < T::B_PER_T; ++i) {
             const int q = t + i * T::THREADS;
@@ -171,19 +178,57 @@ __global__ __launch_bounds__(T::THREADS) void gemm_kernel(const GemmArgs p) {
         }
     };
 
+    // Interior slice load (whole tile inside M x N, whole slices inside the k-slab, aligned
+    // operands): straight 128-bit loads from running pointers, no predicates, no branches.
+    const float* a_ptr[T::A_PER_T];
+    const float* b_ptr[T::B_PER_T];
+    int cv_c = 0, cv_kw = 0, cv_kh = 0;           // conv: (c, kw, kh) of this lane's quad in the current slice
+    auto init_full = [&]() {
+        const int64_t k = kbeg + 4 * aq;
+        if constexpr (CONV) {
+            cv_c = (int)(k % p.g.C);
+            cv_kw = (int)((k / p.g.C) % p.g.KW);
+            cv_kh = (int)(k / (p.g.C * p.g.KW));
+        }
+#pragma unroll
+        for (int i = 0; i < T::A_PER_T; ++i) a_ptr[i] = p.A + a_rowbase[i] + (CONV ? 0 : k);
+#pragma unroll
+        for (int i = 0; i < T::B_PER_T; ++i) {
+            const int q = t + i * T::THREADS;
+            b_ptr[i] = p.B + (kbeg + q / (BN / 4)) * p.ldb + n0 + 4 * (q % (BN / 4));
+        }
+    };
+    auto load_slice_full = [&]() {
+        int64_t ko = 0;
+        if constexpr (CONV) ko = ((int64_t)cv_kh * p.g.DH * p.g.W + (int64_t)cv_kw * p.g.DW) * p.g.C + cv_c;
+#pragma unroll
+        for (int i = 0; i < T::A_PER_T; ++i) ra[i] = *reinterpret_cast<const float4*>(a_ptr[i] + ko);
+#pragma unroll
+        for (int i = 0; i < T::B_PER_T; ++i) rb[i] = *reinterpret_cast<const float4*>(b_ptr[i]);
+        // advance to the next slice
+        if constexpr (CONV) {
+            cv_c += BK;
+            while (cv_c >= (int)p.g.C) {
+                cv_c -= (int)p.g.C;
+                if (++cv_kw == (int)p.g.KW) { cv_kw = 0; ++cv_kh; }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < T::A_PER_T; ++i) a_ptr[i] += BK;
+        }
+#pragma unroll
+        for (int i = 0; i < T::B_PER_T; ++i) b_ptr[i] += (int64_t)BK * p.ldb;
+    };
+
     auto store_slice = [&](int buf) {
         float* as = As + buf * (BM * BK);
         float* bs = Bs + buf * (BK * BN);
 #pragma unroll
-        for (int i = 0; i < T::A_PER_T; ++i) {
-            const int r = t / 4 + i * (T::THREADS / 4);
-            *reinterpret_cast<float4*>(as + a_lds_off(r, aq)) = ra[i];
-        }
+        for (int i = 0; i < T::A_PER_T; ++i)
+            *reinterpret_cast<float4*>(as + T::a_off(ar0 + i * T::A_ROW_STEP, aq)) = ra[i];
 #pragma unroll
-        for (int i = 0; i < T::B_PER_T; ++i) {
-            const int q = t + i * T::THREADS;
-            *reinterpret_cast<float4*>(bs + 4 * q) = rb[i];      // row-major [BK][BN]
-        }
+        for (int i = 0; i < T::B_PER_T; ++i)
+            *reinterpret_cast<float4*>(bs + 4 * (t + i * T::THREADS)) = rb[i];      // row-major [BK][BN]
     };
 
     // ---- accumulators ------------------------------------------------------------------------
@@ -195,50 +240,76 @@ __global__ __launch_bounds__(T::THREADS) void gemm_kernel(const GemmArgs p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
 
+    // One k-slice from LDS.  Half-wave h of MFMA step st = 4j + i multiplies k = 8j + 4h + i.
+    // Software-pipelined: all A fragments of the slice are fetched up front, the B fragment of
+    // step st+1 is fetched before the MFMAs of step st are issued, so LDS latency hides behind
+    // MB*NB*64 cycles of matrix work instead of stalling the in-order wave.
     auto compute_slice = [&](int buf) {
         const float* as = As + buf * (BM * BK);
-        const float* bs = Bs + buf * (BK * BN) + wn0 + NB * c32;
+        const float* bs = Bs + buf * (BK * BN) + wn0 + NB * c32 + 4 * h * BN;
+        constexpr int NJ = BK / 8, NSTEP = BK / 2;
+        float4 a[NJ][MB];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            float4 a[MB];
+        for (int j = 0; j < NJ; ++j)
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
-                a[mb] = *reinterpret_cast<const float4*>(as + a_lds_off(wm0 + mb * 32 + c32, 2 * j + h));
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float* brow = bs + (8 * j + 4 * h + i) * BN;
-                float b[NB];
-                if constexpr (NB == 4) {
-                    const float4 v = *reinterpret_cast<const float4*>(brow);
-                    b[0] = v.x; b[1] = v.y; b[2] = v.z; b[3] = v.w;
-                } else if constexpr (NB == 2) {
-                    const float2 v = *reinterpret_cast<const float2*>(brow);
-                    b[0] = v.x; b[1] = v.y;
-                } else {
-                    b[0] = *brow;
-                }
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    const float av = (i == 0) ? a[mb].x : (i == 1) ? a[mb].y : (i == 2) ? a[mb].z : a[mb].w;
-#pragma unroll
-                    for (int nb = 0; nb < NB; ++nb)
-                        acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, b[nb], acc[mb][nb], 0, 0, 0);
-                }
+                a[j][mb] = *reinterpret_cast<const float4*>(as + T::a_off(wm0 + mb * 32 + c32, 2 * j + h));
+        float b[2][NB];
+        auto load_b = [&](int st, float (&dst)[NB]) {
+            const float* brow = bs + (8 * (st / 4) + (st % 4)) * BN;
+            if constexpr (NB == 4) {
+                const float4 v = *reinterpret_cast<const float4*>(brow);
+                dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+            } else if constexpr (NB == 2) {
+                const float2 v = *reinterpret_cast<const float2*>(brow);
+                dst[0] = v.x; dst[1] = v.y;
+            } else {
+                dst[0] = *brow;
             }
+        };
+        load_b(0, b[0]);
+#pragma unroll
+        for (int st = 0; st < NSTEP; ++st) {
+            if (st + 1 < NSTEP) load_b(st + 1, b[(st + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            const int j = st / 4, i = st % 4;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                const float av = (i == 0) ? a[j][mb].x : (i == 1) ? a[j][mb].y : (i == 2) ? a[j][mb].z : a[j][mb].w;
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, b[st & 1][nb], acc[mb][nb], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
-    // ---- main loop -----------------------------------------------------------------------------
+    // ---- main loop: LDS double buffer, next slice's global loads in flight during the multiply -----
+    const bool interior = VEC && (m0 + BM <= p.M) && (n0 + BN <= p.N) && ((kend - kbeg) % BK == 0);
     if (nslices > 0) {
-        load_slice(kbeg);
-        store_slice(0);
-        __syncthreads();
-        for (int s = 0; s < nslices; ++s) {
-            const bool more = s + 1 < nslices;
-            if (more) load_slice(kbeg + (int64_t)(s + 1) * BK);
-            compute_slice(s & 1);
-            if (more) store_slice((s + 1) & 1);
+        if (interior) {
+            init_full();
+            load_slice_full();
+            store_slice(0);
             __syncthreads();
+            for (int s = 0; s < nslices - 1; ++s) {
+                load_slice_full();
+                compute_slice(s & 1);
+                store_slice((s + 1) & 1);
+                __syncthreads();
+            }
+            compute_slice((nslices - 1) & 1);
+        } else {
+            load_slice_edge(kbeg);
+            store_slice(0);
+            __syncthreads();
+            for (int s = 0; s < nslices; ++s) {
+                const bool more = s + 1 < nslices;
+                if (more) load_slice_edge(kbeg + (int64_t)(s + 1) * BK);
+                compute_slice(s & 1);
+                if (more) store_slice((s + 1) & 1);
+                __syncthreads();
+            }
         }
     }
 
@@ -305,42 +376,53 @@ __global__ __launch_bounds__(256) void fill_zero_2d_kernel(float* C, int64_t M, 
 
 // ---- host side ---------------------------------------------------------------------------------
 
-using TileBig = Tile<256, 256, 64, 128>;   // 8 waves, 2 per SIMD, 128 accumulator registers per lane
-using TileMid = Tile<128, 128, 64, 64>;    // 4 waves
-using TileSmall = Tile<64, 64, 32, 32>;    // 4 waves
+// The tile menu.  Efficiencies are the measured fraction of the fp32 MFMA rate each configuration
+// sustains on large problems (clock-normalised); the planner only needs their ratios.
+using Tile0 = Tile<128, 256, 16, 32, 128, 2>;   // 8 waves of 32x128, two workgroups per CU
+using Tile1 = Tile<128, 128, 16, 32, 128, 4>;   // 4 waves of 32x128, up to four workgroups per CU
+using Tile2 = Tile<128, 64, 16, 32, 64, 4>;     // 4 waves of 32x64 (narrow outputs, e.g. F = 64)
+using Tile3 = Tile<64, 64, 16, 32, 32, 4>;      // 4 waves of 32x32 (tiny problems)
+
+struct TileInfo { int bm, bn; double eff; };
+constexpr int kNumTiles = 4;
+static const TileInfo kTiles[kNumTiles] = {{128, 256, 0.92}, {128, 128, 0.86}, {128, 64, 0.70}, {64, 64, 0.45}};
 
 struct Plan {
-    int tile;          // 0 big, 1 mid, 2 small
+    int tile;          // index into kTiles
     int64_t tiles_m, tiles_n, splits, k_per_split;
 };
 
 constexpr int kCUs = 256;
+constexpr int kKGran = 32;   // split-k slabs are multiples of this (the deepest k-slice of any tile)
 
+// Pick (tile, k-split) by a small cost model: the busiest CU's MFMA time at the tile's efficiency
+// (padding of ragged edges included), a fixed fill/drain cost per workgroup, and for split-k the
+// partial-sum traffic plus the launch of the combine kernel.
 static Plan make_plan(int64_t M, int64_t N, int64_t K) {
-    Plan pl;
-    const int bm[3] = {256, 128, 64};
-    // largest tile that still gives every CU a workgroup; otherwise the smallest and split k
-    int tile = 2;
-    for (int c = 0; c < 3; ++c) {
-        if (cdiv(M, bm[c]) * cdiv(N, bm[c]) >= kCUs) { tile = c; break; }
+    const double cu_flops = 157.3e12 / kCUs;
+    const int64_t kslabs = cdiv(K, kKGran);
+    static const int split_menu[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
+    Plan best{};
+    double best_cost = 1e300;
+    for (int ti = 0; ti < kNumTiles; ++ti) {
+        const int64_t tm = cdiv(M, kTiles[ti].bm), tn = cdiv(N, kTiles[ti].bn);
+        for (int sp : split_menu) {
+            if (sp > 1 && kslabs < 2 * sp) break;              // keep at least 64 k per slab
+            const int64_t slabs_per = cdiv(kslabs, sp);
+            const int64_t kps = slabs_per * kKGran;
+            const int64_t splits = cdiv(K, kps);
+            if (splits != sp && sp > 1) continue;                // same plan as a smaller menu entry
+            const int64_t wgs = tm * tn * splits;
+            const double wg_flops = 2.0 * kTiles[ti].bm * kTiles[ti].bn * (double)(kps < K ? kps : K);
+            double cost = (double)cdiv(wgs, kCUs) * (wg_flops / (cu_flops * kTiles[ti].eff) + 2.5e-6);
+            if (splits > 1) cost += 2.0 * splits * M * N * 4.0 / 3.0e12 + 5e-6;
+            if (cost < best_cost) {
+                best_cost = cost;
+                best.tile = ti; best.tiles_m = tm; best.tiles_n = tn; best.splits = splits; best.k_per_split = kps;
+            }
+        }
     }
-    pl.tile = tile;
-    pl.tiles_m = cdiv(M, bm[tile]);
-    pl.tiles_n = cdiv(N, bm[tile]);
-    const int64_t tiles = pl.tiles_m * pl.tiles_n;
-    int64_t splits = 1;
-    const int64_t slices = cdiv(K, BK);
-    if (tiles < kCUs && slices >= 8) {
-        splits = cdiv(2 * kCUs, tiles);                      // aim at ~2 workgroups per CU
-        const int64_t max_splits = slices / 4 > 0 ? slices / 4 : 1;   // at least 4 slices (64 k) per slab
-        if (splits > max_splits) splits = max_splits;
-        if (splits > 64) splits = 64;
-    }
-    int64_t slices_per = cdiv(slices, splits);
-    pl.k_per_split = slices_per * BK;
-    pl.splits = cdiv(K, pl.k_per_split);
-    if (pl.splits < 1) pl.splits = 1;
-    return pl;
+    return best;
 }
 
 static size_t plan_workspace(const Plan& pl, int64_t M, int64_t N) {
@@ -388,9 +470,10 @@ static int run_gemm(GemmArgs a, bool vec, int user_accumulate, void* workspace, 
         if (vec) launch_gemm<TILE, true, CONV>(a, z, s);                  \
         else     launch_gemm<TILE, false, CONV>(a, z, s);                 \
     } while (0)
-    if (pl.tile == 0) LG_LAUNCH(TileBig);
-    else if (pl.tile == 1) LG_LAUNCH(TileMid);
-    else LG_LAUNCH(TileSmall);
+    if (pl.tile == 0) LG_LAUNCH(Tile0);
+    else if (pl.tile == 1) LG_LAUNCH(Tile1);
+    else if (pl.tile == 2) LG_LAUNCH(Tile2);
+    else LG_LAUNCH(Tile3);
 #undef LG_LAUNCH
     if (launch_status() != LG_OK) return LG_ERR_RUNTIME;
     if (pl.splits > 1) {
@@ -417,9 +500,8 @@ extern "C" int lg_matmul_plan(int64_t M, int64_t N, int64_t K, int* block_m, int
     using namespace lg;
     if (M <= 0 || N <= 0 || K <= 0) return LG_ERR_INVALID_ARG;
     const Plan pl = make_plan(M, N, K);
-    const int edge[3] = {TileBig::BM, TileMid::BM, TileSmall::BM};
-    if (block_m) *block_m = edge[pl.tile];
-    if (block_n) *block_n = edge[pl.tile];
+    if (block_m) *block_m = kTiles[pl.tile].bm;
+    if (block_n) *block_n = kTiles[pl.tile].bn;
     if (k_splits) *k_splits = (int)pl.splits;
     return LG_OK;
 }
