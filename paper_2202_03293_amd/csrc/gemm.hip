@@ -23,6 +23,29 @@
 namespace lg {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) void lds_void;
+
+// LDS byte address of a pointer into __shared__ memory.
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+    return (uint32_t)(uintptr_t)(lds_void*)p;
+}
+
+// One global -> LDS transfer of 16 bytes per lane: lane l's data lands at LDS address lds + 16*l.
+// `base` and `lds` must be wave-uniform; `voff` is the lane's byte offset from base.  Written as
+// inline assembly on purpose: the compiler then neither knows that LDS is being written
+// asynchronously (it would otherwise make every later ds_read wait for ALL transfers in flight,
+// defeating the prefetch) nor orders anything around it, so the caller owns the synchronisation:
+// dma_wait<N>() followed by a workgroup barrier before the data is read.
+__device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t lds) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds), "v"(voff), "s"(base) : "memory");
+}
+
+// Wait until at most N of this wave's global->LDS transfers are still in flight.
+template <int N>
+__device__ __forceinline__ void dma_wait() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 
 struct ConvGeom {        // implicit-GEMM A operand: row m -> (n, oh, ow), column k -> (kh, kw, c)
     int64_t H, W, C, KW, SH, SW, DH, DW, OH, OW;
@@ -56,11 +79,13 @@ struct Tile {
     static constexpr int A_PER_T = A_QUADS / THREADS;
     static constexpr int B_PER_T = B_QUADS / THREADS;
     static constexpr int A_ROW_STEP = THREADS / QPR;
-    static constexpr int LDS_FLOATS = 2 * (BM * BK + BK * BN);
+    static constexpr int STAGES = 3;                // LDS ring: one slice being multiplied, two in flight
+    static constexpr int LDS_FLOATS = STAGES * (BM * BK + BK * BN);
     static_assert(BK == 16 || BK == 32, "k-slice depth");
     static_assert(NB == 1 || NB == 2 || NB == 4, "wave tile width must be 32, 64 or 128");
     static_assert(A_QUADS % THREADS == 0 && B_QUADS % THREADS == 0, "slice must divide over the workgroup");
     static_assert(THREADS % QPR == 0, "A staging layout");
+    static_assert(A_PER_T == 1 || A_ROW_STEP % 8 == 0, "a lane's A rows must share one swizzle");
 
     // LDS position (in floats) of the float4 holding A[m][4q .. 4q+3] of a slice.  Rows are BK floats;
     // the quad index is XOR-swizzled with bits of m so that 8 consecutive rows reading the same
@@ -75,8 +100,8 @@ template <class T, bool VEC, bool CONV>
 __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArgs p) {
     constexpr int BM = T::BM, BN = T::BN, BK = T::BK, MB = T::MB, NB = T::NB;
     extern __shared__ __align__(16) float lds[];
-    float* As = lds;                        // [2][BM*BK]
-    float* Bs = lds + 2 * BM * BK;          // [2][BK*BN]
+    float* As = lds;                               // [STAGES][BM*BK]
+    float* Bs = lds + T::STAGES * BM * BK;         // [STAGES][BK*BN]
 
     // ---- which tile ------------------------------------------------------------------------
     const unsigned ntiles = p.tiles_m * p.tiles_n;
@@ -178,46 +203,62 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
         }
     };
 
-    // Interior slice load (whole tile inside M x N, whole slices inside the k-slab, aligned
-    // operands): straight 128-bit loads from running pointers, no predicates, no branches.
-    const float* a_ptr[T::A_PER_T];
-    const float* b_ptr[T::B_PER_T];
+    // Interior slices (whole tile inside M x N, whole slices inside the k-slab, aligned operands)
+    // bypass the registers: global_load_lds_dwordx4 moves 16 bytes per lane straight into LDS, the
+    // 64 lanes of a wave filling 1 KiB at consecutive addresses.  A and B slices are therefore laid
+    // out in LDS in lane order: float4 number q = t + i*THREADS of a slice is written by lane t's
+    // i-th load.  For B (row-major [BK][BN]) that is the natural order.  For A, physical quad
+    // q % QPR of row q / QPR must hold the logical quad (q % QPR) ^ swizzle(row), so the lane simply
+    // FETCHES that logical quad; the XOR swizzle costs nothing.  Addresses are a wave-uniform base
+    // (advanced by scalar adds) plus a per-lane 32-bit byte offset that never changes.  (The
+    // convolution gather adds a per-lane k-offset: its (kh, kw, c) walk is not uniform across lanes.)
+    const char* a_base = reinterpret_cast<const char*>(p.A);
+    const char* b_base = reinterpret_cast<const char*>(p.B);
+    uint32_t a_loff[T::A_PER_T], b_loff[T::B_PER_T];
     int cv_c = 0, cv_kw = 0, cv_kh = 0;           // conv: (c, kw, kh) of this lane's quad in the current slice
+    constexpr int SWZ_SH = (T::QPR == 4) ? 1 : 0;
+    const int lq = aq ^ ((ar0 >> SWZ_SH) & (T::QPR - 1));     // logical quad this lane fetches
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     auto init_full = [&]() {
-        const int64_t k = kbeg + 4 * aq;
+        const int64_t k = kbeg + 4 * lq;
         if constexpr (CONV) {
             cv_c = (int)(k % p.g.C);
             cv_kw = (int)((k / p.g.C) % p.g.KW);
             cv_kh = (int)(k / (p.g.C * p.g.KW));
-        }
 #pragma unroll
-        for (int i = 0; i < T::A_PER_T; ++i) a_ptr[i] = p.A + a_rowbase[i] + (CONV ? 0 : k);
+            for (int i = 0; i < T::A_PER_T; ++i) a_loff[i] = (uint32_t)(a_rowbase[i] * 4);
+        } else {
+            a_base += (m0 * p.lda + kbeg) * 4;
+#pragma unroll
+            for (int i = 0; i < T::A_PER_T; ++i)
+                a_loff[i] = (uint32_t)(((int64_t)(ar0 + i * T::A_ROW_STEP) * p.lda + 4 * lq) * 4);
+        }
+        b_base += (kbeg * p.ldb + n0) * 4;
 #pragma unroll
         for (int i = 0; i < T::B_PER_T; ++i) {
             const int q = t + i * T::THREADS;
-            b_ptr[i] = p.B + (kbeg + q / (BN / 4)) * p.ldb + n0 + 4 * (q % (BN / 4));
+            b_loff[i] = (uint32_t)(((int64_t)(q / (BN / 4)) * p.ldb + 4 * (q % (BN / 4))) * 4);
         }
     };
-    auto load_slice_full = [&]() {
-        int64_t ko = 0;
-        if constexpr (CONV) ko = ((int64_t)cv_kh * p.g.DH * p.g.W + (int64_t)cv_kw * p.g.DW) * p.g.C + cv_c;
-#pragma unroll
-        for (int i = 0; i < T::A_PER_T; ++i) ra[i] = *reinterpret_cast<const float4*>(a_ptr[i] + ko);
-#pragma unroll
-        for (int i = 0; i < T::B_PER_T; ++i) rb[i] = *reinterpret_cast<const float4*>(b_ptr[i]);
-        // advance to the next slice
+    // Start the transfer of the next slice into LDS stage `buf`.
+    auto issue_slice = [&](int buf) {
+        float* as = As + buf * (BM * BK) + 4 * 64 * wave_u;
+        float* bs = Bs + buf * (BK * BN) + 4 * 64 * wave_u;
+        uint32_t ko = 0;
         if constexpr (CONV) {
+            ko = (uint32_t)((((int64_t)cv_kh * p.g.DH * p.g.W + (int64_t)cv_kw * p.g.DW) * p.g.C + cv_c) * 4);
             cv_c += BK;
             while (cv_c >= (int)p.g.C) {
                 cv_c -= (int)p.g.C;
                 if (++cv_kw == (int)p.g.KW) { cv_kw = 0; ++cv_kh; }
             }
-        } else {
-#pragma unroll
-            for (int i = 0; i < T::A_PER_T; ++i) a_ptr[i] += BK;
         }
 #pragma unroll
-        for (int i = 0; i < T::B_PER_T; ++i) b_ptr[i] += (int64_t)BK * p.ldb;
+        for (int i = 0; i < T::A_PER_T; ++i) dma16(a_base, a_loff[i] + ko, lds_addr(as + 4 * i * T::THREADS));
+#pragma unroll
+        for (int i = 0; i < T::B_PER_T; ++i) dma16(b_base, b_loff[i], lds_addr(bs + 4 * i * T::THREADS));
+        if constexpr (!CONV) a_base += BK * 4;
+        b_base += (int64_t)BK * p.ldb * 4;
     };
 
     auto store_slice = [&](int buf) {
@@ -284,21 +325,40 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
         }
     };
 
-    // ---- main loop: LDS double buffer, next slice's global loads in flight during the multiply -----
-    const bool interior = VEC && (m0 + BM <= p.M) && (n0 + BN <= p.N) && ((kend - kbeg) % BK == 0);
+    // ---- main loop --------------------------------------------------------------------------
+    // The interior path addresses operands with 32-bit byte offsets from the tile origin.
+    const bool small_offsets = CONV ? (p.g.H * p.g.W * p.g.C * (p.M / (p.g.OH * p.g.OW) + 1) * 4 < ((int64_t)1 << 31))
+                                    : ((int64_t)BM * p.lda * 4 < ((int64_t)1 << 31));
+    const bool interior = VEC && small_offsets && ((int64_t)BK * p.ldb * 4 < ((int64_t)1 << 31)) &&
+                          (m0 + BM <= p.M) && (n0 + BN <= p.N) && ((kend - kbeg) % BK == 0);
     if (nslices > 0) {
         if (interior) {
+            // Ring of three LDS stages, transfers two slices ahead.  Each wave waits for its own
+            // transfers of the slice needed next (vmcnt counts them in order), then the barrier makes
+            // everybody's visible and also guarantees nobody still reads the stage refilled next.
+            constexpr int L = T::A_PER_T + T::B_PER_T;      // transfers per slice per wave
             init_full();
-            load_slice_full();
-            store_slice(0);
-            __syncthreads();
-            for (int s = 0; s < nslices - 1; ++s) {
-                load_slice_full();
-                compute_slice(s & 1);
-                store_slice((s + 1) & 1);
-                __syncthreads();
+            issue_slice(0);
+            if (nslices > 1) {
+                issue_slice(1);
+                dma_wait<L>();
+            } else {
+                dma_wait<0>();
             }
-            compute_slice((nslices - 1) & 1);
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            int cur = 0;
+            for (int s = 0; s < nslices; ++s) {
+                const int nxt2 = cur >= 1 ? cur - 1 : 2;    // (cur + 2) % 3
+                if (s + 2 < nslices) issue_slice(nxt2);
+                compute_slice(cur);
+                if (s + 1 < nslices) {
+                    if (s + 2 < nslices) dma_wait<L>(); else dma_wait<0>();
+                    __builtin_amdgcn_s_barrier();
+                    asm volatile("" ::: "memory");
+                }
+                cur = cur == 2 ? 0 : cur + 1;
+            }
         } else {
             load_slice_edge(kbeg);
             store_slice(0);
@@ -377,15 +437,15 @@ __global__ __launch_bounds__(256) void fill_zero_2d_kernel(float* C, int64_t M, 
 // ---- host side ---------------------------------------------------------------------------------
 
 // The tile menu.  Efficiencies are the measured fraction of the fp32 MFMA rate each configuration
-// sustains on large problems (clock-normalised); the planner only needs their ratios.
-using Tile0 = Tile<128, 256, 16, 32, 128, 2>;   // 8 waves of 32x128, two workgroups per CU
+// sustains on a large problem (4096^3, clock-normalised); the planner only needs their ratios.
+using Tile0 = Tile<128, 256, 16, 64, 128, 2>;   // 4 waves of 64x128 (one per SIMD), two workgroups per CU
 using Tile1 = Tile<128, 128, 16, 32, 128, 4>;   // 4 waves of 32x128, up to four workgroups per CU
 using Tile2 = Tile<128, 64, 16, 32, 64, 4>;     // 4 waves of 32x64 (narrow outputs, e.g. F = 64)
-using Tile3 = Tile<64, 64, 16, 32, 32, 4>;      // 4 waves of 32x32 (tiny problems)
+using Tile3 = Tile<64, 64, 16, 32, 32, 4>;      // 4 waves of 32x32 (small problems)
 
 struct TileInfo { int bm, bn; double eff; };
 constexpr int kNumTiles = 4;
-static const TileInfo kTiles[kNumTiles] = {{128, 256, 0.92}, {128, 128, 0.86}, {128, 64, 0.70}, {64, 64, 0.45}};
+static const TileInfo kTiles[kNumTiles] = {{128, 256, 0.935}, {128, 128, 0.92}, {128, 64, 0.91}, {64, 64, 0.88}};
 
 struct Plan {
     int tile;          // index into kTiles
