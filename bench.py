@@ -9,8 +9,8 @@ touched, more than the 256 MiB Infinity Cache).
 
 Prints ONE JSON line.  `value` is the contraction throughput of the whole step (matmul + conv
 FLOPs divided by the full step time, memory-bound ops included in the time); per-op figures
-against their own rooflines are under `ops`; `roofline` describes the dominant kernel (the
-256x256 MFMA GEMM tile) and `cpu_baseline` the CPU oracle timed on a bounded sample.
+against their own rooflines are under `ops`; `roofline` describes the dominant kernel (the MFMA
+GEMM tile the 8192^3 matmul runs on) and `cpu_baseline` the CPU oracle timed on a bounded sample.
 """
 import argparse
 import json
@@ -24,6 +24,29 @@ if ROOT not in sys.path:
 
 MFMA_FP32_PEAK = 157.3e12      # 256 CU x 4 SIMD x 64 FLOP/clk x 2.4 GHz
 HBM_PEAK = 8.0e12              # bytes/s
+
+
+# HBM traffic of the dominant kernel per launch (average over the launches of one step), from two
+# counter runs of this file (FETCH_SIZE, then WRITE_SIZE; commands and raw figures in
+# profiles/gemm_128x256_bench_step.md).  Valid only for the kernel source it was taken with.
+TRAFFIC = {
+    "kernel": "gemm_128x256",
+    "source_sha256": None,
+    "fetch_bytes": None,
+    "write_bytes": None,
+}
+
+
+def measured_traffic(kernel_name):
+    import hashlib
+    src = os.path.join(ROOT, "paper_2202_03293_amd", "csrc", "gemm.hip")
+    if TRAFFIC["source_sha256"] is None or TRAFFIC["kernel"] != kernel_name:
+        return None
+    with open(src, "rb") as f:
+        if hashlib.sha256(f.read()).hexdigest() != TRAFFIC["source_sha256"]:
+            return None          # the kernel changed since the counters were read
+    return dict(fetch_bytes=TRAFFIC["fetch_bytes"], write_bytes=TRAFFIC["write_bytes"],
+                total_bytes=TRAFFIC["fetch_bytes"] + TRAFFIC["write_bytes"])
 
 
 def main():
@@ -186,15 +209,17 @@ def main():
     contraction_flops = sum(op["flops"] for op in ops if op["bound"] == "mfma")
     value = contraction_flops / (ms_per_step * 1e-3) / 1e9
 
-    # dominant kernel: the 256x256 GEMM tile (all launches that share that kernel, like a
-    # kernel-trace summary groups them)
-    dom = [op for op in ops if op["kernel"] == "gemm_256x256"]
-    dom_flops = sum(op["flops"] for op in dom) / max(len(dom), 1)
-    dom_dur = sum(op["mean_s"] for op in dom) / max(len(dom), 1)
-    roofline = dict(bound="mfma", kernel="gemm_kernel<Tile<256,256,64,128>,vec,matmul>",
-                    launches_per_step=len(dom), flops_per_launch=dom_flops, avg_launch_us=dom_dur * 1e6,
+    # dominant kernel: the GEMM tile the 8192^3 matmul runs on, averaged over ALL launches of a step
+    # that share that kernel (a kernel-trace summary groups them the same way)
+    dom_name = mm[(8192, 8192, 8192)]["kernel"]
+    dom = [op for op in ops if op["kernel"] == dom_name]
+    dom_flops = sum(op["flops"] for op in dom) / len(dom)
+    dom_dur = sum(op["mean_s"] for op in dom) / len(dom)
+    roofline = dict(bound="mfma", kernel=f"lg::gemm_kernel<{dom_name}, vec, matmul>",
+                    launches_per_step=len(dom), ops=[op["name"] for op in dom],
+                    flops_per_launch=dom_flops, avg_launch_us=dom_dur * 1e6,
                     achieved=dom_flops / dom_dur / 1e12, peak=MFMA_FP32_PEAK / 1e12, unit="TFLOP/s",
-                    frac=dom_flops / dom_dur / MFMA_FP32_PEAK, traffic=None)
+                    frac=dom_flops / dom_dur / MFMA_FP32_PEAK, traffic=measured_traffic(dom_name))
 
     out = dict(metric="matmul/conv GFLOP/s (% fp32 MFMA peak); reduce/transpose GB/s (% HBM peak)",
                value=value, unit="GFLOP/s", n_gpus=1, steps=args.steps, warmup=args.warmup,

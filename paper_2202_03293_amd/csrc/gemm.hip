@@ -106,7 +106,7 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
     // ---- which tile ------------------------------------------------------------------------
     const unsigned ntiles = p.tiles_m * p.tiles_n;
     const unsigned L = xcd_contiguous_id(blockIdx.x, ntiles);
-    constexpr unsigned GM = 4;              // tile rows per panel: an XCD's share is ~GM x (32/GM) tiles
+    constexpr unsigned GM = 8;              // tile rows per panel: the ~64 workgroups an XCD runs at once form an 8 x 8 block of tiles
     const unsigned panel = L / (GM * p.tiles_n);
     const unsigned first_m = panel * GM;
     const unsigned gsz = (p.tiles_m - first_m < GM) ? p.tiles_m - first_m : GM;
