@@ -5,8 +5,8 @@
 //
 // Decomposition (the hardware counterpart of the paper's tile / pack / vectorise / contract steps):
 //   grid      -> BM x BN output tiles, dealt so that each XCD's L2 sees a compact block of tiles
-//   workgroup -> stages A[BM x 16] and B[16 x BN] k-slices global -> registers -> LDS, double buffered,
-//                with the next slice's global loads in flight while the current one is multiplied
+//   workgroup -> stages A[BM x BK] and B[BK x BN] k-slices global -> LDS directly (no registers), a ring
+//                of three LDS stages with the transfers running two slices ahead of the multiply
 //   wavefront -> WM x WN register tile of 32x32 fp32 accumulators, v_mfma_f32_32x32x2_f32
 //   epilogue  -> accumulators (+ C) straight to global memory with 128-bit stores
 //
@@ -81,7 +81,7 @@ struct Tile {
     static constexpr int A_ROW_STEP = THREADS / QPR;
     static constexpr int STAGES = 3;                // LDS ring: one slice being multiplied, two in flight
     static constexpr int LDS_FLOATS = STAGES * (BM * BK + BK * BN);
-    static_assert(BK == 16 || BK == 32, "k-slice depth");
+    static_assert(BK == 16 || BK == 32 || BK == 64, "k-slice depth");
     static_assert(NB == 1 || NB == 2 || NB == 4, "wave tile width must be 32, 64 or 128");
     static_assert(A_QUADS % THREADS == 0 && B_QUADS % THREADS == 0, "slice must divide over the workgroup");
     static_assert(THREADS % QPR == 0, "A staging layout");
@@ -90,10 +90,12 @@ struct Tile {
     // LDS position (in floats) of the float4 holding A[m][4q .. 4q+3] of a slice.  Rows are BK floats;
     // the quad index is XOR-swizzled with bits of m so that 8 consecutive rows reading the same
     // logical quad touch 8 distinct 4-bank groups (and so do the 8 lanes that write a row pair / row).
-    __device__ static __forceinline__ int a_off(int m, int q) {
-        constexpr int SH = (QPR == 4) ? 1 : 0;
-        return m * BK + ((q ^ ((m >> SH) & (QPR - 1))) << 2);
-    }
+    // swizzle(m): 3 (or 2) row bits XOR-ed into the quad index.  A row is BK floats = BK/32 times all
+    // banks (BK = 16: two rows span the banks, so the row bits used start at bit 1).
+    static constexpr int SWZ_SH = (QPR == 4) ? 1 : 0;
+    static constexpr int SWZ_MASK = (QPR < 8) ? QPR - 1 : 7;
+    __device__ static __forceinline__ int swizzle(int m) { return (m >> SWZ_SH) & SWZ_MASK; }
+    __device__ static __forceinline__ int a_off(int m, int q) { return m * BK + ((q ^ swizzle(m)) << 2); }
 };
 
 template <class T, bool VEC, bool CONV>
@@ -216,8 +218,7 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
     const char* b_base = reinterpret_cast<const char*>(p.B);
     uint32_t a_loff[T::A_PER_T], b_loff[T::B_PER_T];
     int cv_c = 0, cv_kw = 0, cv_kh = 0;           // conv: (c, kw, kh) of this lane's quad in the current slice
-    constexpr int SWZ_SH = (T::QPR == 4) ? 1 : 0;
-    const int lq = aq ^ ((ar0 >> SWZ_SH) & (T::QPR - 1));     // logical quad this lane fetches
+    const int lq = aq ^ T::swizzle(ar0);          // logical quad this lane fetches
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     auto init_full = [&]() {
         const int64_t k = kbeg + 4 * lq;
@@ -436,16 +437,21 @@ __global__ __launch_bounds__(256) void fill_zero_2d_kernel(float* C, int64_t M, 
 
 // ---- host side ---------------------------------------------------------------------------------
 
-// The tile menu.  Efficiencies are the measured fraction of the fp32 MFMA rate each configuration
-// sustains on a large problem (4096^3, clock-normalised); the planner only needs their ratios.
-using Tile0 = Tile<128, 256, 16, 64, 128, 2>;   // 4 waves of 64x128 (one per SIMD), two workgroups per CU
-using Tile1 = Tile<128, 128, 16, 32, 128, 4>;   // 4 waves of 32x128, up to four workgroups per CU
-using Tile2 = Tile<128, 64, 16, 32, 64, 4>;     // 4 waves of 32x64 (narrow outputs, e.g. F = 64)
-using Tile3 = Tile<64, 64, 16, 32, 32, 4>;      // 4 waves of 32x32 (small problems)
+// The tile menu (all: 4 wavefronts, one per SIMD).  `occ` = workgroups of that tile a CU can hold
+// (LDS and registers), `mfma` = matrix-pipe clocks one k-slice costs one SIMD, `eff` = the measured
+// fraction of the matrix-pipe rate the tile sustains with a full CU (4096^3, clock-normalised).
+using Tile0 = Tile<128, 256, 16, 64, 128, 2>;   // waves of 64x128
+using Tile1 = Tile<128, 128, 16, 32, 128, 4>;   // waves of 32x128
+using Tile2 = Tile<128, 64, 16, 32, 64, 4>;     // waves of 32x64 (narrow outputs, e.g. F = 64)
+using Tile3 = Tile<64, 64, 16, 32, 32, 4>;      // waves of 32x32 (small problems)
+using Tile4 = Tile<64, 128, 32, 32, 64, 4>;     // waves of 32x64, deeper slices (mid-size problems)
+using Tile5 = Tile<64, 64, 32, 32, 32, 4>;      // waves of 32x32, deeper slices
 
-struct TileInfo { int bm, bn; double eff; };
-constexpr int kNumTiles = 4;
-static const TileInfo kTiles[kNumTiles] = {{128, 256, 0.935}, {128, 128, 0.92}, {128, 64, 0.91}, {64, 64, 0.88}};
+struct TileInfo { int bm, bn, bk, occ, mfma; double eff; };
+constexpr int kNumTiles = 6;
+static const TileInfo kTiles[kNumTiles] = {
+    {128, 256, 16, 2, 4096, 0.935}, {128, 128, 16, 4, 2048, 0.92}, {128, 64, 16, 4, 1024, 0.90},
+    {64, 64, 16, 6, 512, 0.875},    {64, 128, 32, 2, 2048, 0.89},  {64, 64, 32, 3, 1024, 0.87}};
 
 struct Plan {
     int tile;          // index into kTiles
@@ -453,28 +459,35 @@ struct Plan {
 };
 
 constexpr int kCUs = 256;
-constexpr int kKGran = 32;   // split-k slabs are multiples of this (the deepest k-slice of any tile)
+constexpr int kKGran = 64;   // split-k slabs are multiples of this (a multiple of every tile's BK)
 
-// Pick (tile, k-split) by a small cost model: the busiest CU's MFMA time at the tile's efficiency
-// (padding of ragged edges included), a fixed fill/drain cost per workgroup, and for split-k the
-// partial-sum traffic plus the launch of the combine kernel.
+// Pick (tile, k-split) with a cost model fitted to measurements on this part: when c workgroups
+// share a CU, one k-slice of all of them takes  c * mfma / eff + dead / c  clocks, where `dead`
+// (barrier skew + LDS refill after the barrier, ~350 clocks, more for deeper slices) is only
+// hidden by other workgroups.  The busiest CU decides; a launch costs ~4 us of fill and drain;
+// split-k adds the partial-sum traffic and a second launch.
 static Plan make_plan(int64_t M, int64_t N, int64_t K) {
-    const double cu_flops = 157.3e12 / kCUs;
+    const double clk = 2.4e9;
     const int64_t kslabs = cdiv(K, kKGran);
     static const int split_menu[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
     Plan best{};
     double best_cost = 1e300;
     for (int ti = 0; ti < kNumTiles; ++ti) {
-        const int64_t tm = cdiv(M, kTiles[ti].bm), tn = cdiv(N, kTiles[ti].bn);
+        const TileInfo& tl = kTiles[ti];
+        const int64_t tm = cdiv(M, tl.bm), tn = cdiv(N, tl.bn);
+        const double dead = 350.0 + 8.0 * (tl.bk - 16);
         for (int sp : split_menu) {
-            if (sp > 1 && kslabs < 2 * sp) break;              // keep at least 64 k per slab
-            const int64_t slabs_per = cdiv(kslabs, sp);
-            const int64_t kps = slabs_per * kKGran;
+            if (sp > 1 && kslabs < 2 * sp) break;                // keep at least 128 k per slab
+            const int64_t kps = cdiv(kslabs, sp) * kKGran;
             const int64_t splits = cdiv(K, kps);
             if (splits != sp && sp > 1) continue;                // same plan as a smaller menu entry
             const int64_t wgs = tm * tn * splits;
-            const double wg_flops = 2.0 * kTiles[ti].bm * kTiles[ti].bn * (double)(kps < K ? kps : K);
-            double cost = (double)cdiv(wgs, kCUs) * (wg_flops / (cu_flops * kTiles[ti].eff) + 2.5e-6);
+            const double nslices = (double)cdiv(kps < K ? kps : K, tl.bk);
+            const int64_t per_cu = cdiv(wgs, kCUs);              // workgroups on the busiest CU
+            const int64_t full = per_cu / tl.occ, rest = per_cu % tl.occ;
+            double clocks = (double)full * nslices * (tl.occ * tl.mfma / tl.eff + dead / tl.occ);
+            if (rest) clocks += nslices * (rest * tl.mfma / tl.eff + dead / rest);
+            double cost = clocks / clk + 4e-6;
             if (splits > 1) cost += 2.0 * splits * M * N * 4.0 / 3.0e12 + 5e-6;
             if (cost < best_cost) {
                 best_cost = cost;
@@ -530,10 +543,14 @@ static int run_gemm(GemmArgs a, bool vec, int user_accumulate, void* workspace, 
         if (vec) launch_gemm<TILE, true, CONV>(a, z, s);                  \
         else     launch_gemm<TILE, false, CONV>(a, z, s);                 \
     } while (0)
-    if (pl.tile == 0) LG_LAUNCH(Tile0);
-    else if (pl.tile == 1) LG_LAUNCH(Tile1);
-    else if (pl.tile == 2) LG_LAUNCH(Tile2);
-    else LG_LAUNCH(Tile3);
+    switch (pl.tile) {
+        case 0: LG_LAUNCH(Tile0); break;
+        case 1: LG_LAUNCH(Tile1); break;
+        case 2: LG_LAUNCH(Tile2); break;
+        case 3: LG_LAUNCH(Tile3); break;
+        case 4: LG_LAUNCH(Tile4); break;
+        default: LG_LAUNCH(Tile5); break;
+    }
 #undef LG_LAUNCH
     if (launch_status() != LG_OK) return LG_ERR_RUNTIME;
     if (pl.splits > 1) {

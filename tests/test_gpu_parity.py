@@ -46,6 +46,8 @@ MATMUL_SHAPES = [
     (1000, 24, 2000),       # split-k, ragged everywhere
     (2048, 2048, 96), (4100, 4104, 36),   # big tile with ragged edges
     (33, 4096, 8),
+    (2048, 2048, 192), (1024, 1024, 320), (1020, 1000, 264), (2048, 1024, 100),   # mid-size tiles, deep slices
+    (6272, 512, 256), (16384, 512, 128),
 ]
 
 
