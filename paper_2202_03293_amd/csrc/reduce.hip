@@ -84,15 +84,17 @@ constexpr int kCRowsPerWave = 64;   // rows one lane adds sequentially before th
 constexpr int kCMaxSplit = 1024;
 
 // Stage 1 of out[j] = sum_i in[i,j]: workgroup (bx, by) sums rows [by*rows_per_wg, ...) of the
-// 64*W columns starting at bx*64*W.  Each lane owns W adjacent columns; the four wavefronts take
+// 64*W columns starting at bx*64*W.  Each lane owns W adjacent columns; the NTH/64 wavefronts take
 // interleaved rows and are combined through LDS.  dst is the partial buffer (row by of width
-// ldp) or the final output when the row range is not split.
-template <bool VEC>
-__global__ __launch_bounds__(kRThreads) void reduce_cols_kernel(
+// ldp) or the final output when the row range is not split.  NTH = 1024 for tall inputs (measured
+// on 4096 x 16384: 16 waves x 512 rows per workgroup 45 us, 4 waves x 256 rows 50 us, combine included).
+template <bool VEC, int NTH>
+__global__ __launch_bounds__(NTH) void reduce_cols_kernel(
     const float* __restrict__ in, float* __restrict__ dst,
     int64_t R, int64_t Cn, int64_t ld, int64_t rows_per_wg, int64_t ldp, int final_accumulate) {
     constexpr int W = VEC ? 4 : 1;
-    __shared__ float part[kRWaves][kWave * W];
+    constexpr int NW = NTH / kWave;
+    __shared__ float part[NW][kWave * W];
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
     const int64_t col = ((int64_t)blockIdx.x * kWave + lane) * W;
     const int64_t r0 = (int64_t)blockIdx.y * rows_per_wg;
@@ -105,35 +107,36 @@ __global__ __launch_bounds__(kRThreads) void reduce_cols_kernel(
         int64_t r = r0 + wave;
         if constexpr (VEC) {
             constexpr int U = 8;                     // rows in flight per lane
-            for (; r + (U - 1) * kRWaves < r1; r += U * kRWaves) {
+            for (; r + (U - 1) * NW < r1; r += U * NW) {
                 float4 v[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u) v[u] = load_stream4(p + (r + u * kRWaves) * ld);
+                for (int u = 0; u < U; ++u) v[u] = load_stream4(p + (r + u * NW) * ld);
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     acc[u & 1][0] += v[u].x; acc[u & 1][1] += v[u].y; acc[u & 1][2] += v[u].z; acc[u & 1][3] += v[u].w;
                 }
             }
-            for (; r < r1; r += kRWaves) {
+            for (; r < r1; r += NW) {
                 const float4 v0 = load_stream4(p + r * ld);
                 acc[0][0] += v0.x; acc[0][1] += v0.y; acc[0][2] += v0.z; acc[0][3] += v0.w;
             }
         } else {
-            for (; r + kRWaves < r1; r += 2 * kRWaves) {
+            for (; r + NW < r1; r += 2 * NW) {
                 acc[0][0] += p[r * ld];
-                acc[1][0] += p[(r + kRWaves) * ld];
+                acc[1][0] += p[(r + NW) * ld];
             }
-            for (; r < r1; r += kRWaves) acc[0][0] += p[r * ld];
+            for (; r < r1; r += NW) acc[0][0] += p[r * ld];
         }
     }
 #pragma unroll
     for (int w = 0; w < W; ++w) part[wave][lane * W + w] = acc[0][w] + acc[1][w];
     __syncthreads();
-    // 64*W columns, 256 threads: thread t finishes column t (and t+256.. when W == 4 -> exactly W/ (256/64)=1 pass)
-    for (int c = threadIdx.x; c < kWave * W; c += kRThreads) {
+    for (int c = threadIdx.x; c < kWave * W; c += NTH) {
         const int64_t gc = (int64_t)blockIdx.x * kWave * W + c;
         if (gc < Cn) {
-            float tot = (part[0][c] + part[1][c]) + (part[2][c] + part[3][c]);
+            float tot = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; w += 4) tot += (part[w][c] + part[w + 1][c]) + (part[w + 2][c] + part[w + 3][c]);
             float* o = dst + (int64_t)blockIdx.y * ldp + gc;
             if (final_accumulate) tot += *o;
             *o = tot;
@@ -166,11 +169,12 @@ __global__ void fill_zero_kernel(float* out, int64_t n) {
     if (i < n) out[i] = 0.f;
 }
 
-struct ColPlan { int64_t splits, rows_per_wg, ldp; };
+struct ColPlan { int64_t splits, rows_per_wg, ldp; bool big; };
 
 static ColPlan plan_cols(int64_t R, int64_t Cn) {
     ColPlan p;
-    const int64_t rows_per_wg_min = (int64_t)kCRowsPerWave * kRWaves;   // 128 rows per workgroup
+    p.big = R >= 2048;                                                  // 16-wave workgroups, 512 rows each
+    const int64_t rows_per_wg_min = p.big ? 512 : (int64_t)kCRowsPerWave * kRWaves;
     int64_t splits = cdiv(R, rows_per_wg_min);
     if (splits > kCMaxSplit) splits = kCMaxSplit;
     if (splits < 1) splits = 1;
@@ -238,12 +242,14 @@ extern "C" int lg_reduce_cols(const float* in, float* out, int64_t R, int64_t Cn
     const bool vec = (Cn % 4 == 0) && (ld % 4 == 0) && aligned16(in);
     const int64_t bx = cdiv(Cn, vec ? 256 : 64);
     if (bx > kMaxGrid || p.splits > 65535) return LG_ERR_UNSUPPORTED;
-    const dim3 g((unsigned)bx, (unsigned)p.splits), b(kRThreads);
+    const dim3 g((unsigned)bx, (unsigned)p.splits), b(kRThreads), b16(1024);
     float* dst = p.splits > 1 ? static_cast<float*>(workspace) : out;
     const int64_t ldp = p.splits > 1 ? p.ldp : 0;
     const int facc = p.splits > 1 ? 0 : accumulate;
-    if (vec) hipLaunchKernelGGL(reduce_cols_kernel<true>, g, b, 0, s, in, dst, R, Cn, ld, p.rows_per_wg, ldp, facc);
-    else     hipLaunchKernelGGL(reduce_cols_kernel<false>, g, b, 0, s, in, dst, R, Cn, ld, p.rows_per_wg, ldp, facc);
+    if (vec && p.big) hipLaunchKernelGGL((reduce_cols_kernel<true, 1024>), g, b16, 0, s, in, dst, R, Cn, ld, p.rows_per_wg, ldp, facc);
+    else if (vec)     hipLaunchKernelGGL((reduce_cols_kernel<true, 256>), g, b, 0, s, in, dst, R, Cn, ld, p.rows_per_wg, ldp, facc);
+    else if (p.big)   hipLaunchKernelGGL((reduce_cols_kernel<false, 1024>), g, b16, 0, s, in, dst, R, Cn, ld, p.rows_per_wg, ldp, facc);
+    else              hipLaunchKernelGGL((reduce_cols_kernel<false, 256>), g, b, 0, s, in, dst, R, Cn, ld, p.rows_per_wg, ldp, facc);
     if (launch_status() != LG_OK) return LG_ERR_RUNTIME;
     if (p.splits > 1) {
         hipLaunchKernelGGL(reduce_cols_combine_kernel, dim3((unsigned)cdiv(Cn, kRThreads)), b, 0, s,

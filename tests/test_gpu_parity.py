@@ -311,7 +311,8 @@ def run_cols(lg, x, out0=None, accumulate=False):
 
 
 RED_SHAPES = [(250, 960), (1, 1), (7, 5), (64, 4096), (100, 4100), (33, 8191), (513, 64),
-              (1000, 3), (5, 20000), (300, 1024), (4096, 8), (129, 260)]
+              (1000, 3), (5, 20000), (300, 1024), (4096, 8), (129, 260),
+              (2500, 1000), (2049, 260), (4100, 37), (2048, 4096)]
 
 
 @pytest.mark.parametrize("R,Cn", RED_SHAPES)
