@@ -19,6 +19,7 @@
 //     ds_read_b{32*NB} fetches the B values of all NB blocks and the epilogue finds NB adjacent
 //     columns of one row in one lane -> 128-bit stores when NB = 4.
 #include "lg_common.hpp"
+#include <type_traits>
 
 namespace lg {
 
@@ -212,22 +213,49 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
     // i-th load.  For B (row-major [BK][BN]) that is the natural order.  For A, physical quad
     // q % QPR of row q / QPR must hold the logical quad (q % QPR) ^ swizzle(row), so the lane simply
     // FETCHES that logical quad; the XOR swizzle costs nothing.  Addresses are a wave-uniform base
-    // (advanced by scalar adds) plus a per-lane 32-bit byte offset that never changes.  (The
-    // convolution gather adds a per-lane k-offset: its (kh, kw, c) walk is not uniform across lanes.)
+    // (advanced by scalar adds) plus a per-lane 32-bit byte offset that never changes.
     const char* a_base = reinterpret_cast<const char*>(p.A);
     const char* b_base = reinterpret_cast<const char*>(p.B);
     uint32_t a_loff[T::A_PER_T], b_loff[T::B_PER_T];
-    int cv_c = 0, cv_kw = 0, cv_kh = 0;           // conv: (c, kw, kh) of this lane's quad in the current slice
+    // Convolution gather: this lane's quad sits at (kh, kw, c); its byte offset from the row base,
+    // cv_off, is advanced incrementally.  One k-slice moves c by BK; when c passes C the tap moves on
+    // (kw, then kh), which changes the offset by constants that are the same for every lane.  For
+    // C >= BK at most one wrap happens per slice and the update is branch-free.
+    int cv_c = 0, cv_kw = 0, cv_kh = 0;
+    uint32_t cv_off = 0;
     const int lq = aq ^ T::swizzle(ar0);          // logical quad this lane fetches
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const int cvC = (int)p.g.C, cvKW = (int)p.g.KW;
+    const uint32_t cv_d_kw = (uint32_t)((p.g.DW * p.g.C - p.g.C) * 4);                       // c wraps, kw + 1
+    const uint32_t cv_d_kh = (uint32_t)((p.g.DH * p.g.W * p.g.C - p.g.KW * p.g.DW * p.g.C) * 4);   // kw wraps, kh + 1
+    auto cv_offset = [&]() {
+        return (uint32_t)((((int64_t)cv_kh * p.g.DH * p.g.W + (int64_t)cv_kw * p.g.DW) * p.g.C + cv_c) * 4);
+    };
+    // When C is a multiple of BK a slice never straddles a filter tap, the walk is the same for all
+    // lanes and lives in scalar registers (su_*): the main loop then spends no vector ALU
+    // instruction on it (vector ALU instructions are not free here: they take issue slots from the
+    // matrix pipe, which small tiles feel).
+    const bool conv_uniform = CONV && (cvC % BK == 0);
+    int su_c = 0, su_kw = 0;
+    uint32_t su_off = 0;
     auto init_full = [&]() {
-        const int64_t k = kbeg + 4 * lq;
         if constexpr (CONV) {
-            cv_c = (int)(k % p.g.C);
-            cv_kw = (int)((k / p.g.C) % p.g.KW);
-            cv_kh = (int)(k / (p.g.C * p.g.KW));
+            if (conv_uniform) {
+                su_c = (int)(kbeg % p.g.C);
+                su_kw = (int)((kbeg / p.g.C) % p.g.KW);
+                const int64_t kh = kbeg / (p.g.C * p.g.KW);
+                su_off = (uint32_t)(((kh * p.g.DH * p.g.W + (int64_t)su_kw * p.g.DW) * p.g.C + su_c) * 4);
 #pragma unroll
-            for (int i = 0; i < T::A_PER_T; ++i) a_loff[i] = (uint32_t)(a_rowbase[i] * 4);
+                for (int i = 0; i < T::A_PER_T; ++i) a_loff[i] = (uint32_t)(a_rowbase[i] * 4) + 16u * lq;
+            } else {
+                const int64_t k = kbeg + 4 * lq;
+                cv_c = (int)(k % p.g.C);
+                cv_kw = (int)((k / p.g.C) % p.g.KW);
+                cv_kh = (int)(k / (p.g.C * p.g.KW));
+                cv_off = cv_offset();
+#pragma unroll
+                for (int i = 0; i < T::A_PER_T; ++i) a_loff[i] = (uint32_t)(a_rowbase[i] * 4);
+            }
         } else {
             a_base += (m0 * p.lda + kbeg) * 4;
 #pragma unroll
@@ -245,20 +273,44 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
     auto issue_slice = [&](int buf) {
         float* as = As + buf * (BM * BK) + 4 * 64 * wave_u;
         float* bs = Bs + buf * (BK * BN) + 4 * 64 * wave_u;
-        uint32_t ko = 0;
-        if constexpr (CONV) {
-            ko = (uint32_t)((((int64_t)cv_kh * p.g.DH * p.g.W + (int64_t)cv_kw * p.g.DW) * p.g.C + cv_c) * 4);
-            cv_c += BK;
-            while (cv_c >= (int)p.g.C) {
-                cv_c -= (int)p.g.C;
-                if (++cv_kw == (int)p.g.KW) { cv_kw = 0; ++cv_kh; }
-            }
+        if (CONV && conv_uniform) {
+            const char* ab = a_base + su_off;
+#pragma unroll
+            for (int i = 0; i < T::A_PER_T; ++i) dma16(ab, a_loff[i], lds_addr(as + 4 * i * T::THREADS));
+        } else {
+            const uint32_t ko = CONV ? cv_off : 0u;
+#pragma unroll
+            for (int i = 0; i < T::A_PER_T; ++i) dma16(a_base, a_loff[i] + ko, lds_addr(as + 4 * i * T::THREADS));
         }
 #pragma unroll
-        for (int i = 0; i < T::A_PER_T; ++i) dma16(a_base, a_loff[i] + ko, lds_addr(as + 4 * i * T::THREADS));
-#pragma unroll
         for (int i = 0; i < T::B_PER_T; ++i) dma16(b_base, b_loff[i], lds_addr(bs + 4 * i * T::THREADS));
-        if constexpr (!CONV) a_base += BK * 4;
+        if (CONV && conv_uniform) {
+            su_c += BK;
+            const bool w1 = su_c >= cvC;
+            su_c -= w1 ? cvC : 0;
+            su_kw += w1 ? 1 : 0;
+            const bool w2 = su_kw == cvKW;
+            su_kw = w2 ? 0 : su_kw;
+            su_off += BK * 4 + (w1 ? cv_d_kw : 0u) + (w2 ? cv_d_kh : 0u);
+        } else if constexpr (CONV) {
+            cv_c += BK;
+            if (cvC >= BK) {                       // uniform test; one possible wrap, no branches below
+                const bool w1 = cv_c >= cvC;
+                cv_c -= w1 ? cvC : 0;
+                cv_kw += w1 ? 1 : 0;
+                const bool w2 = cv_kw == cvKW;
+                cv_kw = w2 ? 0 : cv_kw;
+                cv_off += BK * 4 + (w1 ? cv_d_kw : 0u) + (w2 ? cv_d_kh : 0u);
+            } else {
+                while (cv_c >= cvC) {
+                    cv_c -= cvC;
+                    if (++cv_kw == cvKW) { cv_kw = 0; ++cv_kh; }
+                }
+                cv_off = cv_offset();
+            }
+        } else {
+            a_base += BK * 4;
+        }
         b_base += (int64_t)BK * p.ldb * 4;
     };
 
@@ -348,18 +400,26 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
             }
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
-            int cur = 0;
-            for (int s = 0; s < nslices; ++s) {
-                const int nxt2 = cur >= 1 ? cur - 1 : 2;    // (cur + 2) % 3
-                if (s + 2 < nslices) issue_slice(nxt2);
-                compute_slice(cur);
+            // One trip = three slices, one per LDS stage, so that every LDS address in the loop is a
+            // lane constant plus an immediate (no vector ALU work per slice).
+            auto step = [&](auto stage_c, int s) {
+                constexpr int stage = decltype(stage_c)::value;
+                if (s + 2 < nslices) issue_slice((stage + 2) % 3);
+                compute_slice(stage);
                 if (s + 1 < nslices) {
                     if (s + 2 < nslices) dma_wait<L>(); else dma_wait<0>();
                     __builtin_amdgcn_s_barrier();
                     asm volatile("" ::: "memory");
                 }
-                cur = cur == 2 ? 0 : cur + 1;
+            };
+            int s = 0;
+            for (; s + 3 <= nslices; s += 3) {
+                step(std::integral_constant<int, 0>{}, s);
+                step(std::integral_constant<int, 1>{}, s + 1);
+                step(std::integral_constant<int, 2>{}, s + 2);
             }
+            if (s < nslices) step(std::integral_constant<int, 0>{}, s);
+            if (s + 1 < nslices) step(std::integral_constant<int, 1>{}, s + 1);
         } else {
             load_slice_edge(kbeg);
             store_slice(0);
