@@ -72,6 +72,21 @@ int lg_matmul(const float *A, const float *B, float *C,
 size_t lg_matmul_workspace_bytes(int64_t M, int64_t N, int64_t K);
 
 /*
+ * Matrix multiplication with one transposed operand, Section 4.6.1 equations (A^T B) and (A B^T):
+ *     transA:  C[m,n] (+)= sum_k A[k,m] * B[k,n]      A is stored K x M (row stride lda >= M)
+ *     transB:  C[m,n] (+)= sum_k A[m,k] * B[n,k]      B is stored N x K (row stride ldb >= K)
+ * The transposition is folded into the operand load of the same kernel as lg_matmul (the
+ * transposed operand is staged in the other shared-memory layout); nothing is transposed in
+ * memory.  transA = transB = 0 is lg_matmul; both set is LG_ERR_UNSUPPORTED (it is not one of the
+ * paper's variants).  Workspace: lg_matmul_workspace_bytes(M, N, K).
+ */
+int lg_matmul_t(const float *A, const float *B, float *C,
+                int64_t M, int64_t N, int64_t K,
+                int64_t lda, int64_t ldb, int64_t ldc,
+                int transA, int transB,
+                int accumulate, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Which decomposition lg_matmul (and lg_conv2d_nhwc_hwcf, for its implicit GEMM extents
  * M = N*OH*OW, N = F, K = KH*KW*C) picks for a shape: the workgroup tile block_m x block_n
  * and the number of k-slabs (1 = no split, no workspace).  Host-only query for tools that

@@ -83,6 +83,36 @@ int lgo_matmul(const float *A, const float *B, float *C,
     return LGO_OK;
 }
 
+/* Section 4.6.1, equations (A^T B) and (A B^T):
+ *   transA: C[m,n] = sum_k A[k,m] * B[k,n]   (A stored K x M)
+ *   transB: C[m,n] = sum_k A[m,k] * B[n,k]   (B stored N x K)
+ * Both flags clear is equation (AB); both set is rejected (not one of the paper's variants). */
+int lgo_matmul_t(const float *A, const float *B, float *C,
+                 int64_t M, int64_t N, int64_t K,
+                 int64_t lda, int64_t ldb, int64_t ldc,
+                 int transA, int transB, int accumulate)
+{
+    if (M < 0 || N < 0 || K < 0 || ldc < N) return LGO_ERR_INVALID_ARG;
+    if (transA && transB) return LGO_ERR_INVALID_ARG;
+    if (lda < (transA ? M : K) || ldb < (transB ? K : N)) return LGO_ERR_INVALID_ARG;
+    if (M == 0 || N == 0) return LGO_OK;
+    if (!C || (K > 0 && (!A || !B))) return LGO_ERR_INVALID_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            double s = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                double a = transA ? (double)A[k * lda + m] : (double)A[m * lda + k];
+                double b = transB ? (double)B[n * ldb + k] : (double)B[k * ldb + n];
+                s += a * b;
+            }
+            if (accumulate) s += (double)C[m * ldc + n];
+            C[m * ldc + n] = (float)s;
+        }
+    }
+    return LGO_OK;
+}
+
 /* Section 4.6.2, equation (2-D):
  *   O[n,h,w,f] = sum_{kh,kw,c} I[n, h*SH + kh*DH, w*SW + kw*DW, c] * K[kh,kw,c,f]
  * I is [N,H,W,C], K is [KH,KW,C,F], O is [N,OH,OW,F], all contiguous. */

@@ -39,6 +39,7 @@ class Oracle:
         L.lgo_conv_out_extent.restype = _i64
         L.lgo_conv_out_extent.argtypes = [_i64] * 4
         L.lgo_matmul.argtypes = [_fp, _fp, _fp] + [_i64] * 6 + [ctypes.c_int]
+        L.lgo_matmul_t.argtypes = [_fp, _fp, _fp] + [_i64] * 6 + [ctypes.c_int] * 3
         L.lgo_conv2d_nhwc_hwcf.argtypes = [_fp, _fp, _fp] + [_i64] * 11 + [ctypes.c_int]
         L.lgo_im2col_nhwc.argtypes = [_fp, _fp] + [_i64] * 10
         L.lgo_dwconv1d_nwc_wc.argtypes = [_fp, _fp, _fp] + [_i64] * 6 + [ctypes.c_int]
@@ -70,6 +71,19 @@ class Oracle:
         _check(self._lib.lgo_matmul(_p(A), _p(B), _p(C), M, N, K, K, N, N, int(accumulate)), "matmul")
         return C
 
+
+    def matmul_t(self, A, B, trans_a=False, trans_b=False, C=None, accumulate=False):
+        """C[M,N] (+)= op(A) @ op(B); A is [K,M] when trans_a, B is [N,K] when trans_b."""
+        K, M = A.shape if trans_a else A.shape[::-1]
+        N = B.shape[0] if trans_b else B.shape[1]
+        assert tuple(B.shape) == ((N, K) if trans_b else (K, N))
+        if C is None:
+            assert not accumulate
+            C = np.empty((M, N), np.float32)
+        assert C.shape == (M, N)
+        _check(self._lib.lgo_matmul_t(_p(A), _p(B), _p(C), M, N, K, A.shape[1], B.shape[1], N,
+                                      int(trans_a), int(trans_b), int(accumulate)), "matmul_t")
+        return C
 
     def conv2d_nhwc_hwcf(self, I, Kf, O=None, stride=(1, 1), dilation=(1, 1), accumulate=False):
         N, H, W, C = I.shape

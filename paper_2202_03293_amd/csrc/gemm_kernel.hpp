@@ -1,0 +1,650 @@
+// The fp32 MFMA GEMM kernel template of liblg: matmul in its three operand layouts (Section 4.6.1,
+// equations AB, A^T B, A B^T) and conv_2d_nhwc_hwcf (Section 4.6.2) as an implicit GEMM with
+// M = N*OH*OW, N = F, K = KH*KW*C whose A operand is gathered from the NHWC input on the fly (the
+// HWCF filter already is a row-major [K, F] matrix).
+//
+// Decomposition (the hardware counterpart of the paper's tile / pack / vectorise / contract steps):
+//   grid      -> BM x BN output tiles, dealt so that each XCD's L2 sees a compact block of tiles
+//   workgroup -> stages A and B k-slices (BK deep) global -> LDS directly (no registers), a ring of
+//                three LDS stages with the transfers running two slices ahead of the multiply
+//   wavefront -> WM x WN register tile of 32x32 fp32 accumulators, v_mfma_f32_32x32x2_f32
+//   epilogue  -> accumulators (+ C) straight to global memory
+//
+// An operand slice comes in one of two kinds, by which of its two axes is contiguous in memory:
+//   R-kind (k contiguous: A of AB and A B^T, B of A B^T): LDS holds [rows][BK], the float4 column
+//       XOR-swizzled with row bits; a lane reads FOUR consecutive k of its row with one
+//       ds_read_b128 and feeds them to four MFMAs.  This works because the sum over k is order-free:
+//       half-wave h of MFMA step 4j+i multiplies k = 8j + 4h + i, for both operands.
+//   C-kind (m or n contiguous: B of AB and A^T B, A of A^T B): LDS holds [BK][cols] as in memory; a
+//       lane reads one k-row per MFMA step.  For B the columns are interleaved over the accumulator
+//       blocks (block nb holds columns NB*c + nb, c = lane % 32), so one ds_read_b{32*NB} feeds all
+//       NB blocks and the epilogue finds NB adjacent columns of a row in one lane (128-bit stores).
+#pragma once
+#include "lg_common.hpp"
+#include <type_traits>
+
+namespace lg {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) void lds_void;
+
+// LDS byte address of a pointer into __shared__ memory.
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+    return (uint32_t)(uintptr_t)(lds_void*)p;
+}
+
+// One global -> LDS transfer of 16 bytes per lane: lane l's data lands at LDS address lds + 16*l.
+// `base` and `lds` must be wave-uniform; `voff` is the lane's byte offset from base.  Written as
+// inline assembly on purpose: the compiler then neither knows that LDS is being written
+// asynchronously (it would otherwise make every later ds_read wait for ALL transfers in flight,
+// defeating the prefetch) nor orders anything around it, so the caller owns the synchronisation:
+// dma_wait<N>() followed by a workgroup barrier before the data is read.
+__device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t lds) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds), "v"(voff), "s"(base) : "memory");
+}
+
+// Wait until at most N of this wave's global->LDS transfers are still in flight.
+template <int N>
+__device__ __forceinline__ void dma_wait() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+struct ConvGeom {        // implicit-GEMM A operand: row m -> (n, oh, ow), column k -> (kh, kw, c)
+    int64_t H, W, C, KW, SH, SW, DH, DW, OH, OW;
+};
+
+struct GemmArgs {
+    const float* A;      // AB, A B^T: M x K (row stride lda).  A^T B: K x M.  conv: NHWC input
+    const float* B;      // AB, A^T B: K x N (row stride ldb).  A B^T: N x K
+    float* C;            // M x N, row stride ldc (or split-k partials: slab z at C + z*M*ldc)
+    int64_t M, N, K;
+    int64_t lda, ldb, ldc;
+    int64_t k_per_split; // multiple of the tile's BK; slab z covers k in [z*k_per_split, min(K, (z+1)*k_per_split))
+    int accumulate;      // only honoured when the grid has one k-slab
+    unsigned tiles_m, tiles_n;
+    ConvGeom g;
+};
+
+// BM x BN output tile per workgroup, BK-deep k-slices, WM x WN register tile per wavefront.
+// MINW = wavefronts per SIMD the register allocation must leave room for.
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int MINW_>
+struct Tile {
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MINW = MINW_;
+    static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN;
+    static constexpr int WAVES = WAVES_M * WAVES_N;
+    static constexpr int THREADS = WAVES * kWave;
+    static constexpr int MB = WM / 32;              // accumulator blocks along m per wave
+    static constexpr int NB = WN / 32;              // along n (1, 2 or 4)
+    static constexpr int QPR = BK / 4;              // float4s per row of an R-kind slice
+    static constexpr int A_PER_T = BM * BK / 4 / THREADS;   // float4s of a slice per lane
+    static constexpr int B_PER_T = BK * BN / 4 / THREADS;
+    static constexpr int ROW_STEP = THREADS / QPR;  // R-kind: rows between a lane's successive float4s
+    static constexpr int STAGES = 3;                // LDS ring: one slice being multiplied, two in flight
+    static constexpr int LDS_FLOATS = STAGES * (BM * BK + BK * BN);
+    static_assert(BK == 16 || BK == 32 || BK == 64, "k-slice depth");
+    static_assert(NB == 1 || NB == 2 || NB == 4, "wave tile width must be 32, 64 or 128");
+    static_assert((BM * BK / 4) % THREADS == 0 && (BK * BN / 4) % THREADS == 0, "slice must divide over the workgroup");
+    static_assert(THREADS % QPR == 0 && ROW_STEP % 8 == 0, "a lane's R-kind rows must share one swizzle");
+
+    // R-kind LDS position (in floats) of the float4 holding k = 4q .. 4q+3 of row r.  Rows are BK
+    // floats; the quad index is XOR-ed with row bits so that 8 consecutive rows reading the same
+    // logical quad touch 8 distinct 4-bank groups.  A row is BK/32 times all banks (BK = 16: two rows
+    // span the banks, so the row bits used start at bit 1).
+    static constexpr int SWZ_SH = (QPR == 4) ? 1 : 0;
+    static constexpr int SWZ_MASK = (QPR < 8) ? QPR - 1 : 7;
+    __device__ static __forceinline__ int swizzle(int r) { return (r >> SWZ_SH) & SWZ_MASK; }
+    __device__ static __forceinline__ int r_off(int r, int q) { return r * BK + ((q ^ swizzle(r)) << 2); }
+};
+
+template <class T, bool VEC, bool CONV, bool TA, bool TB>
+__global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArgs p) {
+    static_assert(!(CONV && (TA || TB)) && !(TA && TB), "supported operand layouts");
+    constexpr int BM = T::BM, BN = T::BN, BK = T::BK, MB = T::MB, NB = T::NB, NTH = T::THREADS;
+    constexpr int APT = T::A_PER_T, BPT = T::B_PER_T;
+    extern __shared__ __align__(16) float lds[];
+    float* As = lds;                               // [STAGES][BM*BK]
+    float* Bs = lds + T::STAGES * BM * BK;         // [STAGES][BK*BN]
+
+    // ---- which tile ------------------------------------------------------------------------
+    const unsigned ntiles = p.tiles_m * p.tiles_n;
+    const unsigned L = xcd_contiguous_id(blockIdx.x, ntiles);
+    constexpr unsigned GM = 8;     // tile rows per panel: the ~64 workgroups an XCD runs at once form an 8 x 8 block of tiles
+    const unsigned panel = L / (GM * p.tiles_n);
+    const unsigned first_m = panel * GM;
+    const unsigned gsz = (p.tiles_m - first_m < GM) ? p.tiles_m - first_m : GM;
+    const unsigned in_panel = L - panel * GM * p.tiles_n;
+    const int64_t m0 = (int64_t)(first_m + in_panel % gsz) * BM;
+    const int64_t n0 = (int64_t)(in_panel / gsz) * BN;
+    const int64_t kbeg = (int64_t)blockIdx.y * p.k_per_split;
+    const int64_t kend = (kbeg + p.k_per_split < p.K) ? kbeg + p.k_per_split : p.K;
+    const int nslices = (int)((kend - kbeg + BK - 1) / BK);
+
+    const int t = threadIdx.x;
+    const int lane = t % kWave, wave = t / kWave;
+    const int wm0 = (wave / T::WAVES_N) * T::WM;   // wave tile origin inside the block tile
+    const int wn0 = (wave % T::WAVES_N) * T::WN;
+    const int c32 = lane % 32, h = lane / 32;
+
+    // ---- staging coordinates ----------------------------------------------------------------------
+    // Float4 number q = t + i*NTH of a slice is staged by lane t (its i-th float4) and lives at LDS
+    // float offset 4q of the stage, for both kinds.  R-kind: q -> row q / QPR, physical quad q % QPR,
+    // and the lane fetches the LOGICAL quad lq = physical ^ swizzle(row) (the same for all i), so the
+    // swizzle costs nothing.  C-kind: q -> k-row q / (cols/4), column quad q % (cols/4).
+    const int r0 = t / T::QPR;
+    const int lq = (t % T::QPR) ^ T::swizzle(r0);
+
+    // R-kind row bases (element offset of the row's k = 0; -1 when the row is outside the matrix)
+    int64_t a_rowbase[TA ? 1 : APT];
+    int64_t b_rowbase[TB ? BPT : 1];
+    if constexpr (!TA) {
+#pragma unroll
+        for (int i = 0; i < APT; ++i) {
+            const int64_t m = m0 + r0 + i * T::ROW_STEP;
+            if (m >= p.M) { a_rowbase[i] = -1; continue; }
+            if constexpr (CONV) {
+                const int64_t ow = m % p.g.OW, oh = (m / p.g.OW) % p.g.OH, n = m / (p.g.OW * p.g.OH);
+                a_rowbase[i] = ((n * p.g.H + oh * p.g.SH) * p.g.W + ow * p.g.SW) * p.g.C;
+            } else {
+                a_rowbase[i] = m * p.lda;
+            }
+        }
+    }
+    if constexpr (TB) {
+#pragma unroll
+        for (int i = 0; i < BPT; ++i) {
+            const int64_t n = n0 + r0 + i * T::ROW_STEP;
+            b_rowbase[i] = n < p.N ? n * p.ldb : -1;
+        }
+    }
+    float4 ra[APT], rb[BPT];
+
+    auto conv_koff = [&](int64_t k) -> int64_t {   // conv: offset of GEMM column k relative to the row base
+        const int64_t c = k % p.g.C, kk = k / p.g.C;
+        const int64_t kw = kk % p.g.KW, kh = kk / p.g.KW;
+        return (kh * p.g.DH * p.g.W + kw * p.g.DW) * p.g.C + c;
+    };
+
+    // ---- general (edge) slice loads: every access predicated ----------------------------------------
+    auto load_R = [&](const float* base, const int64_t* rowbase, bool is_conv, int64_t k0, float4* regs, auto per_c) {
+        constexpr int PER = decltype(per_c)::value;
+        if constexpr (VEC) {
+            const int64_t k = k0 + 4 * lq;
+            const bool kin = k < kend;             // K % 4 == 0 on this path: a quad is all in or all out
+            const int64_t ko = !kin ? 0 : (is_conv ? conv_koff(k) : k);
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                regs[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (kin && rowbase[i] >= 0) regs[i] = *reinterpret_cast<const float4*>(base + rowbase[i] + ko);
+            }
+        } else {
+            int64_t ko[4];
+            bool kin[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int64_t k = k0 + 4 * lq + e;
+                kin[e] = k < kend;
+                ko[e] = !kin[e] ? 0 : (is_conv ? conv_koff(k) : k);
+            }
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                float v[4] = {0.f, 0.f, 0.f, 0.f};
+                if (rowbase[i] >= 0) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (kin[e]) v[e] = base[rowbase[i] + ko[e]];
+                }
+                regs[i] = make_float4(v[0], v[1], v[2], v[3]);
+            }
+        }
+    };
+    auto load_C = [&](const float* base, int64_t ld, int64_t col0, int64_t ncols, int64_t k0, float4* regs,
+                      auto per_c, auto cols_c) {
+        constexpr int PER = decltype(per_c)::value, CQ = decltype(cols_c)::value / 4;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int q = t + i * NTH;
+            const int64_t k = k0 + q / CQ, c = col0 + 4 * (q % CQ);
+            regs[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (k < kend) {
+                const float* ptr = base + k * ld + c;
+                if constexpr (VEC) {
+                    if (c < ncols) regs[i] = *reinterpret_cast<const float4*>(ptr);   // ncols % 4 == 0 here
+                } else {
+                    if (c + 0 < ncols) regs[i].x = ptr[0];
+                    if (c + 1 < ncols) regs[i].y = ptr[1];
+                    if (c + 2 < ncols) regs[i].z = ptr[2];
+                    if (c + 3 < ncols) regs[i].w = ptr[3];
+                }
+            }
+        }
+    };
+    auto load_slice_edge = [&](int64_t k0) {
+        if constexpr (TA) load_C(p.A, p.lda, m0, p.M, k0, ra, std::integral_constant<int, APT>{}, std::integral_constant<int, BM>{});
+        else              load_R(p.A, a_rowbase, CONV, k0, ra, std::integral_constant<int, APT>{});
+        if constexpr (TB) load_R(p.B, b_rowbase, false, k0, rb, std::integral_constant<int, BPT>{});
+        else              load_C(p.B, p.ldb, n0, p.N, k0, rb, std::integral_constant<int, BPT>{}, std::integral_constant<int, BN>{});
+    };
+    auto store_slice = [&](int buf) {
+        float* as = As + buf * (BM * BK);
+        float* bs = Bs + buf * (BK * BN);
+#pragma unroll
+        for (int i = 0; i < APT; ++i) *reinterpret_cast<float4*>(as + 4 * (t + i * NTH)) = ra[i];
+#pragma unroll
+        for (int i = 0; i < BPT; ++i) *reinterpret_cast<float4*>(bs + 4 * (t + i * NTH)) = rb[i];
+    };
+
+    // ---- interior slices: global -> LDS transfers ---------------------------------------------------
+    // Whole tile inside M x N, whole slices inside the k-slab, aligned operands.  global_load_lds_dwordx4
+    // moves 16 bytes per lane straight into LDS, the 64 lanes of a wave filling 1 KiB at consecutive
+    // addresses, which is exactly the lane-order layout above.  Addresses are a wave-uniform base
+    // (advanced by scalar adds) plus a per-lane 32-bit byte offset that never changes, so the main
+    // loop spends no vector ALU instruction on addressing (vector ALU instructions are not free
+    // here: they take issue slots from the matrix pipe, which small tiles feel).
+    const char* a_base = reinterpret_cast<const char*>(p.A);
+    const char* b_base = reinterpret_cast<const char*>(p.B);
+    uint32_t a_loff[APT], b_loff[BPT];
+    int64_t a_adv = 0, b_adv = 0;                  // bytes per k-slice
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+
+    // Convolution gather: a quad sits at filter tap (kh, kw), channel c; its byte offset from the row
+    // base advances by BK channels per slice, and when c passes C the tap moves on (kw, then kh),
+    // which changes the offset by constants.  When C is a multiple of BK a slice never straddles a
+    // tap, the walk is the same for all lanes and lives in scalar registers (su_*); otherwise each
+    // lane walks its own quad (cv_*), branch-free when C >= BK.
+    const int cvC = (int)p.g.C, cvKW = (int)p.g.KW;
+    const uint32_t cv_d_kw = (uint32_t)((p.g.DW * p.g.C - p.g.C) * 4);                          // c wraps, kw + 1
+    const uint32_t cv_d_kh = (uint32_t)((p.g.DH * p.g.W * p.g.C - p.g.KW * p.g.DW * p.g.C) * 4);  // kw wraps, kh + 1
+    const bool conv_uniform = CONV && (cvC % BK == 0);
+    int cv_c = 0, cv_kw = 0, cv_kh = 0, su_c = 0, su_kw = 0;
+    uint32_t cv_off = 0, su_off = 0;
+    auto cv_offset = [&]() {
+        return (uint32_t)((((int64_t)cv_kh * p.g.DH * p.g.W + (int64_t)cv_kw * p.g.DW) * p.g.C + cv_c) * 4);
+    };
+
+    auto r_loff = [&](int64_t ld, uint32_t* loff, auto per_c) {      // R-kind lane offsets from (row0, kbeg)
+#pragma unroll
+        for (int i = 0; i < decltype(per_c)::value; ++i)
+            loff[i] = (uint32_t)(((int64_t)(r0 + i * T::ROW_STEP) * ld + 4 * lq) * 4);
+    };
+    auto c_loff = [&](int64_t ld, uint32_t* loff, auto per_c, auto cols_c) {   // C-kind, from (kbeg, col0)
+        constexpr int CQ = decltype(cols_c)::value / 4;
+#pragma unroll
+        for (int i = 0; i < decltype(per_c)::value; ++i) {
+            const int q = t + i * NTH;
+            loff[i] = (uint32_t)(((int64_t)(q / CQ) * ld + 4 * (q % CQ)) * 4);
+        }
+    };
+    auto init_full = [&]() {
+        if constexpr (CONV) {
+            if (conv_uniform) {
+                su_c = (int)(kbeg % p.g.C);
+                su_kw = (int)((kbeg / p.g.C) % p.g.KW);
+                const int64_t kh = kbeg / (p.g.C * p.g.KW);
+                su_off = (uint32_t)(((kh * p.g.DH * p.g.W + (int64_t)su_kw * p.g.DW) * p.g.C + su_c) * 4);
+#pragma unroll
+                for (int i = 0; i < APT; ++i) a_loff[i] = (uint32_t)(a_rowbase[i] * 4) + 16u * lq;
+            } else {
+                const int64_t k = kbeg + 4 * lq;
+                cv_c = (int)(k % p.g.C);
+                cv_kw = (int)((k / p.g.C) % p.g.KW);
+                cv_kh = (int)(k / (p.g.C * p.g.KW));
+                cv_off = cv_offset();
+#pragma unroll
+                for (int i = 0; i < APT; ++i) a_loff[i] = (uint32_t)(a_rowbase[i] * 4);
+            }
+        } else if constexpr (TA) {
+            a_base += (kbeg * p.lda + m0) * 4;
+            a_adv = (int64_t)BK * p.lda * 4;
+            c_loff(p.lda, a_loff, std::integral_constant<int, APT>{}, std::integral_constant<int, BM>{});
+        } else {
+            a_base += (m0 * p.lda + kbeg) * 4;
+            a_adv = BK * 4;
+            r_loff(p.lda, a_loff, std::integral_constant<int, APT>{});
+        }
+        if constexpr (TB) {
+            b_base += (n0 * p.ldb + kbeg) * 4;
+            b_adv = BK * 4;
+            r_loff(p.ldb, b_loff, std::integral_constant<int, BPT>{});
+        } else {
+            b_base += (kbeg * p.ldb + n0) * 4;
+            b_adv = (int64_t)BK * p.ldb * 4;
+            c_loff(p.ldb, b_loff, std::integral_constant<int, BPT>{}, std::integral_constant<int, BN>{});
+        }
+    };
+    // Start the transfer of the next slice into LDS stage `buf`.
+    auto issue_slice = [&](int buf) {
+        float* as = As + buf * (BM * BK) + 4 * 64 * wave_u;
+        float* bs = Bs + buf * (BK * BN) + 4 * 64 * wave_u;
+        if (CONV && conv_uniform) {
+            const char* ab = a_base + su_off;
+#pragma unroll
+            for (int i = 0; i < APT; ++i) dma16(ab, a_loff[i], lds_addr(as + 4 * i * NTH));
+        } else {
+            const uint32_t ko = CONV ? cv_off : 0u;
+#pragma unroll
+            for (int i = 0; i < APT; ++i) dma16(a_base, a_loff[i] + ko, lds_addr(as + 4 * i * NTH));
+        }
+#pragma unroll
+        for (int i = 0; i < BPT; ++i) dma16(b_base, b_loff[i], lds_addr(bs + 4 * i * NTH));
+        if (CONV && conv_uniform) {
+            su_c += BK;
+            const bool w1 = su_c >= cvC;
+            su_c -= w1 ? cvC : 0;
+            su_kw += w1 ? 1 : 0;
+            const bool w2 = su_kw == cvKW;
+            su_kw = w2 ? 0 : su_kw;
+            su_off += BK * 4 + (w1 ? cv_d_kw : 0u) + (w2 ? cv_d_kh : 0u);
+        } else if constexpr (CONV) {
+            cv_c += BK;
+            if (cvC >= BK) {                       // uniform test; one possible wrap, no branches below
+                const bool w1 = cv_c >= cvC;
+                cv_c -= w1 ? cvC : 0;
+                cv_kw += w1 ? 1 : 0;
+                const bool w2 = cv_kw == cvKW;
+                cv_kw = w2 ? 0 : cv_kw;
+                cv_off += BK * 4 + (w1 ? cv_d_kw : 0u) + (w2 ? cv_d_kh : 0u);
+            } else {
+                while (cv_c >= cvC) {
+                    cv_c -= cvC;
+                    if (++cv_kw == cvKW) { cv_kw = 0; ++cv_kh; }
+                }
+                cv_off = cv_offset();
+            }
+        } else {
+            a_base += a_adv;
+        }
+        b_base += b_adv;
+    };
+
+    // ---- accumulators ------------------------------------------------------------------------
+    floatx16 acc[MB][NB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
+
+    // One k-slice from LDS.  Half-wave h of MFMA step st = 4j + i multiplies k = 8j + 4h + i.
+    // Software-pipelined: R-kind fragments (4 k per read) are fetched up front, the C-kind fragment of
+    // step st+1 is fetched before the MFMAs of step st are issued, so LDS latency hides behind
+    // MB*NB*64 cycles of matrix work instead of stalling the in-order wave.
+    auto compute_slice = [&](int buf) {
+        const float* as = As + buf * (BM * BK);
+        const float* bs = Bs + buf * (BK * BN);
+        constexpr int NJ = BK / 8, NSTEP = BK / 2;
+        float4 a4[TA ? 1 : NJ][MB];
+        float4 b4[TB ? NJ : 1][NB];
+        float a1[2][MB], b1[2][NB];
+        if constexpr (!TA) {
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+                    a4[j][mb] = *reinterpret_cast<const float4*>(as + T::r_off(wm0 + mb * 32 + c32, 2 * j + h));
+        }
+        if constexpr (TB) {      // block nb holds columns nb*32 + c32: consecutive lanes read consecutive rows
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    b4[j][nb] = *reinterpret_cast<const float4*>(bs + T::r_off(wn0 + nb * 32 + c32, 2 * j + h));
+        }
+        auto load_step = [&](int st, int slot) {
+            const int k = 8 * (st / 4) + 4 * h + (st % 4);
+            if constexpr (TA) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) a1[slot][mb] = as[k * BM + wm0 + mb * 32 + c32];
+            }
+            if constexpr (!TB) {
+                const float* brow = bs + k * BN + wn0 + NB * c32;
+                if constexpr (NB == 4) {
+                    const float4 v = *reinterpret_cast<const float4*>(brow);
+                    b1[slot][0] = v.x; b1[slot][1] = v.y; b1[slot][2] = v.z; b1[slot][3] = v.w;
+                } else if constexpr (NB == 2) {
+                    const float2 v = *reinterpret_cast<const float2*>(brow);
+                    b1[slot][0] = v.x; b1[slot][1] = v.y;
+                } else {
+                    b1[slot][0] = *brow;
+                }
+            }
+        };
+        auto comp = [](const float4& v, int i) { return (i == 0) ? v.x : (i == 1) ? v.y : (i == 2) ? v.z : v.w; };
+        load_step(0, 0);
+#pragma unroll
+        for (int st = 0; st < NSTEP; ++st) {
+            if (st + 1 < NSTEP) load_step(st + 1, (st + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
+            const int j = st / 4, i = st % 4;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                float av;
+                if constexpr (TA) av = a1[st & 1][mb]; else av = comp(a4[j][mb], i);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    float bv;
+                    if constexpr (TB) bv = comp(b4[j][nb], i); else bv = b1[st & 1][nb];
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[mb][nb], 0, 0, 0);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // ---- main loop --------------------------------------------------------------------------
+    // The interior path addresses operands with 32-bit byte offsets from the tile origin.
+    const int64_t lim = (int64_t)1 << 31;
+    const bool a_small = CONV ? (p.g.H * p.g.W * p.g.C * (p.M / (p.g.OH * p.g.OW) + 1) * 4 < lim)
+                              : ((int64_t)(TA ? BK : BM) * p.lda * 4 < lim);
+    const bool b_small = (int64_t)(TB ? BN : BK) * p.ldb * 4 < lim;
+    const bool interior = VEC && a_small && b_small && (m0 + BM <= p.M) && (n0 + BN <= p.N) &&
+                          ((kend - kbeg) % BK == 0);
+    if (nslices > 0) {
+        if (interior) {
+            // Ring of three LDS stages, transfers two slices ahead.  Each wave waits for its own
+            // transfers of the slice needed next (vmcnt counts them in order), then the barrier makes
+            // everybody's visible and also guarantees nobody still reads the stage refilled next.
+            constexpr int L = APT + BPT;           // transfers per slice per wave
+            init_full();
+            issue_slice(0);
+            if (nslices > 1) {
+                issue_slice(1);
+                dma_wait<L>();
+            } else {
+                dma_wait<0>();
+            }
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            // One trip = three slices, one per LDS stage, so that every LDS address in the loop is a
+            // lane constant plus an immediate (no vector ALU work per slice).
+            auto step = [&](auto stage_c, int s) {
+                constexpr int stage = decltype(stage_c)::value;
+                if (s + 2 < nslices) issue_slice((stage + 2) % 3);
+                compute_slice(stage);
+                if (s + 1 < nslices) {
+                    if (s + 2 < nslices) dma_wait<L>(); else dma_wait<0>();
+                    __builtin_amdgcn_s_barrier();
+                    asm volatile("" ::: "memory");
+                }
+            };
+            int s = 0;
+            for (; s + 3 <= nslices; s += 3) {
+                step(std::integral_constant<int, 0>{}, s);
+                step(std::integral_constant<int, 1>{}, s + 1);
+                step(std::integral_constant<int, 2>{}, s + 2);
+            }
+            if (s < nslices) step(std::integral_constant<int, 0>{}, s);
+            if (s + 1 < nslices) step(std::integral_constant<int, 1>{}, s + 1);
+        } else {
+            // Edge tiles, k tails, unaligned operands: registers -> LDS, two of the three stages.
+            load_slice_edge(kbeg);
+            store_slice(0);
+            __syncthreads();
+            for (int s = 0; s < nslices; ++s) {
+                const bool more = s + 1 < nslices;
+                if (more) load_slice_edge(kbeg + (int64_t)(s + 1) * BK);
+                compute_slice(s & 1);
+                if (more) store_slice((s + 1) & 1);
+                __syncthreads();
+            }
+        }
+    }
+
+    // ---- epilogue ------------------------------------------------------------------------------
+    // accumulator register r of block (mb, nb): row = 32*mb + 8*(r/4) + 4*h + r%4;
+    // column = NB*c32 + nb (interleaved, C-kind B) or nb*32 + c32 (R-kind B)
+    float* Cz = p.C + (int64_t)blockIdx.y * p.M * p.ldc;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t m = m0 + wm0 + mb * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+            if (m >= p.M) continue;
+            float v[NB];
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) v[nb] = acc[mb][nb][r];
+            if constexpr (TB) {
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    const int64_t n = n0 + wn0 + nb * 32 + c32;
+                    float* cp = Cz + m * p.ldc + n;
+                    if (n < p.N) *cp = p.accumulate ? *cp + v[nb] : v[nb];
+                }
+            } else {
+                const int64_t ncol = n0 + wn0 + NB * c32;
+                float* cp = Cz + m * p.ldc + ncol;
+                if constexpr (VEC && NB == 4) {
+                    if (ncol < p.N) {
+                        float4 o = make_float4(v[0], v[1], v[2], v[3]);
+                        if (p.accumulate) {
+                            const float4 c = *reinterpret_cast<const float4*>(cp);
+                            o.x += c.x; o.y += c.y; o.z += c.z; o.w += c.w;
+                        }
+                        *reinterpret_cast<float4*>(cp) = o;
+                    }
+                } else if constexpr (VEC && NB == 2) {
+                    if (ncol < p.N) {
+                        float2 o = make_float2(v[0], v[1]);
+                        if (p.accumulate) {
+                            const float2 c = *reinterpret_cast<const float2*>(cp);
+                            o.x += c.x; o.y += c.y;
+                        }
+                        *reinterpret_cast<float2*>(cp) = o;
+                    }
+                } else {
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+                        if (ncol + nb < p.N) cp[nb] = p.accumulate ? cp[nb] + v[nb] : v[nb];
+                }
+            }
+        }
+    }
+}
+
+// ---- the tile menu and the planner (host) ---------------------------------------------------------
+// All tiles: 4 wavefronts, one per SIMD.  `occ` = workgroups of that tile a CU can hold (LDS and
+// registers), `mfma` = matrix-pipe clocks one k-slice costs one SIMD, `eff` = the measured fraction
+// of the matrix-pipe rate the tile sustains with a full CU (4096^3, clock-normalised).
+using Tile0 = Tile<128, 256, 16, 64, 128, 2>;   // waves of 64x128
+using Tile1 = Tile<128, 128, 16, 32, 128, 4>;   // waves of 32x128
+using Tile2 = Tile<128, 64, 16, 32, 64, 4>;     // waves of 32x64 (narrow outputs, e.g. F = 64)
+using Tile3 = Tile<64, 64, 16, 32, 32, 4>;      // waves of 32x32 (small problems)
+using Tile4 = Tile<64, 128, 32, 32, 64, 4>;     // waves of 32x64, deeper slices (mid-size problems)
+using Tile5 = Tile<64, 64, 32, 32, 32, 4>;      // waves of 32x32, deeper slices
+
+struct TileInfo { int bm, bn, bk, occ, mfma; double eff; };
+constexpr int kNumTiles = 6;
+static const TileInfo kTiles[kNumTiles] = {
+    {128, 256, 16, 2, 4096, 0.935}, {128, 128, 16, 4, 2048, 0.92}, {128, 64, 16, 4, 1024, 0.90},
+    {64, 64, 16, 6, 512, 0.875},    {64, 128, 32, 2, 2048, 0.89},  {64, 64, 32, 3, 1024, 0.87}};
+
+struct Plan {
+    int tile;          // index into kTiles
+    int64_t tiles_m, tiles_n, splits, k_per_split;
+};
+
+constexpr int kCUs = 256;
+constexpr int kKGran = 64;   // split-k slabs are multiples of this (a multiple of every tile's BK)
+
+// Pick (tile, k-split) with a cost model fitted to measurements on this part: when c workgroups
+// share a CU, one k-slice of all of them takes  c * mfma / eff + dead / c  clocks, where `dead`
+// (barrier skew + LDS refill after the barrier, ~350 clocks, more for deeper slices) is only
+// hidden by other workgroups.  The busiest CU decides; a launch costs ~4 us of fill and drain;
+// split-k adds the partial-sum traffic and a second launch.
+inline Plan make_plan(int64_t M, int64_t N, int64_t K) {
+    const double clk = 2.4e9;
+    const int64_t kslabs = cdiv(K, kKGran);
+    static const int split_menu[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
+    Plan best{};
+    double best_cost = 1e300;
+    for (int ti = 0; ti < kNumTiles; ++ti) {
+        const TileInfo& tl = kTiles[ti];
+        const int64_t tm = cdiv(M, tl.bm), tn = cdiv(N, tl.bn);
+        const double dead = 350.0 + 8.0 * (tl.bk - 16);
+        for (int sp : split_menu) {
+            if (sp > 1 && kslabs < 2 * sp) break;                // keep at least 128 k per slab
+            const int64_t kps = cdiv(kslabs, sp) * kKGran;
+            const int64_t splits = cdiv(K, kps);
+            if (splits != sp && sp > 1) continue;                // same plan as a smaller menu entry
+            const int64_t wgs = tm * tn * splits;
+            const double nslices = (double)cdiv(kps < K ? kps : K, tl.bk);
+            const int64_t per_cu = cdiv(wgs, kCUs);              // workgroups on the busiest CU
+            const int64_t full = per_cu / tl.occ, rest = per_cu % tl.occ;
+            double clocks = (double)full * nslices * (tl.occ * tl.mfma / tl.eff + dead / tl.occ);
+            if (rest) clocks += nslices * (rest * tl.mfma / tl.eff + dead / rest);
+            double cost = clocks / clk + 4e-6;
+            if (splits > 1) cost += 2.0 * splits * M * N * 4.0 / 3.0e12 + 5e-6;
+            if (cost < best_cost) {
+                best_cost = cost;
+                best.tile = ti; best.tiles_m = tm; best.tiles_n = tn; best.splits = splits; best.k_per_split = kps;
+            }
+        }
+    }
+    return best;
+}
+
+inline size_t plan_workspace(const Plan& pl, int64_t M, int64_t N) {
+    return pl.splits > 1 ? (size_t)(pl.splits * M * N) * sizeof(float) : 0;
+}
+
+template <class T, bool VEC, bool CONV, bool TA, bool TB>
+static void launch_gemm(const GemmArgs& a, unsigned splits, hipStream_t s) {
+    static bool configured = false;
+    const size_t lds_bytes = T::LDS_FLOATS * sizeof(float);
+    if (!configured) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<T, VEC, CONV, TA, TB>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        configured = true;
+    }
+    hipLaunchKernelGGL((gemm_kernel<T, VEC, CONV, TA, TB>), dim3(a.tiles_m * a.tiles_n, splits), dim3(T::THREADS),
+                       lds_bytes, s, a);
+}
+
+// Launch the planned tile of one operand-layout variant (the split-k combine is the caller's job).
+template <bool CONV, bool TA, bool TB>
+static void launch_planned(const GemmArgs& a, const Plan& pl, bool vec, hipStream_t s) {
+    const unsigned z = (unsigned)pl.splits;
+#define LG_LAUNCH(TILE)                                                        \
+    do {                                                                       \
+        if (vec) launch_gemm<TILE, true, CONV, TA, TB>(a, z, s);               \
+        else     launch_gemm<TILE, false, CONV, TA, TB>(a, z, s);              \
+    } while (0)
+    switch (pl.tile) {
+        case 0: LG_LAUNCH(Tile0); break;
+        case 1: LG_LAUNCH(Tile1); break;
+        case 2: LG_LAUNCH(Tile2); break;
+        case 3: LG_LAUNCH(Tile3); break;
+        case 4: LG_LAUNCH(Tile4); break;
+        default: LG_LAUNCH(Tile5); break;
+    }
+#undef LG_LAUNCH
+}
+
+// Implemented in gemm.hip (AB and convolution) and gemm_t.hip (A^T B, A B^T).
+void launch_nn(const GemmArgs& a, const Plan& pl, bool vec, hipStream_t s);
+void launch_conv(const GemmArgs& a, const Plan& pl, bool vec, hipStream_t s);
+void launch_tn(const GemmArgs& a, const Plan& pl, bool vec, hipStream_t s);
+void launch_nt(const GemmArgs& a, const Plan& pl, bool vec, hipStream_t s);
+
+}  // namespace lg

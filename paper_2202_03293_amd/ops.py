@@ -17,6 +17,7 @@ _SIGNATURES = {
     "lg_status_string": (ctypes.c_char_p, [_int]),
     "lg_conv_out_extent": (_i64, [_i64] * 4),
     "lg_matmul": (_int, [_vp, _vp, _vp] + [_i64] * 6 + [_int, _vp, _sz, _vp]),
+    "lg_matmul_t": (_int, [_vp, _vp, _vp] + [_i64] * 6 + [_int, _int, _int, _vp, _sz, _vp]),
     "lg_matmul_workspace_bytes": (_sz, [_i64] * 3),
     "lg_matmul_plan": (_int, [_i64] * 3 + [ctypes.POINTER(_int)] * 3),
     "lg_conv2d_nhwc_hwcf": (_int, [_vp, _vp, _vp] + [_i64] * 11 + [_int, _vp, _sz, _vp]),
@@ -129,6 +130,18 @@ def lg_matmul(A, B, C, accumulate=False, workspace=None, stream=None):
     wp, wb = _ws(workspace)
     _check("lg_matmul", lib().lg_matmul(_ptr(A), _ptr(B), _ptr(C), M, N, K, _ld(A), _ld(B), _ld(C),
                                         int(accumulate), wp, wb, _stream(stream)))
+    return C
+
+
+def lg_matmul_t(A, B, C, trans_a=False, trans_b=False, accumulate=False, workspace=None, stream=None):
+    """C[M,N] (+)= op(A) @ op(B); A is stored [K,M] when trans_a, B is stored [N,K] when trans_b."""
+    M, N = C.shape
+    K = A.shape[0] if trans_a else A.shape[1]
+    if tuple(A.shape) != ((K, M) if trans_a else (M, K)) or tuple(B.shape) != ((N, K) if trans_b else (K, N)):
+        raise ValueError("matmul shapes do not agree")
+    wp, wb = _ws(workspace)
+    _check("lg_matmul_t", lib().lg_matmul_t(_ptr(A), _ptr(B), _ptr(C), M, N, K, _ld(A), _ld(B), _ld(C),
+                                            int(trans_a), int(trans_b), int(accumulate), wp, wb, _stream(stream)))
     return C
 
 

@@ -56,6 +56,9 @@ def test_argument_validation_without_device(L):
     assert L.lg_matmul(None, P, Q, 4, 4, 4, 4, 4, 4, 0, None, 0, None) == -1
     assert L.lg_matmul(P, P, P, 4, 4, 4, 4, 4, 4, 0, None, 0, None) == -1      # A aliases C
     assert L.lg_matmul(P, P, Q, 0, 4, 4, 4, 4, 4, 0, None, 0, None) == 0       # empty output
+    assert L.lg_matmul_t(P, P, Q, 4, 4, 8, 3, 4, 4, 1, 0, 0, None, 0, None) == -1   # A stored K x M: lda < M
+    assert L.lg_matmul_t(P, P, Q, 4, 4, 8, 4, 4, 4, 0, 1, 0, None, 0, None) == -1   # B stored N x K: ldb < K
+    assert L.lg_matmul_t(P, P, Q, 4, 4, 8, 4, 8, 4, 1, 1, 0, None, 0, None) == -2   # both transposed
     assert L.lg_conv2d_nhwc_hwcf(P, P, Q, 1, 2, 2, 4, 3, 3, 4, 1, 1, 1, 1, 0, None, 0, None) == -1  # window too big
     assert L.lg_conv2d_nhwc_hwcf(P, P, Q, 1, 8, 8, 4, 3, 3, 4, 0, 1, 1, 1, 0, None, 0, None) == -1  # stride 0
     assert L.lg_dwconv1d_nwc_wc(P, P, Q, 1, 8, 4, 3, 1, 0, 0, None) == -1                           # dilation 0

@@ -154,6 +154,66 @@ def test_matmul_full_size_sampled(lg, lgo, case, shape):
     assert bool(torch.isfinite(Cd).all())
 
 
+MATMUL_T_SHAPES = [(1, 1, 1), (5, 7, 3), (64, 64, 64), (130, 70, 50), (256, 256, 256), (300, 520, 136),
+                   (1000, 24, 2000), (1024, 1024, 320), (2048, 1024, 128), (516, 260, 1028), (4100, 4104, 36)]
+
+
+@pytest.mark.parametrize("M,N,K", MATMUL_T_SHAPES)
+@pytest.mark.parametrize("trans", ["a", "b"])
+def test_matmul_transposed_matches_oracle(lg, lgo, M, N, K, trans):
+    A, B = si.matmul_inputs(116, M, N, K)
+    ta, tb = trans == "a", trans == "b"
+    As = np.ascontiguousarray(A.T) if ta else A          # stored K x M
+    Bs = np.ascontiguousarray(B.T) if tb else B          # stored N x K
+    out = Guarded((M, N), init=np.full((M, N), np.nan, np.float32))
+    ws = workspace(lg.lg_matmul_workspace_bytes(M, N, K))
+    lg.lg_matmul_t(dev(As), dev(Bs), out.t, trans_a=ta, trans_b=tb, workspace=ws)
+    sync(); out.check()
+    assert_close(out.host(), lgo.matmul_t(As, Bs, trans_a=ta, trans_b=tb), K, f"matmul_t {trans} {M}x{N}x{K}")
+
+
+def test_matmul_transposed_accumulate_ld_exact(lg, lgo):
+    M, N, K = 136, 200, 72
+    A, B = si.matmul_inputs(117, M, N, K)
+    C0 = si.uniform(117, 7, (M, N), -1, 1)
+    for ta, tb in [(True, False), (False, True)]:
+        As = np.ascontiguousarray(A.T) if ta else A
+        Bs = np.ascontiguousarray(B.T) if tb else B
+        ref = C0.copy(); lgo.matmul_t(As, Bs, trans_a=ta, trans_b=tb, C=ref, accumulate=True)
+        for pad in (4, 3):        # aligned and odd leading dimensions
+            Ad = torch.full((As.shape[0], As.shape[1] + pad), float("nan"), device="cuda"); Ad[:, :As.shape[1]] = dev(As)
+            Bd = torch.full((Bs.shape[0], Bs.shape[1] + pad), float("nan"), device="cuda"); Bd[:, :Bs.shape[1]] = dev(Bs)
+            Cd = torch.full((M, N + pad), 7.0, device="cuda"); Cd[:, :N] = dev(C0)
+            lg.lg_matmul_t(Ad[:, :As.shape[1]], Bd[:, :Bs.shape[1]], Cd[:, :N], trans_a=ta, trans_b=tb, accumulate=True,
+                           workspace=workspace(lg.lg_matmul_workspace_bytes(M, N, K)))
+            sync()
+            Ch = Cd.cpu().numpy()
+            assert_close(Ch[:, :N], ref, K, "matmul_t accumulate/ld")
+            assert np.all(Ch[:, N:] == 7.0)
+    # integer-valued operands: exact in any order
+    Ai = si.small_integers(118, 0, (96, 200)); Bi = si.small_integers(118, 1, (96, 136))      # A stored K x M
+    out = Guarded((200, 136)); lg.lg_matmul_t(dev(Ai), dev(Bi), out.t, trans_a=True); sync(); out.check()
+    assert np.array_equal(out.host(), lgo.matmul_t(Ai, Bi, trans_a=True))
+    with pytest.raises(lg.LgError) as e:
+        lg.lg_matmul_t(dev(Ai), dev(Bi.T.copy()), out.t, trans_a=True, trans_b=True)
+    assert e.value.status == -2
+
+
+def test_matmul_transposed_full_size_sampled(lg, lgo):
+    M = N = K = 4096
+    A, B = si.matmul_inputs(2, M, N, K, case=1)
+    for ta, tb in [(True, False), (False, True)]:
+        As = np.ascontiguousarray(A.T) if ta else A
+        Bs = np.ascontiguousarray(B.T) if tb else B
+        Cd = torch.full((M, N), float("nan"), device="cuda")
+        lg.lg_matmul_t(dev(As), dev(Bs), Cd, trans_a=ta, trans_b=tb, workspace=workspace(lg.lg_matmul_workspace_bytes(M, N, K)))
+        sync()
+        for r0 in (0, 252, M - 8):
+            ref = lgo.matmul(np.ascontiguousarray(A[r0:r0 + 8]), B)
+            assert_close(Cd[r0:r0 + 8].cpu().numpy(), ref, K, f"matmul_t full rows {r0}")
+        assert bool(torch.isfinite(Cd).all())
+
+
 # ------------------------------------------------------------------------------- conv2d
 
 def run_conv(lg, I, Kf, stride=(1, 1), dilation=(1, 1), O0=None, accumulate=False):

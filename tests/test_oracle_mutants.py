@@ -22,6 +22,11 @@ MUTANTS = [
     ("lgo_matmul", "(double)A[m * lda + k]", "(double)A[(M - 1 - m) * lda + k]"),
     ("lgo_matmul", "if (accumulate) s += (double)C[m * ldc + n];", "if (accumulate) s -= (double)C[m * ldc + n];"),
     ("lgo_matmul", "double s = 0.0;", "float s = 0.0f;"),
+    ("lgo_matmul_t", "double a = transA ? (double)A[k * lda + m] : (double)A[m * lda + k];",
+     "double a = transA ? (double)A[k * lda + (M - 1 - m)] : (double)A[m * lda + k];"),
+    ("lgo_matmul_t", "double b = transB ? (double)B[n * ldb + k] : (double)B[k * ldb + n];",
+     "double b = transB ? (double)B[(N - 1 - n) * ldb + k] : (double)B[k * ldb + n];"),
+    ("lgo_matmul_t", "for (int64_t k = 0; k < K; ++k) {", "for (int64_t k = 0; k + 1 < K; ++k) {"),
     ("lgo_conv_out_extent", "return (in - span) / s + 1;", "return (in - span) / s;"),
     ("lgo_conv2d_nhwc_hwcf", "Kf[((kh * KW + kw) * C + c) * F + f]", "Kf[(((KH - 1 - kh) * KW + kw) * C + c) * F + f]"),
     ("lgo_conv2d_nhwc_hwcf", "Kf[((kh * KW + kw) * C + c) * F + f]", "Kf[((kw * KH + kh) * C + c) * F + f]"),

@@ -144,6 +144,36 @@ def test_matmul_linearity_power_of_two(lgo):
     assert np.array_equal(bits(lgo.matmul(A * np.float32(4), B)), bits(lgo.matmul(A, B) * np.float32(4)))
 
 
+def test_matmul_transposed_operands(lgo):
+    # hand literal: A stored K x M = [[1,2],[3,4],[5,6]] (K=3, M=2), B stored K x N = [[1,0],[0,1],[1,1]]
+    At = np.array([[1, 2], [3, 4], [5, 6]], np.float32)
+    B = np.array([[1, 0], [0, 1], [1, 1]], np.float32)
+    # C[m,n] = sum_k At[k,m] B[k,n]: row0 = [1+5, 3+5], row1 = [2+6, 4+6]
+    assert lgo.matmul_t(At, B, trans_a=True).tolist() == [[6, 8], [8, 10]]
+    # A stored M x K = [[1,2,3]], B stored N x K = [[4,5,6],[7,8,9]] : C = [[32, 50]]
+    assert lgo.matmul_t(np.array([[1, 2, 3]], np.float32), np.array([[4, 5, 6], [7, 8, 9]], np.float32),
+                        trans_b=True).tolist() == [[32, 50]]
+    # Section 4.6.1: the transposed variants are the plain product after a transpose -> bit-exact
+    M, N, K = 13, 9, 21
+    A, B = si.matmul_inputs(25, M, N, K)
+    ref = lgo.matmul(A, B)
+    assert np.array_equal(bits(lgo.matmul_t(lgo.transpose(A), B, trans_a=True)), bits(ref))
+    assert np.array_equal(bits(lgo.matmul_t(A, lgo.transpose(B), trans_b=True)), bits(ref))
+    assert np.array_equal(bits(lgo.matmul_t(A, B)), bits(ref))
+    assert_half_ulp(lgo.matmul_t(lgo.transpose(A), B, trans_a=True), A.astype(np.float64) @ B.astype(np.float64))
+    # accumulate and leading dimensions
+    C0 = si.uniform(25, 9, (M, N), -1, 1)
+    C = C0.copy()
+    lgo.matmul_t(A, lgo.transpose(B), trans_b=True, C=C, accumulate=True)
+    assert_half_ulp(C, A.astype(np.float64) @ B.astype(np.float64) + C0)
+    Atp = np.full((K, M + 3), np.nan, np.float32); Atp[:, :M] = A.T
+    Cp = np.full((M, N + 1), 7.0, np.float32)
+    rc = lgo.lib().lgo_matmul_t(lgo._p(Atp), lgo._p(B), lgo._p(Cp), M, N, K, M + 3, N, N + 1, 1, 0, 0)
+    assert rc == 0 and np.array_equal(bits(Cp[:, :N]), bits(ref)) and np.all(Cp[:, N:] == 7.0)
+    assert lgo.lib().lgo_matmul_t(lgo._p(Atp), lgo._p(B), lgo._p(Cp), M, N, K, M - 1, N, N + 1, 1, 0, 0) == -1
+    assert lgo.lib().lgo_matmul_t(lgo._p(Atp), lgo._p(B), lgo._p(Cp), M, N, K, M + 3, N, N + 1, 1, 1, 0) == -1
+
+
 # --------------------------------------------------------------------------- conv2d
 
 def test_conv_out_extent_closed_forms(lgo):
