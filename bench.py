@@ -142,6 +142,17 @@ def main():
                           nbytes=4.0 * (touched_in + KH * KW * C * F + N * OH * OW * F),
                           kernel="conv_" + gemm_kernel_name(N * OH * OW, F, KH * KW * C)))
 
+    # the transposed-operand variants of the 4096^3 product (Section 4.6.1: A^T B, A B^T)
+    Mt = Nt = Kt = 4096
+    At_h, Bt_h = si.matmul_inputs(2, Mt, Nt, Kt, case=5)
+    At_d = dev(np.ascontiguousarray(At_h.T))            # stored K x M
+    Bn_d = dev(Bt_h)
+    An_d = dev(At_h)
+    Bt_d = dev(np.ascontiguousarray(Bt_h.T))            # stored N x K
+    Ct_d = torch.zeros((Mt, Nt), device="cuda")
+    wt = ws(lg.lg_matmul_workspace_bytes(Mt, Nt, Kt))
+    del At_h, Bt_h
+
     def add_mm(shape):
         d = mm[shape]
         add(d["name"], d["call"], d["flops"], d["nbytes"], "mfma", d["kernel"])
@@ -168,6 +179,10 @@ def main():
     add("reduce_cols_4096x16384", lambda: lg.lg_reduce_cols(x_cols, out_cols, workspace=ws_cols), R * Cn,
         4.0 * (R * Cn + Cn), "hbm", "reduce_cols")
     add_mm((8192, 8192, 8192))
+    add("matmul_AtB_4096x4096x4096", lambda: lg.lg_matmul_t(At_d, Bn_d, Ct_d, trans_a=True, workspace=wt),
+        2.0 * Mt * Nt * Kt, 12.0 * Mt * Nt, "mfma", gemm_kernel_name(Mt, Nt, Kt) + "_tn")
+    add("matmul_ABt_4096x4096x4096", lambda: lg.lg_matmul_t(An_d, Bt_d, Ct_d, trans_b=True, workspace=wt),
+        2.0 * Mt * Nt * Kt, 12.0 * Mt * Nt, "mfma", gemm_kernel_name(Mt, Nt, Kt) + "_nt")
     add_mm((1024, 1024, 1024))
     add_mm((4096, 4096, 64))
 
@@ -226,7 +241,7 @@ def main():
                ms_per_step=ms_per_step, higher_is_better=True, scaling="weak", vs_baseline=None,
                dtype="f32", data="synthetic",
                config=dict(workload="configs[1..4]: reduce_rows/cols 4096x16384, transpose (+copy) 8192^2, matmul sweep "
-                                    "(1024^3, 4096^3, 8192^3, 16384x512x2048, 4096x4096x64), conv2d x3, "
+                                    "(1024^3, 4096^3, 8192^3, 16384x512x2048, 4096x4096x64; A^T B and A B^T at 4096^3), conv2d x3, "
                                     "dwconv1d, dwconv2d; one launch of each per step"),
                frac_mfma_peak=value * 1e9 / MFMA_FP32_PEAK, roofline=roofline, ops=per_op)
 

@@ -113,6 +113,21 @@ size_t lg_conv2d_workspace_bytes(int64_t N, int64_t H, int64_t W, int64_t C,
                                  int64_t KH, int64_t KW, int64_t F,
                                  int64_t SH, int64_t SW, int64_t DH, int64_t DW);
 
+/*
+ * 1-D convolution, Section 3 (the running example) and Section 4.6.2 equation (1-D), NWC input,
+ * WCF filter:
+ *     O[n,w,f] (+)= sum_{kw,c} I[n, w*SW + kw*DW, c] * Kf[kw,c,f]
+ * I dense [N,W,C], Kf dense [KW,C,F], O dense [N,OW,F] with the same "valid" OW as above.
+ * Arguments, workspace and errors as for lg_conv2d_nhwc_hwcf, of which this is the case
+ * H = KH = 1 (the same kernel runs it).
+ */
+int lg_conv1d_nwc_wcf(const float *I, const float *Kf, float *O,
+                      int64_t N, int64_t W, int64_t C, int64_t KW, int64_t F,
+                      int64_t SW, int64_t DW,
+                      int accumulate, void *workspace, size_t workspace_bytes, void *stream);
+size_t lg_conv1d_workspace_bytes(int64_t N, int64_t W, int64_t C, int64_t KW, int64_t F,
+                                 int64_t SW, int64_t DW);
+
 /* Output extent used above for one spatial dimension; 0 when the window does not fit. */
 int64_t lg_conv_out_extent(int64_t in, int64_t k, int64_t stride, int64_t dilation);
 
@@ -163,6 +178,22 @@ int lg_transpose(const float *in, float *out, int64_t R, int64_t Cn,
  */
 int lg_copy2d(const float *in, float *out, int64_t R, int64_t Cn,
               int64_t ld_in, int64_t ld_out, void *stream);
+
+/*
+ * Batched 2-D transpose, Section 4.4: a transpose of more than two dimensions is a set of 2-D
+ * transposes at various places in the tensor (the paper's example: [i,j,k,l] -> [k,j,l,i] is
+ * j x k transposes of an i x l matrix).  For every b0 < B0, b1 < B1, i < R, j < Cn:
+ *     out[b0*out_stride0 + b1*out_stride1 + j*ld_out + i] =
+ *      in[b0*in_stride0  + b1*in_stride1  + i*ld_in  + j]
+ * All strides in elements, >= 0; ld_in >= Cn, ld_out >= R.  B0, B1 <= 65535.  One launch.
+ * Bit-exact data movement.  The output slices of different batches must not overlap each
+ * other (not checked); in and out as a whole must not overlap (checked).
+ */
+int lg_transpose_batched(const float *in, float *out, int64_t R, int64_t Cn,
+                         int64_t ld_in, int64_t ld_out,
+                         int64_t B0, int64_t B1,
+                         int64_t in_stride0, int64_t in_stride1,
+                         int64_t out_stride0, int64_t out_stride1, void *stream);
 
 #ifdef __cplusplus
 }

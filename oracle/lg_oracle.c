@@ -155,6 +155,38 @@ int lgo_conv2d_nhwc_hwcf(const float *I, const float *Kf, float *O,
     return LGO_OK;
 }
 
+/* Section 3 (running example) and Section 4.6.2, equation (1-D):
+ *   O[n,w,f] = sum_{kw,c} I[n, w*SW + kw*DW, c] * K[kw,c,f]
+ * I is [N,W,C], K is [KW,C,F], O is [N,OW,F], all contiguous. */
+int lgo_conv1d_nwc_wcf(const float *I, const float *Kf, float *O,
+                       int64_t N, int64_t W, int64_t C, int64_t KW, int64_t F,
+                       int64_t SW, int64_t DW, int accumulate)
+{
+    if (N < 0 || W < 0 || C < 0 || KW < 1 || F < 0) return LGO_ERR_INVALID_ARG;
+    if (SW < 1 || DW < 1) return LGO_ERR_INVALID_ARG;
+    if (N == 0 || F == 0) return LGO_OK;
+    int64_t OW = lgo_conv_out_extent(W, KW, SW, DW);
+    if (OW == 0) return LGO_ERR_INVALID_ARG;
+    if (!O || (C > 0 && (!I || !Kf))) return LGO_ERR_INVALID_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t w = 0; w < OW; ++w) {
+            for (int64_t f = 0; f < F; ++f) {
+                double s = 0.0;
+                for (int64_t kw = 0; kw < KW; ++kw)
+                    for (int64_t c = 0; c < C; ++c) {
+                        int64_t x = w * SW + kw * DW;
+                        s += (double)I[(n * W + x) * C + c] * (double)Kf[(kw * C + c) * F + f];
+                    }
+                int64_t o = (n * OW + w) * F + f;
+                if (accumulate) s += (double)O[o];
+                O[o] = (float)s;
+            }
+        }
+    }
+    return LGO_OK;
+}
+
 /* Section 4.6.2 asks for conv against an independent formulation: materialise
  * the window matrix col[(n,h,w),(kh,kw,c)] = I[n,h*SH+kh*DH,w*SW+kw*DW,c]
  * explicitly; the caller then multiplies it with K viewed as [KH*KW*C, F]
@@ -301,6 +333,26 @@ int lgo_transpose(const float *in, float *out, int64_t R, int64_t Cn,
     for (int64_t i = 0; i < R; ++i)
         for (int64_t j = 0; j < Cn; ++j)
             memcpy(&out[j * ld_out + i], &in[i * ld_in + j], sizeof(float));
+    return LGO_OK;
+}
+
+/* Section 4.4: a transpose of more than two dimensions written as B0 x B1 2-D
+ * transposes placed by element strides,
+ *   out[b0*os0 + b1*os1 + j*ld_out + i] = in[b0*is0 + b1*is1 + i*ld_in + j]. */
+int lgo_transpose_batched(const float *in, float *out, int64_t R, int64_t Cn,
+                          int64_t ld_in, int64_t ld_out, int64_t B0, int64_t B1,
+                          int64_t is0, int64_t is1, int64_t os0, int64_t os1)
+{
+    if (R < 0 || Cn < 0 || B0 < 0 || B1 < 0 || ld_in < Cn || ld_out < R) return LGO_ERR_INVALID_ARG;
+    if (is0 < 0 || is1 < 0 || os0 < 0 || os1 < 0) return LGO_ERR_INVALID_ARG;
+    if (R == 0 || Cn == 0 || B0 == 0 || B1 == 0) return LGO_OK;
+    if (!in || !out) return LGO_ERR_INVALID_ARG;
+    for (int64_t b0 = 0; b0 < B0; ++b0)
+        for (int64_t b1 = 0; b1 < B1; ++b1)
+            for (int64_t i = 0; i < R; ++i)
+                for (int64_t j = 0; j < Cn; ++j)
+                    memcpy(&out[b0 * os0 + b1 * os1 + j * ld_out + i],
+                           &in[b0 * is0 + b1 * is1 + i * ld_in + j], sizeof(float));
     return LGO_OK;
 }
 

@@ -41,12 +41,14 @@ class Oracle:
         L.lgo_matmul.argtypes = [_fp, _fp, _fp] + [_i64] * 6 + [ctypes.c_int]
         L.lgo_matmul_t.argtypes = [_fp, _fp, _fp] + [_i64] * 6 + [ctypes.c_int] * 3
         L.lgo_conv2d_nhwc_hwcf.argtypes = [_fp, _fp, _fp] + [_i64] * 11 + [ctypes.c_int]
+        L.lgo_conv1d_nwc_wcf.argtypes = [_fp, _fp, _fp] + [_i64] * 7 + [ctypes.c_int]
         L.lgo_im2col_nhwc.argtypes = [_fp, _fp] + [_i64] * 10
         L.lgo_dwconv1d_nwc_wc.argtypes = [_fp, _fp, _fp] + [_i64] * 6 + [ctypes.c_int]
         L.lgo_dwconv2d_nhwc_hwc.argtypes = [_fp, _fp, _fp] + [_i64] * 10 + [ctypes.c_int]
         L.lgo_reduce_rows.argtypes = [_fp, _fp] + [_i64] * 3 + [ctypes.c_int]
         L.lgo_reduce_cols.argtypes = [_fp, _fp] + [_i64] * 3 + [ctypes.c_int]
         L.lgo_transpose.argtypes = [_fp, _fp] + [_i64] * 4
+        L.lgo_transpose_batched.argtypes = [_fp, _fp] + [_i64] * 10
         L.lgo_copy2d.argtypes = [_fp, _fp] + [_i64] * 4
         self._lib = L
 
@@ -100,6 +102,19 @@ class Oracle:
                                           int(accumulate)), "conv2d_nhwc_hwcf")
         return O
 
+
+    def conv1d_nwc_wcf(self, I, Kf, O=None, stride=1, dilation=1, accumulate=False):
+        N, W, C = I.shape
+        KW, C2, F = Kf.shape
+        assert C == C2
+        OW = self.conv_out_extent(W, KW, stride, dilation)
+        if O is None:
+            assert not accumulate
+            O = np.empty((N, OW, F), np.float32)
+        assert O.shape == (N, OW, F)
+        _check(self._lib.lgo_conv1d_nwc_wcf(_p(I), _p(Kf), _p(O), N, W, C, KW, F, stride, dilation,
+                                            int(accumulate)), "conv1d_nwc_wcf")
+        return O
 
     def im2col_nhwc(self, I, KH, KW, stride=(1, 1), dilation=(1, 1)):
         N, H, W, C = I.shape
@@ -167,6 +182,16 @@ class Oracle:
         _check(self._lib.lgo_transpose(_p(x), _p(out), R, Cn, Cn, R), "transpose")
         return out
 
+
+    def transpose_batched(self, x, out, R, Cn, ld_in, ld_out, B0, B1, is0, is1, os0, os1):
+        """x and out are flat float32 arrays; writes into out and returns it."""
+        assert x.ndim == 1 and out.ndim == 1
+        if R and Cn and B0 and B1:
+            assert (B0 - 1) * is0 + (B1 - 1) * is1 + (R - 1) * ld_in + Cn <= x.size
+            assert (B0 - 1) * os0 + (B1 - 1) * os1 + (Cn - 1) * ld_out + R <= out.size
+        _check(self._lib.lgo_transpose_batched(_p(x), _p(out), R, Cn, ld_in, ld_out, B0, B1,
+                                               is0, is1, os0, os1), "transpose_batched")
+        return out
 
     def copy2d(self, x):
         R, Cn = x.shape

@@ -140,6 +140,36 @@ __global__ __launch_bounds__(kDThreads) void dwconv_general_kernel(
     O[idx] = s;
 }
 
+// General depthwise kernel for C % 4 == 0: one output position x 4 channels per lane, any filter
+// size, stride and dilation (the paper sweeps strides and dilations 1 and 2, Section 4.7).  Taps
+// are read through L1/L2; neighbouring lanes share them.
+__global__ __launch_bounds__(kDThreads) void dwconv_general_vec4_kernel(
+    const float* __restrict__ I, const float* __restrict__ Kf, float* __restrict__ O,
+    int64_t N, int64_t H, int64_t W, int64_t C, int64_t KH, int64_t KW,
+    int64_t SH, int64_t SW, int64_t DH, int64_t DW, int64_t OH, int64_t OW, int accumulate) {
+    const int64_t C4 = C / 4;
+    const int64_t total = N * OH * OW * C4;
+    const int64_t idx = (int64_t)blockIdx.x * kDThreads + threadIdx.x;
+    if (idx >= total) return;
+    const int64_t c4 = idx % C4;
+    const int64_t w = (idx / C4) % OW;
+    const int64_t h = (idx / (C4 * OW)) % OH;
+    const int64_t n = idx / (C4 * OW * OH);
+    const float* ip = I + ((n * H + h * SH) * W + w * SW) * C + 4 * c4;
+    const float* kp = Kf + 4 * c4;
+    float4 s = make_float4(0, 0, 0, 0);
+    for (int64_t a = 0; a < KH; ++a)
+        for (int64_t b = 0; b < KW; ++b)
+            s = fma4(*reinterpret_cast<const float4*>(ip + (a * DH * W + b * DW) * C),
+                     *reinterpret_cast<const float4*>(kp + (a * KW + b) * C), s);
+    float* q = O + 4 * idx;
+    if (accumulate) {
+        const float4 acc = *reinterpret_cast<const float4*>(q);
+        s.x += acc.x; s.y += acc.y; s.z += acc.z; s.w += acc.w;
+    }
+    store_stream4(q, s);
+}
+
 static int dwconv_dispatch(const float* I, const float* Kf, float* O,
                            int64_t N, int64_t H, int64_t W, int64_t C, int64_t KH, int64_t KW,
                            int64_t SH, int64_t SW, int64_t DH, int64_t DW, int accumulate, void* stream) {
@@ -173,6 +203,13 @@ static int dwconv_dispatch(const float* I, const float* Kf, float* O,
         if (blocks > kMaxGrid) return LG_ERR_UNSUPPORTED;
         hipLaunchKernelGGL((dwconv2d_s1_kernel<3, 3, TH, TW>), dim3((unsigned)blocks), dim3(kDThreads), 0, s,
                            I, Kf, O, N, H, W, C, OH, OW, accumulate);
+        return launch_status();
+    }
+    if (vec) {
+        const int64_t blocks4 = cdiv(out_elems / 4, kDThreads);
+        if (blocks4 > kMaxGrid) return LG_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(dwconv_general_vec4_kernel, dim3((unsigned)blocks4), dim3(kDThreads), 0, s,
+                           I, Kf, O, N, H, W, C, KH, KW, SH, SW, DH, DW, OH, OW, accumulate);
         return launch_status();
     }
     const int64_t blocks = cdiv(out_elems, kDThreads);

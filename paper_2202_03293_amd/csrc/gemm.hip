@@ -183,3 +183,16 @@ extern "C" int lg_conv2d_nhwc_hwcf(const float* I, const float* Kf, float* O,
     a.g = ConvGeom{H, W, C, KW, SH, SW, DH, DW, OH, OW};
     return run_gemm(a, Layout::CONV, vec, accumulate, workspace, workspace_bytes, s);
 }
+
+extern "C" size_t lg_conv1d_workspace_bytes(int64_t N, int64_t W, int64_t C, int64_t KW, int64_t F,
+                                            int64_t SW, int64_t DW) {
+    return lg_conv2d_workspace_bytes(N, 1, W, C, 1, KW, F, 1, SW, 1, DW);
+}
+
+extern "C" int lg_conv1d_nwc_wcf(const float* I, const float* Kf, float* O,
+                                 int64_t N, int64_t W, int64_t C, int64_t KW, int64_t F,
+                                 int64_t SW, int64_t DW,
+                                 int accumulate, void* workspace, size_t workspace_bytes, void* stream) {
+    return lg_conv2d_nhwc_hwcf(I, Kf, O, N, 1, W, C, 1, KW, F, 1, SW, 1, DW, accumulate, workspace,
+                               workspace_bytes, stream);
+}

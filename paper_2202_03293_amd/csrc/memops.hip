@@ -56,12 +56,17 @@ __global__ __launch_bounds__(kCopyThreads) void copy2d_kernel(
 // differ in both row and column block: their strided accesses then do not pile onto the same
 // memory channels.  The XCD-contiguous id order is deliberately NOT used here (measured slower:
 // nothing is shared between tiles, and spreading neighbours over all L2s is what helps).
+// element offsets of batch (b0, b1): b0 * in0 + b1 * in1 into the input, likewise the output
+struct BatchStrides { int64_t in0, in1, out0, out1; };
+
 template <int TS, int THREADS, bool VEC>
 __global__ __launch_bounds__(THREADS) void transpose_kernel(
     const uint32_t* __restrict__ in, uint32_t* __restrict__ out,
-    int64_t R, int64_t Cn, int64_t ld_in, int64_t ld_out, unsigned tiles_j) {
+    int64_t R, int64_t Cn, int64_t ld_in, int64_t ld_out, unsigned tiles_j, BatchStrides bs) {
     extern __shared__ uint32_t tile[];              // [TS][TS + 1]
     constexpr int S = TS + 1;
+    in += blockIdx.z * bs.in0 + blockIdx.y * bs.in1;      // batch (b0, b1) = (blockIdx.z, blockIdx.y)
+    out += blockIdx.z * bs.out0 + blockIdx.y * bs.out1;
     const unsigned ti = blockIdx.x / tiles_j;
     const unsigned tj = (blockIdx.x % tiles_j + ti) % tiles_j;
     const int64_t i0 = (int64_t)ti * TS;            // first input row of the tile
@@ -122,9 +127,9 @@ __global__ __launch_bounds__(THREADS) void transpose_kernel(
 
 template <int TS, int THREADS, bool VEC>
 static int launch_transpose(const uint32_t* in, uint32_t* out, int64_t R, int64_t Cn,
-                            int64_t ld_in, int64_t ld_out, hipStream_t s) {
+                            int64_t ld_in, int64_t ld_out, int64_t B0, int64_t B1, BatchStrides bs, hipStream_t s) {
     const int64_t ti = cdiv(R, TS), tj = cdiv(Cn, TS);
-    if (ti * tj > kMaxGrid) return LG_ERR_UNSUPPORTED;
+    if (ti * tj > kMaxGrid || B0 > 65535 || B1 > 65535) return LG_ERR_UNSUPPORTED;
     constexpr size_t lds = (size_t)TS * (TS + 1) * sizeof(uint32_t);
     static bool configured = false;
     if (!configured) {
@@ -132,8 +137,8 @@ static int launch_transpose(const uint32_t* in, uint32_t* out, int64_t R, int64_
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         configured = true;
     }
-    hipLaunchKernelGGL((transpose_kernel<TS, THREADS, VEC>), dim3((unsigned)(ti * tj)), dim3(THREADS), lds, s,
-                       in, out, R, Cn, ld_in, ld_out, (unsigned)tj);
+    hipLaunchKernelGGL((transpose_kernel<TS, THREADS, VEC>), dim3((unsigned)(ti * tj), (unsigned)B1, (unsigned)B0),
+                       dim3(THREADS), lds, s, in, out, R, Cn, ld_in, ld_out, (unsigned)tj, bs);
     return launch_status();
 }
 
@@ -161,6 +166,22 @@ extern "C" int lg_copy2d(const float* in, float* out, int64_t R, int64_t Cn,
     return launch_status();
 }
 
+namespace lg {
+
+static int transpose_dispatch(const float* in, float* out, int64_t R, int64_t Cn, int64_t ld_in, int64_t ld_out,
+                              int64_t B0, int64_t B1, BatchStrides bs, bool vec, void* stream) {
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    auto* i32 = reinterpret_cast<const uint32_t*>(in);
+    auto* o32 = reinterpret_cast<uint32_t*>(out);
+    // 128x128 tiles once they still give every CU several workgroups, 64x64 below that
+    const bool big = cdiv(R, 128) * cdiv(Cn, 128) * B0 * B1 >= 1024 && R >= 128 && Cn >= 128;
+    if (vec && big) return launch_transpose<128, 1024, true>(i32, o32, R, Cn, ld_in, ld_out, B0, B1, bs, s);
+    if (vec)        return launch_transpose<64, 256, true>(i32, o32, R, Cn, ld_in, ld_out, B0, B1, bs, s);
+    return launch_transpose<64, 256, false>(i32, o32, R, Cn, ld_in, ld_out, B0, B1, bs, s);
+}
+
+}  // namespace lg
+
 extern "C" int lg_transpose(const float* in, float* out, int64_t R, int64_t Cn,
                             int64_t ld_in, int64_t ld_out, void* stream) {
     using namespace lg;
@@ -170,12 +191,25 @@ extern "C" int lg_transpose(const float* in, float* out, int64_t R, int64_t Cn,
     if (overlaps(in, ((R - 1) * ld_in + Cn) * 4, out, ((Cn - 1) * ld_out + R) * 4)) return LG_ERR_INVALID_ARG;
     const bool vec = (Cn % 4 == 0) && (R % 4 == 0) && (ld_in % 4 == 0) && (ld_out % 4 == 0) &&
                      aligned16(in) && aligned16(out);
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    auto* i32 = reinterpret_cast<const uint32_t*>(in);
-    auto* o32 = reinterpret_cast<uint32_t*>(out);
-    // 128x128 tiles once they still give every CU several workgroups, 64x64 below that
-    const bool big = cdiv(R, 128) * cdiv(Cn, 128) >= 1024;
-    if (vec && big) return launch_transpose<128, 1024, true>(i32, o32, R, Cn, ld_in, ld_out, s);
-    if (vec)        return launch_transpose<64, 256, true>(i32, o32, R, Cn, ld_in, ld_out, s);
-    return launch_transpose<64, 256, false>(i32, o32, R, Cn, ld_in, ld_out, s);
+    return transpose_dispatch(in, out, R, Cn, ld_in, ld_out, 1, 1, BatchStrides{0, 0, 0, 0}, vec, stream);
+}
+
+extern "C" int lg_transpose_batched(const float* in, float* out, int64_t R, int64_t Cn,
+                                    int64_t ld_in, int64_t ld_out,
+                                    int64_t B0, int64_t B1,
+                                    int64_t in_stride0, int64_t in_stride1,
+                                    int64_t out_stride0, int64_t out_stride1, void* stream) {
+    using namespace lg;
+    if (R < 0 || Cn < 0 || B0 < 0 || B1 < 0 || ld_in < Cn || ld_out < R) return LG_ERR_INVALID_ARG;
+    if (in_stride0 < 0 || in_stride1 < 0 || out_stride0 < 0 || out_stride1 < 0) return LG_ERR_INVALID_ARG;
+    if (R == 0 || Cn == 0 || B0 == 0 || B1 == 0) return LG_OK;
+    if (!in || !out) return LG_ERR_INVALID_ARG;
+    const int64_t in_span = (B0 - 1) * in_stride0 + (B1 - 1) * in_stride1 + (R - 1) * ld_in + Cn;
+    const int64_t out_span = (B0 - 1) * out_stride0 + (B1 - 1) * out_stride1 + (Cn - 1) * ld_out + R;
+    if (overlaps(in, in_span * 4, out, out_span * 4)) return LG_ERR_INVALID_ARG;
+    const bool vec = (Cn % 4 == 0) && (R % 4 == 0) && (ld_in % 4 == 0) && (ld_out % 4 == 0) &&
+                     (in_stride0 % 4 == 0) && (in_stride1 % 4 == 0) && (out_stride0 % 4 == 0) &&
+                     (out_stride1 % 4 == 0) && aligned16(in) && aligned16(out);
+    return transpose_dispatch(in, out, R, Cn, ld_in, ld_out, B0, B1,
+                              BatchStrides{in_stride0, in_stride1, out_stride0, out_stride1}, vec, stream);
 }

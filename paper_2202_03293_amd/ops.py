@@ -22,12 +22,15 @@ _SIGNATURES = {
     "lg_matmul_plan": (_int, [_i64] * 3 + [ctypes.POINTER(_int)] * 3),
     "lg_conv2d_nhwc_hwcf": (_int, [_vp, _vp, _vp] + [_i64] * 11 + [_int, _vp, _sz, _vp]),
     "lg_conv2d_workspace_bytes": (_sz, [_i64] * 11),
+    "lg_conv1d_nwc_wcf": (_int, [_vp, _vp, _vp] + [_i64] * 7 + [_int, _vp, _sz, _vp]),
+    "lg_conv1d_workspace_bytes": (_sz, [_i64] * 7),
     "lg_dwconv1d_nwc_wc": (_int, [_vp, _vp, _vp] + [_i64] * 6 + [_int, _vp]),
     "lg_dwconv2d_nhwc_hwc": (_int, [_vp, _vp, _vp] + [_i64] * 10 + [_int, _vp]),
     "lg_reduce_rows": (_int, [_vp, _vp] + [_i64] * 3 + [_int, _vp]),
     "lg_reduce_cols": (_int, [_vp, _vp] + [_i64] * 3 + [_int, _vp, _sz, _vp]),
     "lg_reduce_cols_workspace_bytes": (_sz, [_i64] * 2),
     "lg_transpose": (_int, [_vp, _vp] + [_i64] * 4 + [_vp]),
+    "lg_transpose_batched": (_int, [_vp, _vp] + [_i64] * 10 + [_vp]),
     "lg_copy2d": (_int, [_vp, _vp] + [_i64] * 4 + [_vp]),
 }
 
@@ -90,7 +93,7 @@ def _ld(t):
 
 def _dense(t):
     if not t.is_contiguous():
-        raise ValueError("convolution operands must be dense")
+        raise ValueError("operands of this op must be dense (contiguous)")
 
 
 def _check(name, status):
@@ -170,6 +173,28 @@ def lg_conv2d_nhwc_hwcf(I, Kf, O, stride=(1, 1), dilation=(1, 1), accumulate=Fal
     return O
 
 
+def lg_conv1d_workspace_bytes(N, W, C, KW, F, SW=1, DW=1):
+    return lib().lg_conv1d_workspace_bytes(N, W, C, KW, F, SW, DW)
+
+
+def lg_conv1d_nwc_wcf(I, Kf, O, stride=1, dilation=1, accumulate=False, workspace=None, stream=None):
+    """O[N,OW,F] (+)= conv(I[N,W,C], Kf[KW,C,F]), no padding."""
+    N, W, C = I.shape
+    KW, C2, F = Kf.shape
+    if C != C2:
+        raise ValueError("channel extents do not agree")
+    for t in (I, Kf, O):
+        _dense(t)
+    OW = lg_conv_out_extent(W, KW, stride, dilation)
+    if tuple(O.shape) != (N, OW, F):
+        raise ValueError(f"output must have shape {(N, OW, F)}")
+    wp, wb = _ws(workspace)
+    _check("lg_conv1d_nwc_wcf",
+           lib().lg_conv1d_nwc_wcf(_ptr(I), _ptr(Kf), _ptr(O), N, W, C, KW, F, stride, dilation,
+                                   int(accumulate), wp, wb, _stream(stream)))
+    return O
+
+
 def lg_dwconv1d_nwc_wc(I, Kf, O, stride=1, dilation=1, accumulate=False, stream=None):
     """O[N,OW,C] (+)= depthwise conv(I[N,W,C], Kf[KW,C])."""
     N, W, C = I.shape
@@ -246,4 +271,23 @@ def lg_copy2d(x, out, stream=None):
     if tuple(out.shape) != (R, Cn):
         raise ValueError("out must have the same shape")
     _check("lg_copy2d", lib().lg_copy2d(_ptr(x), _ptr(out), R, Cn, _ld(x), _ld(out), _stream(stream)))
+    return out
+
+
+def lg_transpose_batched(x, out, R, Cn, ld_in, ld_out, B0, B1, in_strides, out_strides, stream=None):
+    """B0 x B1 transposes of R x Cn matrices inside the flat tensors x and out; batch (b0, b1) starts
+    at element b0*in_strides[0] + b1*in_strides[1] of x and likewise of out."""
+    if x.dim() != 1 or out.dim() != 1:
+        raise ValueError("x and out are passed flat (view(-1))")
+    for t in (x, out):
+        _dense(t)
+    if R and Cn and B0 and B1:
+        if (B0 - 1) * in_strides[0] + (B1 - 1) * in_strides[1] + (R - 1) * ld_in + Cn > x.numel():
+            raise ValueError("batched transpose reads past the end of x")
+        if (B0 - 1) * out_strides[0] + (B1 - 1) * out_strides[1] + (Cn - 1) * ld_out + R > out.numel():
+            raise ValueError("batched transpose writes past the end of out")
+    _check("lg_transpose_batched",
+           lib().lg_transpose_batched(_ptr(x), _ptr(out), R, Cn, ld_in, ld_out, B0, B1,
+                                      in_strides[0], in_strides[1], out_strides[0], out_strides[1],
+                                      _stream(stream)))
     return out

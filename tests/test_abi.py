@@ -70,6 +70,13 @@ def test_argument_validation_without_device(L):
     assert L.lg_transpose(P, P, 4, 4, 4, 4, None) == -1                        # in place
     assert L.lg_copy2d(P, Q, 4, 8, 7, 8, None) == -1
     assert L.lg_transpose(P, Q, 0, 8, 8, 8, None) == 0
+    assert L.lg_conv1d_nwc_wcf(P, P, Q, 1, 4, 4, 3, 4, 1, 2, 0, None, 0, None) == -1   # dilated window too big
+    assert L.lg_conv1d_nwc_wcf(P, P, Q, 1, 8, 4, 3, 4, 0, 1, 0, None, 0, None) == -1   # stride 0
+    assert L.lg_conv1d_nwc_wcf(P, P, Q, 0, 8, 4, 3, 4, 1, 1, 0, None, 0, None) == 0    # empty batch
+    assert L.lg_transpose_batched(P, Q, 4, 8, 8, 3, 2, 2, 32, 64, 32, 64, None) == -1  # ld_out < R
+    assert L.lg_transpose_batched(P, Q, 4, 8, 8, 4, 2, 2, -1, 64, 32, 64, None) == -1  # negative stride
+    assert L.lg_transpose_batched(P, P, 4, 4, 4, 4, 2, 1, 16, 0, 16, 0, None) == -1    # in place
+    assert L.lg_transpose_batched(P, Q, 4, 4, 4, 4, 0, 1, 16, 0, 16, 0, None) == 0     # empty batch
 
 
 def test_workspace_queries(L):
@@ -78,6 +85,8 @@ def test_workspace_queries(L):
     assert L.lg_reduce_cols_workspace_bytes(4096, 16384) > 0
     assert L.lg_reduce_cols_workspace_bytes(4096, 16384) <= 4096 * 16384 * 4 // 32   # << input
     assert L.lg_reduce_cols_workspace_bytes(64, 16384) == 0
+    assert L.lg_conv1d_workspace_bytes(4, 100, 32, 3, 64, 2, 2) == \
+        L.lg_conv2d_workspace_bytes(4, 1, 100, 32, 1, 3, 64, 1, 2, 1, 2)
     ws = L.lg_conv2d_workspace_bytes(8, 16, 16, 256, 3, 3, 256, 1, 1, 1, 1)
     assert ws % (8 * 14 * 14 * 256 * 4) == 0
 

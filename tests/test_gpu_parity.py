@@ -281,6 +281,51 @@ def test_conv2d_full_size(lg, lgo, case, shape):
     assert np.all(np.isfinite(O))
 
 
+# ------------------------------------------------------------------------------- conv1d
+
+def run_conv1d(lg, I, Kf, s=1, d=1, O0=None, accumulate=False):
+    N, W, C = I.shape
+    KW, _, F = Kf.shape
+    OW = lg.lg_conv_out_extent(W, KW, s, d)
+    out = Guarded((N, OW, F), init=O0 if O0 is not None else np.full((N, OW, F), np.nan, np.float32))
+    ws = workspace(lg.lg_conv1d_workspace_bytes(N, W, C, KW, F, s, d))
+    lg.lg_conv1d_nwc_wcf(dev(I), dev(Kf), out.t, stride=s, dilation=d, accumulate=accumulate, workspace=ws)
+    sync(); out.check()
+    return out.host()
+
+
+# the paper's 1-D sweep (Section 4.6.2): (N, C, F, K_w) = (1, 32, 64, 3), strides and dilations 1 and 2,
+# widths including the ragged 20 and 55; plus batches, odd channel counts and a long signal
+@pytest.mark.parametrize("N,W,C,F,KW", [(1, 20, 32, 64, 3), (1, 55, 32, 64, 3), (1, 256, 32, 64, 3),
+                                        (3, 77, 5, 7, 4), (2, 5000, 48, 96, 5)])
+@pytest.mark.parametrize("s,d", [(1, 1), (2, 1), (1, 2), (2, 2)])
+def test_conv1d_matches_oracle(lg, lgo, N, W, C, F, KW, s, d):
+    I = si.uniform(125, 0, (N, W, C), -1, 1)
+    Kf = si.uniform(125, 1, (KW, C, F), -1, 1)
+    assert_close(run_conv1d(lg, I, Kf, s, d), lgo.conv1d_nwc_wcf(I, Kf, stride=s, dilation=d), KW * C,
+                 f"conv1d {(N, W, C, F, KW, s, d)}")
+
+
+def test_conv1d_accumulate_and_exact(lg, lgo):
+    I = si.uniform(126, 0, (2, 60, 8), -1, 1)
+    Kf = si.uniform(126, 1, (3, 8, 12), -1, 1)
+    O0 = si.uniform(126, 9, (2, 28, 12), -1, 1)
+    ref = O0.copy(); lgo.conv1d_nwc_wcf(I, Kf, ref, stride=2, dilation=2, accumulate=True)
+    assert_close(run_conv1d(lg, I, Kf, 2, 2, O0=O0, accumulate=True), ref, 24, "conv1d accumulate")
+    Ii = si.small_integers(127, 0, (2, 33, 8))
+    Ki = si.small_integers(127, 1, (3, 8, 8))
+    assert np.array_equal(run_conv1d(lg, Ii, Ki, 2, 1), lgo.conv1d_nwc_wcf(Ii, Ki, stride=2))
+
+
+# the paper's 2-D sweep: (N, C, F, K_h, K_w) = (1, 32, 64, 3, 3), strides and dilations 1 and 2
+@pytest.mark.parametrize("HW", [20, 55])
+@pytest.mark.parametrize("s,d", [(1, 1), (2, 1), (1, 2), (2, 2)])
+def test_conv2d_paper_sweep(lg, lgo, HW, s, d):
+    I, Kf = si.conv2d_inputs(128, 1, HW, HW, 32, 64, 3, 3)
+    assert_close(run_conv(lg, I, Kf, (s, s), (d, d)), lgo.conv2d_nhwc_hwcf(I, Kf, stride=(s, s), dilation=(d, d)),
+                 288, f"conv2d sweep {(HW, s, d)}")
+
+
 # ------------------------------------------------------------------------------- depthwise
 
 def run_dw1(lg, I, Kf, s=1, d=1, O0=None, accumulate=False):
@@ -307,6 +352,8 @@ def run_dw2(lg, I, Kf, st=(1, 1), dl=(1, 1), O0=None, accumulate=False):
     (3, 100, 64, 3, 1, 1), (2, 19, 8, 3, 1, 1), (2, 3, 4, 3, 1, 1),
     (2, 50, 12, 3, 2, 1), (2, 50, 12, 3, 1, 2), (1, 64, 20, 5, 2, 2),
     (2, 33, 7, 3, 1, 1), (1, 17, 1, 2, 1, 1), (4, 1000, 512, 3, 1, 1),
+    # the paper's stride x dilation sweep at (N, C, K_w) = (1, 32, 3), Section 4.7
+    (1, 259, 32, 3, 2, 1), (1, 259, 32, 3, 1, 2), (1, 259, 32, 3, 2, 2), (3, 700, 256, 7, 3, 2),
 ])
 def test_dwconv1d_matches_oracle(lg, lgo, N, W, C, KW, s, d):
     I, Kf = si.dwconv1d_inputs(130, N, W, C, KW)
@@ -319,6 +366,9 @@ def test_dwconv1d_matches_oracle(lg, lgo, N, W, C, KW, s, d):
     (2, 35, 37, 96, 3, 3, (1, 1), (1, 1)), (2, 14, 15, 12, 3, 3, (2, 1), (1, 2)),
     (1, 16, 16, 6, 2, 4, (1, 2), (2, 1)), (2, 10, 9, 5, 3, 3, (1, 1), (1, 1)),
     (2, 1, 30, 8, 1, 3, (1, 1), (1, 1)),
+    # the paper's stride x dilation sweep at (N, C, K_h, K_w) = (1, 32, 3, 3), Section 4.7
+    (1, 41, 43, 32, 3, 3, (2, 2), (1, 1)), (1, 41, 43, 32, 3, 3, (1, 1), (2, 2)),
+    (1, 41, 43, 32, 3, 3, (2, 2), (2, 2)), (2, 60, 57, 128, 5, 4, (2, 3), (3, 2)),
 ])
 def test_dwconv2d_matches_oracle(lg, lgo, N, H, W, C, KH, KW, st, dl):
     I, Kf = si.dwconv2d_inputs(131, N, H, W, C, KH, KW)
@@ -334,6 +384,10 @@ def test_dwconv_accumulate_and_delta(lg, lgo):
     O0 = si.uniform(133, 9, (2, 10, 10, 8), -1, 1)
     ref = O0.copy(); lgo.dwconv2d_nhwc_hwc(I2, K2, ref, accumulate=True)
     assert_close(run_dw2(lg, I2, K2, O0=O0, accumulate=True), ref, 9, "dwconv2d accumulate")
+    I3, K3 = si.dwconv2d_inputs(134, 2, 21, 20, 16, 3, 3)
+    O0 = si.uniform(134, 9, (2, 9, 8, 16), -1, 1)
+    ref = O0.copy(); lgo.dwconv2d_nhwc_hwc(I3, K3, ref, stride=(2, 2), dilation=(2, 2), accumulate=True)
+    assert_close(run_dw2(lg, I3, K3, (2, 2), (2, 2), O0=O0, accumulate=True), ref, 9, "dwconv2d strided accumulate")
     Kd = np.zeros((3, 3, 8), np.float32); Kd[1, 2] = 1
     assert np.array_equal(bits(run_dw2(lg, I2, Kd)), bits(I2[:, 1:11, 2:12, :]))
     K1 = np.zeros((3, 16), np.float32); K1[2] = 1
@@ -455,6 +509,45 @@ def test_transpose_copy_leading_dims(lg, lgo):
         lg.lg_copy2d(xd[:, :Cn], cd[:, :Cn]); sync()
         ch = cd.view(torch.int32).cpu().numpy().view(np.uint32)
         assert np.array_equal(ch[:, :Cn], xb) and np.all(ch[:, Cn:] == 0x5EADBEEF)
+
+
+def run_transpose_batched(lg, lgo, xb, out_shape, R, Cn, ld_in, ld_out, B0, B1, ist, ost):
+    """Runs both sides on the same bits; untouched output words must keep their fill pattern."""
+    n_out = int(np.prod(out_shape))
+    ref = np.full(n_out, 0x5EADBEEF, np.uint32)
+    lgo.transpose_batched(np.ascontiguousarray(xb).view(np.float32).ravel(), ref.view(np.float32),
+                          R, Cn, ld_in, ld_out, B0, B1, ist[0], ist[1], ost[0], ost[1])
+    od = torch.full((n_out,), 0x5EADBEEF, dtype=torch.int32, device="cuda").view(torch.float32)
+    lg.lg_transpose_batched(dev(np.ascontiguousarray(xb).view(np.float32).ravel()), od, R, Cn, ld_in, ld_out,
+                            B0, B1, ist, ost)
+    sync()
+    got = od.view(torch.int32).cpu().numpy().view(np.uint32)
+    assert np.array_equal(got, ref)
+    return got.reshape(out_shape)
+
+
+@pytest.mark.parametrize("dims", [(5, 3, 4, 7), (64, 6, 5, 128), (130, 2, 3, 260), (256, 9, 8, 256), (1, 1, 1, 1)])
+def test_transpose_batched_4d_paper_permutation(lg, lgo, dims):
+    # Section 4.4: [i,j,k,l] -> [k,j,l,i] as j x k transposes of (i, l) matrices
+    Ni, Nj, Nk, Nl = dims
+    xb = special_bits(dims, 142)
+    got = run_transpose_batched(lg, lgo, xb, (Nk, Nj, Nl, Ni), Ni, Nl, Nj * Nk * Nl, Ni, Nj, Nk,
+                                (Nk * Nl, Nl), (Nl * Ni, Nj * Nl * Ni))
+    assert np.array_equal(got, np.transpose(xb, (2, 1, 3, 0)))
+
+
+def test_transpose_batched_3d_padded_and_empty(lg, lgo):
+    # [b,i,j] -> [b,j,i] with padded rows on both sides: the padding keeps its fill pattern
+    B, R, Cn, pi, po = 7, 50, 36, 3, 5
+    xb = special_bits((B, R, Cn + pi), 143)
+    got = run_transpose_batched(lg, lgo, xb, (B, Cn, R + po), R, Cn, Cn + pi, R + po, B, 1,
+                                (R * (Cn + pi), 0), (Cn * (R + po), 0))
+    assert np.array_equal(got[:, :, :R], np.transpose(xb[:, :, :Cn], (0, 2, 1)))
+    assert np.all(got[:, :, R:] == 0x5EADBEEF)
+    x = torch.zeros(16, device="cuda"); o = torch.zeros(16, device="cuda")
+    lg.lg_transpose_batched(x, o, 4, 4, 4, 4, 0, 1, (0, 0), (0, 0)); sync()      # empty batch: no launch
+    with pytest.raises(lg.LgError):
+        lg.lg_transpose_batched(x, o, 2, 2, 1, 2, 1, 1, (0, 0), (0, 0))             # ld_in < Cn
 
 
 def test_transpose_full_size(lg, lgo):

@@ -48,6 +48,12 @@ MUTANTS = [
      "memcpy(&out[j * ld_out + i], &in[i * ld_in + (Cn - 1 - j)], sizeof(float));"),
     ("lgo_transpose", "memcpy(&out[j * ld_out + i], &in[i * ld_in + j], sizeof(float));",
      "out[j * ld_out + i] = in[i * ld_in + j] + 0.0f;"),
+    ("lgo_conv1d_nwc_wcf", "int64_t x = w * SW + kw * DW;", "int64_t x = w * SW + kw;"),
+    ("lgo_conv1d_nwc_wcf", "int64_t x = w * SW + kw * DW;", "int64_t x = w + kw * DW;"),
+    ("lgo_conv1d_nwc_wcf", "(double)Kf[(kw * C + c) * F + f]", "(double)Kf[((KW - 1 - kw) * C + c) * F + f]"),
+    ("lgo_conv1d_nwc_wcf", "(double)Kf[(kw * C + c) * F + f]", "(double)Kf[(kw * C + c) * F + (F - 1 - f)]"),
+    ("lgo_transpose_batched", "&in[b0 * is0 + b1 * is1 + i * ld_in + j]", "&in[b1 * is1 + i * ld_in + j]"),
+    ("lgo_transpose_batched", "memcpy(&out[b0 * os0 + b1 * os1 + j * ld_out + i]", "memcpy(&out[b0 * os0 + b1 * os1 + i * ld_out + j]"),
     ("lgo_copy2d", "memcpy(&out[i * ld_out + j], &in[i * ld_in + j], sizeof(float));",
      "memcpy(&out[i * ld_out + j], &in[(R - 1 - i) * ld_in + j], sizeof(float));"),
 ]

@@ -305,6 +305,52 @@ def test_conv2d_accumulate_and_errors(lgo):
         lgo.conv2d_nhwc_hwcf(np.zeros((1, 2, 2, 1), np.float32), np.zeros((3, 3, 1, 1), np.float32))
 
 
+# --------------------------------------------------------------------------- conv1d
+
+def test_conv1d_hand_literal(lgo):
+    # one channel, one filter, no flip: [1,2,3,4,5] with taps [1,10,100]
+    I = np.arange(1, 6, dtype=np.float32).reshape(1, 5, 1)
+    Kf = np.array([1, 10, 100], np.float32).reshape(3, 1, 1)
+    assert lgo.conv1d_nwc_wcf(I, Kf).ravel().tolist() == [321, 432, 543]
+    assert lgo.conv1d_nwc_wcf(I, Kf, stride=2).ravel().tolist() == [321, 543]
+    assert lgo.conv1d_nwc_wcf(I, Kf, dilation=2).ravel().tolist() == [531]
+    # two channels -> two filters at one tap: K[0,c,f] = [[1,10],[100,1000]]
+    I = np.array([[2, 3], [5, 7]], np.float32).reshape(1, 2, 2)
+    Kf = np.array([[1, 10], [100, 1000]], np.float32).reshape(1, 2, 2)
+    assert lgo.conv1d_nwc_wcf(I, Kf).reshape(2, 2).tolist() == [[302, 3020], [705, 7050]]
+
+
+@pytest.mark.parametrize("S,D", [(1, 1), (2, 1), (1, 2), (2, 2), (3, 2)])
+def test_conv1d_vs_numpy_fp64_and_conv2d(lgo, S, D):
+    # the paper's sweep point (N, C, F, K_w) = (1, 32, 64, 3) at a ragged width, plus a batch
+    for N, W, C, F, KW in [(1, 55, 32, 64, 3), (3, 23, 5, 7, 4)]:
+        I = si.uniform(38, 0, (N, W, C), -1, 1)
+        Kf = si.uniform(38, 1, (KW, C, F), -1, 1)
+        O = lgo.conv1d_nwc_wcf(I, Kf, stride=S, dilation=D)
+        span = D * (KW - 1) + 1
+        win = np.lib.stride_tricks.sliding_window_view(I.astype(np.float64), span, axis=1)[:, ::S, :, ::D]
+        ref = np.einsum("nwck,kcf->nwf", win, Kf.astype(np.float64))
+        assert O.shape == ref.shape
+        assert_half_ulp(O, ref)
+        # Section 4.6.2: the 2-D op with H = K_h = 1 is this op (same summation order: bit-exact)
+        O2 = lgo.conv2d_nhwc_hwcf(I[:, None], Kf[None], stride=(1, S), dilation=(1, D))
+        assert np.array_equal(bits(O), bits(O2[:, 0]))
+
+
+def test_conv1d_scipy_accumulate_and_errors(lgo):
+    W, KW = 40, 5
+    I = si.uniform(39, 0, (1, W, 1), -1, 1)
+    Kf = si.uniform(39, 1, (KW, 1, 1), -1, 1)
+    ref = signal.correlate(I[0, :, 0].astype(np.float64), Kf[:, 0, 0].astype(np.float64), "valid")
+    assert_half_ulp(lgo.conv1d_nwc_wcf(I, Kf)[0, :, 0], ref)
+    O0 = si.uniform(39, 9, (1, W - KW + 1, 1), -1, 1)
+    O = O0.copy()
+    lgo.conv1d_nwc_wcf(I, Kf, O, accumulate=True)
+    assert_half_ulp(O[0, :, 0], ref + O0[0, :, 0])
+    with pytest.raises(ValueError):
+        lgo.conv1d_nwc_wcf(np.zeros((1, 4, 1), np.float32), np.zeros((3, 1, 1), np.float32), dilation=2)
+
+
 # --------------------------------------------------------------------------- depthwise
 
 def test_dwconv1d_hand_literal(lgo):
@@ -487,6 +533,31 @@ def test_transpose_and_copy_leading_dims(lgo):
     assert rc == 0 and np.array_equal(out[:, :8], xb) and np.all(out[:, 8:] == 0xDEADBEEF)
     assert np.array_equal(bits(lgo.copy2d(xb.view(np.float32))), xb)
     assert lgo.lib().lgo_transpose(lgo._p(xp.view(np.float32)), lgo._p(out.view(np.float32)), 5, 8, 11, 4) == -1
+
+
+def test_transpose_batched_paper_4d_example(lgo):
+    # Section 4.4: [i,j,k,l] -> [k,j,l,i] as j x k transposes of (i, l) matrices
+    Ni, Nj, Nk, Nl = 5, 3, 4, 7
+    xb = special_bits((Ni, Nj, Nk, Nl), 65)
+    out = np.full(Nk * Nj * Nl * Ni, 0xDEADBEEF, np.uint32)
+    lgo.transpose_batched(xb.view(np.float32).ravel(), out.view(np.float32),
+                          Ni, Nl, Nj * Nk * Nl, Ni, Nj, Nk, Nk * Nl, Nl, Nl * Ni, Nj * Nl * Ni)
+    assert np.array_equal(out.reshape(Nk, Nj, Nl, Ni), np.transpose(xb, (2, 1, 3, 0)))
+    # hand literal: two 2x2 matrices stored back to back
+    x = np.array([1, 2, 3, 4, 5, 6, 7, 8], np.float32)
+    o = np.zeros(8, np.float32)
+    lgo.transpose_batched(x, o, 2, 2, 2, 2, 1, 2, 0, 4, 0, 4)
+    assert o.tolist() == [1, 3, 2, 4, 5, 7, 6, 8]
+    # a batch of one equals the plain transpose; [b,i,j] -> [j,b,i] through the outer batch index
+    x2 = special_bits((6, 9), 66)
+    o2 = np.zeros(54, np.uint32)
+    lgo.transpose_batched(x2.view(np.float32).ravel(), o2.view(np.float32), 6, 9, 9, 6, 1, 1, 0, 0, 0, 0)
+    assert np.array_equal(o2.reshape(9, 6), x2.T)
+    x3 = special_bits((4, 3, 5), 67)
+    o3 = np.zeros(60, np.uint32)
+    lgo.transpose_batched(x3.view(np.float32).ravel(), o3.view(np.float32), 3, 5, 5, 12, 4, 1, 15, 0, 3, 0)
+    assert np.array_equal(o3.reshape(5, 4, 3), np.transpose(x3, (2, 0, 1)))
+    assert lgo.lib().lgo_transpose_batched(lgo._p(x), lgo._p(o), 2, 2, 1, 2, 1, 2, 0, 4, 0, 4) == -1
 
 
 # --------------------------------------------------------------------------- inputs
