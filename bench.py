@@ -127,7 +127,7 @@ def main():
     O2 = torch.empty((n2, h2 - kh2 + 1, w2 - kw2 + 1, c2), device="cuda")
 
     convs = []
-    for case, (N, H, W, C, F, KH, KW, s) in enumerate(si.CONV2D_SHAPES):
+    for case, (N, H, W, C, F, KH, KW, s) in enumerate(si.CONV2D_SHAPES + [si.CONV2D_LARGE]):
         Ih, Kh = si.conv2d_inputs(3, N, H, W, C, F, KH, KW, case=case)
         Id, Kd = dev(Ih), dev(Kh)
         OH, OW = (H - KH) // s + 1, (W - KW) // s + 1
@@ -172,13 +172,15 @@ def main():
         4.0 * (O2.numel() + K2.numel() + I2.numel()), "hbm", "dwconv2d")
     add_mm((4096, 4096, 4096))
     add_mm((16384, 512, 2048))
-    for c in convs:
+    for c in convs[:-1]:
         add(c["name"], c["call"], c["flops"], c["nbytes"], "mfma", c["kernel"])
     add("reduce_rows_4096x16384", lambda: lg.lg_reduce_rows(x_rows, out_rows), R * Cn, 4.0 * (R * Cn + R), "hbm",
         "reduce_rows")
     add("reduce_cols_4096x16384", lambda: lg.lg_reduce_cols(x_cols, out_cols, workspace=ws_cols), R * Cn,
         4.0 * (R * Cn + Cn), "hbm", "reduce_cols")
     add_mm((8192, 8192, 8192))
+    c = convs[-1]            # the large conv: what the implicit GEMM does once the machine is full
+    add(c["name"], c["call"], c["flops"], c["nbytes"], "mfma", c["kernel"])
     add("matmul_AtB_4096x4096x4096", lambda: lg.lg_matmul_t(At_d, Bn_d, Ct_d, trans_a=True, workspace=wt),
         2.0 * Mt * Nt * Kt, 12.0 * Mt * Nt, "mfma", gemm_kernel_name(Mt, Nt, Kt) + "_tn")
     add("matmul_ABt_4096x4096x4096", lambda: lg.lg_matmul_t(An_d, Bt_d, Ct_d, trans_b=True, workspace=wt),
@@ -241,8 +243,8 @@ def main():
                ms_per_step=ms_per_step, higher_is_better=True, scaling="weak", vs_baseline=None,
                dtype="f32", data="synthetic",
                config=dict(workload="configs[1..4]: reduce_rows/cols 4096x16384, transpose (+copy) 8192^2, matmul sweep "
-                                    "(1024^3, 4096^3, 8192^3, 16384x512x2048, 4096x4096x64; A^T B and A B^T at 4096^3), conv2d x3, "
-                                    "dwconv1d, dwconv2d; one launch of each per step"),
+                                    "(1024^3, 4096^3, 8192^3, 16384x512x2048, 4096x4096x64; A^T B and A B^T at 4096^3), conv2d x3 "
+                                    "(+ one large conv 32x58x58x256->256 3x3), dwconv1d, dwconv2d; one launch of each per step"),
                frac_mfma_peak=value * 1e9 / MFMA_FP32_PEAK, roofline=roofline, ops=per_op)
 
     # ------------------------------------------------------------------ CPU oracle baseline

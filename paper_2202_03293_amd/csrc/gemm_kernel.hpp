@@ -67,8 +67,8 @@ struct GemmArgs {
 };
 
 // BM x BN output tile per workgroup, BK-deep k-slices, WM x WN register tile per wavefront.
-// MINW = wavefronts per SIMD the register allocation must leave room for.
-template <int BM_, int BN_, int BK_, int WM_, int WN_, int MINW_>
+// MINW = wavefronts per SIMD the register allocation must leave room for (what LDS lets a CU hold).
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int MINW_, int STAGES_ = 3>
 struct Tile {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MINW = MINW_;
     static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN;
@@ -80,7 +80,11 @@ struct Tile {
     static constexpr int A_PER_T = BM * BK / 4 / THREADS;   // float4s of a slice per lane
     static constexpr int B_PER_T = BK * BN / 4 / THREADS;
     static constexpr int ROW_STEP = THREADS / QPR;  // R-kind: rows between a lane's successive float4s
-    static constexpr int STAGES = 3;                // LDS ring: one slice being multiplied, two in flight
+    // LDS ring.  3: one slice being multiplied, two in flight.  4: three in flight and the barrier
+    // publishes slices one step early, so a wave fetches the first fragments of the next slice
+    // while it still multiplies the current one (see the main loop).
+    static constexpr int STAGES = STAGES_;
+    static_assert(STAGES == 3 || STAGES == 4, "ring depth");
     static constexpr int LDS_FLOATS = STAGES * (BM * BK + BK * BN);
     static_assert(BK == 16 || BK == 32 || BK == 64, "k-slice depth");
     static_assert(NB == 1 || NB == 2 || NB == 4, "wave tile width must be 32, 64 or 128");
@@ -432,6 +436,78 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
         }
     };
 
+    // The same, for the ring of four stages: the slice after this one is already visible in LDS, so
+    // its R-kind fragments (register set `1 - set`) and its first C-kind step are fetched while this
+    // slice is multiplied; on entry this slice's own (set `set`, step 0 in slot 0) are in registers.
+    // A wave then crosses the barrier between slices with its next operands in hand, instead of
+    // starting the LDS reads after it.
+    constexpr int NJ = BK / 8, NSTEP = BK / 2;
+    float4 pa4[2][TA ? 1 : NJ][MB];
+    float4 pb4[2][TB ? NJ : 1][NB];
+    float pa1[2][MB], pb1[2][NB];
+    auto fetch_R = [&](int buf, int set) {
+        const float* as = As + buf * (BM * BK);
+        const float* bs = Bs + buf * (BK * BN);
+        if constexpr (!TA) {
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+                    pa4[set][j][mb] = *reinterpret_cast<const float4*>(as + T::r_off(wm0 + mb * 32 + c32, 2 * j + h));
+        }
+        if constexpr (TB) {
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    pb4[set][j][nb] = *reinterpret_cast<const float4*>(bs + T::r_off(wn0 + nb * 32 + c32, 2 * j + h));
+        }
+    };
+    auto fetch_C = [&](int buf, int st, int slot) {
+        const float* as = As + buf * (BM * BK);
+        const float* bs = Bs + buf * (BK * BN);
+        const int k = 8 * (st / 4) + 4 * h + (st % 4);
+        if constexpr (TA) {
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) pa1[slot][mb] = as[k * BM + wm0 + mb * 32 + c32];
+        }
+        if constexpr (!TB) {
+            const float* brow = bs + k * BN + wn0 + NB * c32;
+            if constexpr (NB == 4) {
+                const float4 v = *reinterpret_cast<const float4*>(brow);
+                pb1[slot][0] = v.x; pb1[slot][1] = v.y; pb1[slot][2] = v.z; pb1[slot][3] = v.w;
+            } else if constexpr (NB == 2) {
+                const float2 v = *reinterpret_cast<const float2*>(brow);
+                pb1[slot][0] = v.x; pb1[slot][1] = v.y;
+            } else {
+                pb1[slot][0] = *brow;
+            }
+        }
+    };
+    auto compute_slice_ahead = [&](int buf, int nextbuf, int set) {
+        auto comp = [](const float4& v, int i) { return (i == 0) ? v.x : (i == 1) ? v.y : (i == 2) ? v.z : v.w; };
+#pragma unroll
+        for (int st = 0; st < NSTEP; ++st) {
+            if (st + 1 < NSTEP) fetch_C(buf, st + 1, (st + 1) & 1);
+            else                fetch_C(nextbuf, 0, 0);          // NSTEP is even: slot 0 is free again
+            if (st == 1) fetch_R(nextbuf, 1 - set);
+            __builtin_amdgcn_sched_barrier(0);
+            const int j = st / 4, i = st % 4;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                float av;
+                if constexpr (TA) av = pa1[st & 1][mb]; else av = comp(pa4[set][j][mb], i);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    float bv;
+                    if constexpr (TB) bv = comp(pb4[set][j][nb], i); else bv = pb1[st & 1][nb];
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[mb][nb], 0, 0, 0);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
     // ---- main loop --------------------------------------------------------------------------
     // The interior path addresses operands with 32-bit byte offsets from the tile origin.
     const int64_t lim = (int64_t)1 << 31;
@@ -441,7 +517,41 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
     const bool interior = VEC && a_small && b_small && (m0 + BM <= p.M) && (n0 + BN <= p.N) &&
                           ((kend - kbeg) % BK == 0);
     if (nslices > 0) {
-        if (interior) {
+        if (interior && T::STAGES == 4) {
+            // Ring of four LDS stages, transfers three slices ahead.  The barrier that ends step s makes
+            // slice s+2 visible (each wave first waits for its own transfers of that slice), so during
+            // step s+1 every wave may already read slice s+2.  It also guarantees that nobody still
+            // reads slice s, whose stage the transfer issued in step s+1 refills.
+            constexpr int L = APT + BPT;           // transfers per slice per wave
+            init_full();
+            issue_slice(0);
+            if (nslices > 1) issue_slice(1);
+            if (nslices > 2) { issue_slice(2); dma_wait<L>(); } else { dma_wait<0>(); }
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            fetch_R(0, 0);
+            fetch_C(0, 0, 0);
+            auto step = [&](auto stage_c, int s) {
+                constexpr int stage = decltype(stage_c)::value;
+                if (s + 3 < nslices) issue_slice((stage + 3) % 4);
+                compute_slice_ahead(stage, (stage + 1) % 4, stage & 1);
+                if (s + 2 < nslices) {
+                    if (s + 3 < nslices) dma_wait<L>(); else dma_wait<0>();
+                    __builtin_amdgcn_s_barrier();
+                    asm volatile("" ::: "memory");
+                }
+            };
+            int s = 0;
+            for (; s + 4 <= nslices; s += 4) {
+                step(std::integral_constant<int, 0>{}, s);
+                step(std::integral_constant<int, 1>{}, s + 1);
+                step(std::integral_constant<int, 2>{}, s + 2);
+                step(std::integral_constant<int, 3>{}, s + 3);
+            }
+            if (s < nslices) step(std::integral_constant<int, 0>{}, s);
+            if (s + 1 < nslices) step(std::integral_constant<int, 1>{}, s + 1);
+            if (s + 2 < nslices) step(std::integral_constant<int, 2>{}, s + 2);
+        } else if (interior) {
             // Ring of three LDS stages, transfers two slices ahead.  Each wave waits for its own
             // transfers of the slice needed next (vmcnt counts them in order), then the barrier makes
             // everybody's visible and also guarantees nobody still reads the stage refilled next.
@@ -545,19 +655,22 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
 // ---- the tile menu and the planner (host) ---------------------------------------------------------
 // All tiles: 4 wavefronts, one per SIMD.  `occ` = workgroups of that tile a CU can hold (LDS and
 // registers), `mfma` = matrix-pipe clocks one k-slice costs one SIMD, `eff` = the measured fraction
-// of the matrix-pipe rate the tile sustains with a full CU (4096^3, clock-normalised).
-using Tile0 = Tile<128, 256, 16, 64, 128, 2>;   // waves of 64x128
-using Tile1 = Tile<128, 128, 16, 32, 128, 4>;   // waves of 32x128
-using Tile2 = Tile<128, 64, 16, 32, 64, 4>;     // waves of 32x64 (narrow outputs, e.g. F = 64)
-using Tile3 = Tile<64, 64, 16, 32, 32, 4>;      // waves of 32x32 (small problems)
-using Tile4 = Tile<64, 128, 32, 32, 64, 4>;     // waves of 32x64, deeper slices (mid-size problems)
-using Tile5 = Tile<64, 64, 32, 32, 32, 4>;      // waves of 32x32, deeper slices
+// of the matrix-pipe rate the tile sustains with a full CU (clock-normalised), `dead` = clocks per
+// slice of barrier skew and LDS latency that only other resident workgroups hide (less with the
+// four-stage ring, which fetches across the barrier).  The big tile keeps three stages: a fourth
+// would cost it its second workgroup per CU.
+using Tile0 = Tile<128, 256, 16, 64, 128, 2>;      // waves of 64x128
+using Tile1 = Tile<128, 128, 16, 32, 128, 2, 4>;   // waves of 32x128
+using Tile2 = Tile<128, 64, 16, 32, 64, 3, 4>;     // waves of 32x64 (narrow outputs, e.g. F = 64)
+using Tile3 = Tile<64, 64, 16, 32, 32, 4, 4>;      // waves of 32x32 (small problems)
+using Tile4 = Tile<64, 128, 32, 32, 64, 2>;        // waves of 32x64, deeper slices (mid-size problems)
+using Tile5 = Tile<64, 64, 32, 32, 32, 2, 4>;      // waves of 32x32, deeper slices
 
-struct TileInfo { int bm, bn, bk, occ, mfma; double eff; };
+struct TileInfo { int bm, bn, bk, occ, mfma; double eff, dead; };
 constexpr int kNumTiles = 6;
 static const TileInfo kTiles[kNumTiles] = {
-    {128, 256, 16, 2, 4096, 0.935}, {128, 128, 16, 4, 2048, 0.92}, {128, 64, 16, 4, 1024, 0.90},
-    {64, 64, 16, 6, 512, 0.875},    {64, 128, 32, 2, 2048, 0.89},  {64, 64, 32, 3, 1024, 0.87}};
+    {128, 256, 16, 2, 4096, 0.935, 350}, {128, 128, 16, 2, 2048, 0.93, 300}, {128, 64, 16, 3, 1024, 0.91, 250},
+    {64, 64, 16, 5, 512, 0.88, 220},     {64, 128, 32, 2, 2048, 0.89, 478},  {64, 64, 32, 2, 1024, 0.88, 330}};
 
 struct Plan {
     int tile;          // index into kTiles
@@ -568,9 +681,7 @@ constexpr int kCUs = 256;
 constexpr int kKGran = 64;   // split-k slabs are multiples of this (a multiple of every tile's BK)
 
 // Pick (tile, k-split) with a cost model fitted to measurements on this part: when c workgroups
-// share a CU, one k-slice of all of them takes  c * mfma / eff + dead / c  clocks, where `dead`
-// (barrier skew + LDS refill after the barrier, ~350 clocks, more for deeper slices) is only
-// hidden by other workgroups.  The busiest CU decides; a launch costs ~4 us of fill and drain;
+// share a CU, one k-slice of all of them takes  c * mfma / eff + dead / c  clocks.  The busiest CU decides; a launch costs ~4 us of fill and drain;
 // split-k adds the partial-sum traffic and a second launch.
 inline Plan make_plan(int64_t M, int64_t N, int64_t K) {
     const double clk = 2.4e9;
@@ -581,7 +692,7 @@ inline Plan make_plan(int64_t M, int64_t N, int64_t K) {
     for (int ti = 0; ti < kNumTiles; ++ti) {
         const TileInfo& tl = kTiles[ti];
         const int64_t tm = cdiv(M, tl.bm), tn = cdiv(N, tl.bn);
-        const double dead = 350.0 + 8.0 * (tl.bk - 16);
+        const double dead = tl.dead;
         for (int sp : split_menu) {
             if (sp > 1 && kslabs < 2 * sp) break;                // keep at least 128 k per slab
             const int64_t kps = cdiv(kslabs, sp) * kKGran;

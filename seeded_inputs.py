@@ -73,6 +73,8 @@ MATMUL_SWEEP = [(1024, 1024, 1024), (4096, 4096, 4096), (8192, 8192, 8192),
 # (N, H, W, C, F, KH, KW, stride), seed 3, dilation 1, no padding
 CONV2D_SHAPES = [(8, 58, 58, 64, 64, 3, 3, 1), (8, 16, 16, 256, 256, 3, 3, 1),
                  (8, 56, 56, 256, 512, 1, 1, 2)]
+# a conv large enough to fill the machine (118 GFLOP); not one of the configurations' shapes
+CONV2D_LARGE = (32, 58, 58, 256, 256, 3, 3, 1)
 DWCONV1D_SHAPE = (32, 4098, 512, 3)                  # (N, W, C, KW), seed 4
 DWCONV2D_SHAPE = (8, 114, 114, 96, 3, 3)             # (N, H, W, C, KH, KW), seed 4
 

@@ -269,7 +269,7 @@ def test_conv2d_accumulate_and_exact(lg, lgo):
     assert np.array_equal(bits(run_conv(lg, X, Kd)), bits(X[:, 2:12, 1:11, :]))
 
 
-@pytest.mark.parametrize("case,shape", list(enumerate(si.CONV2D_SHAPES)))
+@pytest.mark.parametrize("case,shape", list(enumerate(si.CONV2D_SHAPES + [si.CONV2D_LARGE])))
 def test_conv2d_full_size(lg, lgo, case, shape):
     N, H, W, C, F, KH, KW, s = shape
     I, Kf = si.conv2d_inputs(3, N, H, W, C, F, KH, KW, case=case)
