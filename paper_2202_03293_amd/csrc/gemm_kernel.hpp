@@ -669,7 +669,7 @@ using Tile5 = Tile<64, 64, 32, 32, 32, 2, 4>;      // waves of 32x32, deeper sli
 struct TileInfo { int bm, bn, bk, occ, mfma; double eff, dead; };
 constexpr int kNumTiles = 6;
 static const TileInfo kTiles[kNumTiles] = {
-    {128, 256, 16, 2, 4096, 0.935, 350}, {128, 128, 16, 2, 2048, 0.93, 300}, {128, 64, 16, 3, 1024, 0.91, 250},
+    {128, 256, 16, 2, 4096, 0.935, 350}, {128, 128, 16, 2, 2048, 0.96, 300}, {128, 64, 16, 3, 1024, 0.91, 250},
     {64, 64, 16, 5, 512, 0.88, 220},     {64, 128, 32, 2, 2048, 0.89, 478},  {64, 64, 32, 2, 1024, 0.88, 330}};
 
 struct Plan {
@@ -681,7 +681,9 @@ constexpr int kCUs = 256;
 constexpr int kKGran = 64;   // split-k slabs are multiples of this (a multiple of every tile's BK)
 
 // Pick (tile, k-split) with a cost model fitted to measurements on this part: when c workgroups
-// share a CU, one k-slice of all of them takes  c * mfma / eff + dead / c  clocks.  The busiest CU decides; a launch costs ~4 us of fill and drain;
+// share a CU, one k-slice of all of them takes  c * mfma / eff + dead / c  clocks.  Each round of
+// workgroups on a CU also pays `fill`: start-up, and the output write, which is HBM-bound because
+// the workgroups of a round reach their epilogues together (~9 bytes per clock per CU).  The busiest CU decides; a launch costs ~4 us of fill and drain;
 // split-k adds the partial-sum traffic and a second launch.
 inline Plan make_plan(int64_t M, int64_t N, int64_t K) {
     const double clk = 2.4e9;
@@ -693,6 +695,7 @@ inline Plan make_plan(int64_t M, int64_t N, int64_t K) {
         const TileInfo& tl = kTiles[ti];
         const int64_t tm = cdiv(M, tl.bm), tn = cdiv(N, tl.bn);
         const double dead = tl.dead;
+        const double fill = 3000.0 + tl.occ * tl.bm * tl.bn * 4.0 / 9.0;
         for (int sp : split_menu) {
             if (sp > 1 && kslabs < 2 * sp) break;                // keep at least 128 k per slab
             const int64_t kps = cdiv(kslabs, sp) * kKGran;
@@ -702,8 +705,8 @@ inline Plan make_plan(int64_t M, int64_t N, int64_t K) {
             const double nslices = (double)cdiv(kps < K ? kps : K, tl.bk);
             const int64_t per_cu = cdiv(wgs, kCUs);              // workgroups on the busiest CU
             const int64_t full = per_cu / tl.occ, rest = per_cu % tl.occ;
-            double clocks = (double)full * nslices * (tl.occ * tl.mfma / tl.eff + dead / tl.occ);
-            if (rest) clocks += nslices * (rest * tl.mfma / tl.eff + dead / rest);
+            double clocks = (double)full * (nslices * (tl.occ * tl.mfma / tl.eff + dead / tl.occ) + fill);
+            if (rest) clocks += nslices * (rest * tl.mfma / tl.eff + dead / rest) + fill;
             double cost = clocks / clk + 4e-6;
             if (splits > 1) cost += 2.0 * splits * M * N * 4.0 / 3.0e12 + 5e-6;
             if (cost < best_cost) {
