@@ -26,25 +26,30 @@ MFMA_FP32_PEAK = 157.3e12      # 256 CU x 4 SIMD x 64 FLOP/clk x 2.4 GHz
 HBM_PEAK = 8.0e12              # bytes/s
 
 
-# HBM traffic of the dominant kernel per launch (average over the launches of one step), from two
-# counter runs of this file (FETCH_SIZE, then WRITE_SIZE; commands and raw figures in
-# profiles/gemm_128x256_bench_step.md).  Valid only for the kernel source it was taken with.
+# HBM traffic of the dominant kernel per launch (average over its launches in one step), from two
+# counter runs of this file (FETCH_SIZE, then WRITE_SIZE; commands, raw figures and the calibration
+# against the copy kernel in profiles/bench_step_hbm_traffic.md).  Valid only for the kernel source
+# the counters were taken with: a changed source makes `traffic` null.
 TRAFFIC = {
-    "kernel": "gemm_128x256",
-    "source_sha256": None,
-    "fetch_bytes": None,
-    "write_bytes": None,
+    "kernel": "gemm_128x128",
+    "source_sha256": "4066e21686661fe03d1ba4d4dca428515cc38e29a936b5ff39802f1ad4c49120",
+    "fetch_bytes": 2496028877,       # 1218764.1 KiB read by FETCH_SIZE x 2.0 (copy-kernel calibration)
+    "write_bytes": 123032883,        # 120149.3 KiB read by WRITE_SIZE x 1.0
 }
+KERNEL_SOURCE = os.path.join(ROOT, "paper_2202_03293_amd", "csrc", "gemm_kernel.hpp")
+
+
+def kernel_source_sha256():
+    import hashlib
+    with open(KERNEL_SOURCE, "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()
 
 
 def measured_traffic(kernel_name):
-    import hashlib
-    src = os.path.join(ROOT, "paper_2202_03293_amd", "csrc", "gemm.hip")
     if TRAFFIC["source_sha256"] is None or TRAFFIC["kernel"] != kernel_name:
         return None
-    with open(src, "rb") as f:
-        if hashlib.sha256(f.read()).hexdigest() != TRAFFIC["source_sha256"]:
-            return None          # the kernel changed since the counters were read
+    if kernel_source_sha256() != TRAFFIC["source_sha256"]:
+        return None              # the kernel changed since the counters were read
     return dict(fetch_bytes=TRAFFIC["fetch_bytes"], write_bytes=TRAFFIC["write_bytes"],
                 total_bytes=TRAFFIC["fetch_bytes"] + TRAFFIC["write_bytes"])
 
@@ -236,7 +241,14 @@ def main():
                     launches_per_step=len(dom), ops=[op["name"] for op in dom],
                     flops_per_launch=dom_flops, avg_launch_us=dom_dur * 1e6,
                     achieved=dom_flops / dom_dur / 1e12, peak=MFMA_FP32_PEAK / 1e12, unit="TFLOP/s",
-                    frac=dom_flops / dom_dur / MFMA_FP32_PEAK, traffic=measured_traffic(dom_name))
+                    frac=dom_flops / dom_dur / MFMA_FP32_PEAK)
+    tr = measured_traffic(dom_name)
+    # HBM bytes per launch as counted (null once the kernel source differs from the counted one), beside
+    # the operand bytes per launch; the excess is A/B panels streamed once per block of output tiles
+    roofline.update(traffic=tr["total_bytes"] if tr else None, traffic_unit="bytes per launch",
+                    traffic_fetch_bytes=tr["fetch_bytes"] if tr else None,
+                    traffic_write_bytes=tr["write_bytes"] if tr else None,
+                    algorithmic_bytes=sum(op["bytes"] for op in dom) / len(dom))
 
     out = dict(metric="matmul/conv GFLOP/s (% fp32 MFMA peak); reduce/transpose GB/s (% HBM peak)",
                value=value, unit="GFLOP/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
