@@ -6,7 +6,8 @@
 // Decomposition (the hardware counterpart of the paper's tile / pack / vectorise / contract steps):
 //   grid      -> BM x BN output tiles, dealt so that each XCD's L2 sees a compact block of tiles
 //   workgroup -> stages A and B k-slices (BK deep) global -> LDS directly (no registers), a ring of
-//                three LDS stages with the transfers running two slices ahead of the multiply
+//                three or four LDS stages with the transfers running two or three slices ahead of
+//                the multiply
 //   wavefront -> WM x WN register tile of 32x32 fp32 accumulators, v_mfma_f32_32x32x2_f32
 //   epilogue  -> accumulators (+ C) straight to global memory
 //
@@ -48,6 +49,14 @@ __device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t 
 template <int N>
 __device__ __forceinline__ void dma_wait() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// A wave-uniform 64-bit value moved into scalar registers (64-bit divisions leave theirs in vector
+// registers even when every lane holds the same number).
+__device__ __forceinline__ int64_t to_scalar(int64_t v) {
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
 struct ConvGeom {        // implicit-GEMM A operand: row m -> (n, oh, ow), column k -> (kh, kw, c)
@@ -138,6 +147,11 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
     const int r0 = t / T::QPR;
     const int lq = (t % T::QPR) ^ T::swizzle(r0);
 
+    // conv: element offset of GEMM row m = (n, oh, ow) at filter tap (0, 0), channel 0; grows with m
+    auto conv_row_base = [&](int64_t m) -> int64_t {
+        const int64_t ow = m % p.g.OW, oh = (m / p.g.OW) % p.g.OH, n = m / (p.g.OW * p.g.OH);
+        return ((n * p.g.H + oh * p.g.SH) * p.g.W + ow * p.g.SW) * p.g.C;
+    };
     // R-kind row bases (element offset of the row's k = 0; -1 when the row is outside the matrix)
     int64_t a_rowbase[TA ? 1 : APT];
     int64_t b_rowbase[TB ? BPT : 1];
@@ -147,8 +161,7 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
             const int64_t m = m0 + r0 + i * T::ROW_STEP;
             if (m >= p.M) { a_rowbase[i] = -1; continue; }
             if constexpr (CONV) {
-                const int64_t ow = m % p.g.OW, oh = (m / p.g.OW) % p.g.OH, n = m / (p.g.OW * p.g.OH);
-                a_rowbase[i] = ((n * p.g.H + oh * p.g.SH) * p.g.W + ow * p.g.SW) * p.g.C;
+                a_rowbase[i] = conv_row_base(m);
             } else {
                 a_rowbase[i] = m * p.lda;
             }
@@ -281,13 +294,16 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
     };
     auto init_full = [&]() {
         if constexpr (CONV) {
+            // lane offsets are relative to the tile's first row, so only the tile has to span < 2 GiB
+            const int64_t base0 = to_scalar(conv_row_base(m0));
+            a_base += base0 * 4;
             if (conv_uniform) {
                 su_c = (int)(kbeg % p.g.C);
                 su_kw = (int)((kbeg / p.g.C) % p.g.KW);
                 const int64_t kh = kbeg / (p.g.C * p.g.KW);
                 su_off = (uint32_t)(((kh * p.g.DH * p.g.W + (int64_t)su_kw * p.g.DW) * p.g.C + su_c) * 4);
 #pragma unroll
-                for (int i = 0; i < APT; ++i) a_loff[i] = (uint32_t)(a_rowbase[i] * 4) + 16u * lq;
+                for (int i = 0; i < APT; ++i) a_loff[i] = (uint32_t)((a_rowbase[i] - base0) * 4) + 16u * lq;
             } else {
                 const int64_t k = kbeg + 4 * lq;
                 cv_c = (int)(k % p.g.C);
@@ -295,7 +311,7 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
                 cv_kh = (int)(k / (p.g.C * p.g.KW));
                 cv_off = cv_offset();
 #pragma unroll
-                for (int i = 0; i < APT; ++i) a_loff[i] = (uint32_t)(a_rowbase[i] * 4);
+                for (int i = 0; i < APT; ++i) a_loff[i] = (uint32_t)((a_rowbase[i] - base0) * 4);
             }
         } else if constexpr (TA) {
             a_base += (kbeg * p.lda + m0) * 4;
@@ -511,8 +527,15 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
     // ---- main loop --------------------------------------------------------------------------
     // The interior path addresses operands with 32-bit byte offsets from the tile origin.
     const int64_t lim = (int64_t)1 << 31;
-    const bool a_small = CONV ? (p.g.H * p.g.W * p.g.C * (p.M / (p.g.OH * p.g.OW) + 1) * 4 < lim)
-                              : ((int64_t)(TA ? BK : BM) * p.lda * 4 < lim);
+    bool a_small;
+    if constexpr (CONV) {      // rows of the tile x the filter's reach, from the tile's first row
+        const int64_t last = (m0 + BM <= p.M) ? m0 + BM - 1 : m0;
+        const int64_t kh_taps = p.K / (p.g.KW * p.g.C);
+        const int64_t reach = ((kh_taps - 1) * p.g.DH * p.g.W + (p.g.KW - 1) * p.g.DW + 1) * p.g.C;
+        a_small = (conv_row_base(last) - conv_row_base(m0) + reach + BK) * 4 < lim;
+    } else {
+        a_small = (int64_t)(TA ? BK : BM) * p.lda * 4 < lim;
+    }
     const bool b_small = (int64_t)(TB ? BN : BK) * p.ldb * 4 < lim;
     const bool interior = VEC && a_small && b_small && (m0 + BM <= p.M) && (n0 + BN <= p.N) &&
                           ((kend - kbeg) % BK == 0);
@@ -587,7 +610,7 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
             if (s < nslices) step(std::integral_constant<int, 0>{}, s);
             if (s + 1 < nslices) step(std::integral_constant<int, 1>{}, s + 1);
         } else {
-            // Edge tiles, k tails, unaligned operands: registers -> LDS, two of the three stages.
+            // Edge tiles, k tails, unaligned operands: registers -> LDS, two of the ring's stages.
             load_slice_edge(kbeg);
             store_slice(0);
             __syncthreads();
