@@ -2,7 +2,7 @@
 """Benchmark of liblg on one MI355X.
 
 One "step" is one pass of the whole hot path: every op of the library at every shape of the
-benchmark configurations 1..4 (memory-bound ops, matmul sweep, conv2d, depthwise conv) on
+benchmark configurations 0..4 (small matmul, memory-bound ops, matmul sweep, conv2d, depthwise conv) on
 seeded synthetic inputs already resident in HBM.  Ops are ordered so that each memory-bound
 launch finds its operands cold (several hundred MiB of other traffic since they were last
 touched, more than the 256 MiB Infinity Cache).
@@ -95,10 +95,13 @@ def main():
 
     host_keep = {}
     mm = {}
-    for case, (M, N, K) in enumerate(si.MATMUL_SWEEP):
-        A, B = si.matmul_inputs(2, M, N, K, case=case)
+    sweep = [(2, case, shape) for case, shape in enumerate(si.MATMUL_SWEEP)] + [(0, 0, si.MATMUL_SMALL)]
+    for seed, case, (M, N, K) in sweep:
+        A, B = si.matmul_inputs(seed, M, N, K, case=case)
         if (M, N, K) == (8192, 8192, 8192):
             host_keep["mm8192"] = (A[:128].copy(), B)
+        if (M, N, K) == si.MATMUL_SMALL:
+            host_keep["mm256"] = (A, B)
         Ad, Bd = dev(A), dev(B)
         Cd = torch.zeros((M, N), device="cuda")
         w = ws(lg.lg_matmul_workspace_bytes(M, N, K))
@@ -192,6 +195,7 @@ def main():
         2.0 * Mt * Nt * Kt, 12.0 * Mt * Nt, "mfma", gemm_kernel_name(Mt, Nt, Kt) + "_nt")
     add_mm((1024, 1024, 1024))
     add_mm((4096, 4096, 64))
+    add_mm(si.MATMUL_SMALL)          # configuration 0: 0.2 us of math, a launch-latency figure
 
     # ------------------------------------------------------------------ run
     def step(events=None):
@@ -222,11 +226,19 @@ def main():
         rec = dict(op=op["name"], kernel=op["kernel"], bound=op["bound"], us_mean=mean * 1e6, us_median=med * 1e6,
                    us_p25=float(np.percentile(ts, 25)) * 1e6, us_p75=float(np.percentile(ts, 75)) * 1e6)
         if op["bound"] == "mfma":
-            rec.update(gflops=op["flops"] / mean / 1e9, frac_mfma_peak=op["flops"] / mean / MFMA_FP32_PEAK)
+            rec.update(gflops=op["flops"] / mean / 1e9, frac_mfma_peak=op["flops"] / mean / MFMA_FP32_PEAK,
+                       gbps=op["bytes"] / mean / 1e9, frac_hbm_peak=op["bytes"] / mean / HBM_PEAK)
         else:
-            rec.update(gbps=op["bytes"] / mean / 1e9, frac_hbm_peak=op["bytes"] / mean / HBM_PEAK)
+            rec.update(gbps=op["bytes"] / mean / 1e9, frac_hbm_peak=op["bytes"] / mean / HBM_PEAK,
+                       gflops=op["flops"] / mean / 1e9)
         op["mean_s"] = mean
         per_op.append(rec)
+    # the measured ceiling for the memory-bound ops: the copy kernel of the same step (the paper,
+    # too, quotes its bandwidth-bound kernels against a measured copy, Section 4.3)
+    copy_gbps = next(r["gbps"] for r in per_op if r["kernel"] == "copy2d")
+    for r in per_op:
+        if r["bound"] == "hbm":
+            r["frac_copy_rate"] = r["gbps"] / copy_gbps
 
     contraction_flops = sum(op["flops"] for op in ops if op["bound"] == "mfma")
     value = contraction_flops / (ms_per_step * 1e-3) / 1e9
@@ -254,7 +266,7 @@ def main():
                value=value, unit="GFLOP/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
                ms_per_step=ms_per_step, higher_is_better=True, scaling="weak", vs_baseline=None,
                dtype="f32", data="synthetic",
-               config=dict(workload="configs[1..4]: reduce_rows/cols 4096x16384, transpose (+copy) 8192^2, matmul sweep "
+               config=dict(workload="configs[0..4]: matmul 256^3, reduce_rows/cols 4096x16384, transpose (+copy) 8192^2, matmul sweep "
                                     "(1024^3, 4096^3, 8192^3, 16384x512x2048, 4096x4096x64; A^T B and A B^T at 4096^3), conv2d x3 "
                                     "(+ one large conv 32x58x58x256->256 3x3), dwconv1d, dwconv2d; one launch of each per step"),
                frac_mfma_peak=value * 1e9 / MFMA_FP32_PEAK, roofline=roofline, ops=per_op)
@@ -277,6 +289,9 @@ def main():
         others["transpose_GBps"] = 2 * xt.nbytes / d / 1e9
         t = time.perf_counter(); lgo.dwconv2d_nhwc_hwc(I2h, K2h); d = time.perf_counter() - t
         others["dwconv2d_GBps"] = 4.0 * (O2.numel() + K2.numel() + I2.numel()) / d / 1e9
+        A256, B256 = host_keep["mm256"]
+        t = time.perf_counter(); lgo.matmul(A256, B256); d = time.perf_counter() - t
+        others["matmul_256_all_threads_GFLOPs"] = 2.0 * 256 ** 3 / d / 1e9
         out["cpu_baseline"] = dict(value=2.0 * 128 * 8192 * 8192 / dt / 1e9, unit="GFLOP/s",
                                    cores=lgo.num_threads(), kind="oracle",
                                    sample="rows 0..127 of the 8192^3 matmul (naive fp64-accumulate loop nest, "

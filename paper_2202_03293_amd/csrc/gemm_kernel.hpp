@@ -747,13 +747,9 @@ inline size_t plan_workspace(const Plan& pl, int64_t M, int64_t N) {
 
 template <class T, bool VEC, bool CONV, bool TA, bool TB>
 static void launch_gemm(const GemmArgs& a, unsigned splits, hipStream_t s) {
-    static bool configured = false;
+    static bool configured[kMaxDevices] = {};
     const size_t lds_bytes = T::LDS_FLOATS * sizeof(float);
-    if (!configured) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<T, VEC, CONV, TA, TB>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        configured = true;
-    }
+    allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_kernel<T, VEC, CONV, TA, TB>), lds_bytes, configured);
     hipLaunchKernelGGL((gemm_kernel<T, VEC, CONV, TA, TB>), dim3(a.tiles_m * a.tiles_n, splits), dim3(T::THREADS),
                        lds_bytes, s, a);
 }

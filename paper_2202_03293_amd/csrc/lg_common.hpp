@@ -21,6 +21,17 @@ inline bool overlaps(const void* a, int64_t na, const void* b, int64_t nb) {
     return a0 < b0 + static_cast<uintptr_t>(nb) && b0 < a0 + static_cast<uintptr_t>(na);
 }
 
+// Raise a kernel's dynamic-LDS limit once per device (the attribute belongs to the kernel as loaded
+// on one device).  `done` is the caller's per-kernel table of kMaxDevices flags.
+constexpr int kMaxDevices = 64;
+inline void allow_dynamic_lds(const void* kernel, size_t bytes, bool* done) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) dev = -1;
+    if (dev >= 0 && done[dev]) return;
+    (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (dev >= 0) done[dev] = true;
+}
+
 inline int launch_status() { return hipGetLastError() == hipSuccess ? LG_OK : LG_ERR_RUNTIME; }
 
 // Workgroups are handed to the 8 XCDs round-robin (hardware id i runs on XCD i % 8) and each XCD
