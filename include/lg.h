@@ -154,7 +154,9 @@ int lg_dwconv2d_nhwc_hwc(const float *I, const float *Kf, float *O,
  * `in` is R x Cn with row stride ld >= Cn.  Sums are fp32, formed as short
  * per-lane partial sums combined by trees (never one long running sum).
  * lg_reduce_cols splits the rows across workgroups and combines the partial
- * vectors from the workspace.
+ * vectors from the workspace.  lg_reduce_rows gives every row one workgroup (one
+ * wavefront when Cn < 4096) and needs no workspace; it fills the GPU once R is in
+ * the hundreds, while a handful of very long rows occupy only as many compute units.
  */
 int lg_reduce_rows(const float *in, float *out, int64_t R, int64_t Cn, int64_t ld,
                    int accumulate, void *stream);
