@@ -60,6 +60,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also time the paper's batch-1 stride/dilation sweep (Sections 4.6.2, 4.7): launch-bound "
+                         "problems, reported per launch from batches of back-to-back launches under `sweep`")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives are part of it); "
@@ -270,6 +273,49 @@ def main():
                                     "(1024^3, 4096^3, 8192^3, 16384x512x2048, 4096x4096x64; A^T B and A B^T at 4096^3), conv2d x3 "
                                     "(+ one large conv 32x58x58x256->256 3x3), dwconv1d, dwconv2d; one launch of each per step"),
                frac_mfma_peak=value * 1e9 / MFMA_FP32_PEAK, roofline=roofline, ops=per_op)
+
+    # ------------------------------------------------------------------ the paper's small sweep
+    if args.sweep:
+        def per_launch_us(call, batch=20, reps=7):
+            for _ in range(batch):
+                call()
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(reps):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record(stream)
+                for _ in range(batch):
+                    call()
+                b.record(stream)
+                torch.cuda.synchronize()
+                ts.append(a.elapsed_time(b) * 1e3 / batch)
+            return float(np.median(ts))
+
+        sweep = []
+        for size in (16, 20, 32, 40, 55, 64, 128):
+            for sd in ((1, 1), (2, 1), (1, 2), (2, 2)):
+                st, dl = sd
+                # (N, C, F, K_w) = (1, 32, 64, 3): conv1d over W = size, conv2d over H = W = size
+                I1s = dev(si.uniform(5, 0, (1, size, 32), -1, 1)); K1s = dev(si.uniform(5, 1, (3, 32, 64), -1, 1))
+                ow = lg.lg_conv_out_extent(size, 3, st, dl)
+                if ow > 0:
+                    O1s = torch.empty((1, ow, 64), device="cuda")
+                    w1s = ws(lg.lg_conv1d_workspace_bytes(1, size, 32, 3, 64, st, dl))
+                    us = per_launch_us(lambda: lg.lg_conv1d_nwc_wcf(I1s, K1s, O1s, stride=st, dilation=dl, workspace=w1s))
+                    sweep.append(dict(op="conv1d", size=size, stride=st, dilation=dl, us=us,
+                                      gflops=2.0 * ow * 64 * 3 * 32 / us / 1e3))
+                    I2s = dev(si.uniform(5, 2, (1, size, size, 32), -1, 1)); K2s = dev(si.uniform(5, 3, (3, 3, 32, 64), -1, 1))
+                    O2s = torch.empty((1, ow, ow, 64), device="cuda")
+                    w2s = ws(lg.lg_conv2d_workspace_bytes(1, size, size, 32, 3, 3, 64, st, st, dl, dl))
+                    us = per_launch_us(lambda: lg.lg_conv2d_nhwc_hwcf(I2s, K2s, O2s, stride=(st, st), dilation=(dl, dl),
+                                                                     workspace=w2s))
+                    sweep.append(dict(op="conv2d", size=size, stride=st, dilation=dl, us=us,
+                                      gflops=2.0 * ow * ow * 64 * 9 * 32 / us / 1e3))
+                    Kd = dev(si.uniform(5, 4, (3, 32), -1, 1)); Od = torch.empty((1, ow, 32), device="cuda")
+                    us = per_launch_us(lambda: lg.lg_dwconv1d_nwc_wc(I1s, Kd, Od, stride=st, dilation=dl))
+                    sweep.append(dict(op="dwconv1d", size=size, stride=st, dilation=dl, us=us,
+                                      gbps=4.0 * (ow * 32 + 3 * 32 + size * 32) / us / 1e3))
+        out["sweep"] = sweep
 
     # ------------------------------------------------------------------ CPU oracle baseline
     if not args.no_cpu_baseline:
