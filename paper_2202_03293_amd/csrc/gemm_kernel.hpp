@@ -27,6 +27,8 @@
 namespace lg {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) void lds_void;
 
 // LDS byte address of a pointer into __shared__ memory.
@@ -654,7 +656,8 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
                             const float4 c = *reinterpret_cast<const float4*>(cp);
                             o.x += c.x; o.y += c.y; o.z += c.z; o.w += c.w;
                         }
-                        *reinterpret_cast<float4*>(cp) = o;
+                        // written once, never read back here: stream it past the caches that hold A and B
+                        __builtin_nontemporal_store(f32x4{o.x, o.y, o.z, o.w}, reinterpret_cast<f32x4*>(cp));
                     }
                 } else if constexpr (VEC && NB == 2) {
                     if (ncol < p.N) {
@@ -663,7 +666,7 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
                             const float2 c = *reinterpret_cast<const float2*>(cp);
                             o.x += c.x; o.y += c.y;
                         }
-                        *reinterpret_cast<float2*>(cp) = o;
+                        __builtin_nontemporal_store(f32x2{o.x, o.y}, reinterpret_cast<f32x2*>(cp));
                     }
                 } else {
 #pragma unroll
