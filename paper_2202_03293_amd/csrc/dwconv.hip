@@ -1,10 +1,11 @@
 // Depthwise convolutions (Section 4.7): no contraction across channels, so no matrix cores;
 // K_w (or K_h*K_w) FMAs per output element against 8 bytes of traffic -> HBM-bound.
 //
-// Fast kernels: a lane owns 4 adjacent channels (one 128-bit access) and a run of output
-// positions, keeps the input window in registers so each input element is loaded once per
-// lane, and neighbouring lanes/workgroups share the halo through L2.  General kernels cover
-// any stride, dilation, filter size and channel count one output element per lane.
+// Register-window kernels (filter widths 3, 5, 7 in 1-D, 3x3 in 2-D; strides and dilations 1 and 2,
+// the values the paper sweeps): a lane owns 4 adjacent channels (one 128-bit access) and a few output
+// positions, keeps the input window in registers so each input element is loaded once per lane, and
+// neighbouring lanes/workgroups share the halo through L2.  General kernels cover any other
+// stride, dilation, filter size and channel count, one output position per lane.
 #include "lg_common.hpp"
 
 namespace lg {
@@ -22,58 +23,91 @@ __device__ __forceinline__ float4 fma4(const float4 a, const float4 b, const flo
     return make_float4(fmaf(a.x, b.x, c.x), fmaf(a.y, b.y, c.y), fmaf(a.z, b.z, c.z), fmaf(a.w, b.w, c.w));
 }
 
-// 1-D, stride 1, dilation 1, C % 4 == 0.  Lane -> (n, run of TW outputs, 4 channels); channels vary
-// fastest across lanes so a wavefront reads 1 KiB contiguous per input position.
-template <int KW, int TW>
-__global__ __launch_bounds__(kDThreads) void dwconv1d_s1_kernel(
+// ---- register-window kernels: compile-time filter size, stride and dilation ---------------------
+// A lane owns T outputs along a dimension, G apart, where G = D / gcd(S, D) is the output spacing
+// at which neighbouring outputs share input positions (1 except for dilation 2 at stride 1, where
+// outputs of equal parity share).  Output j (at G*j from the lane's first) reads window positions
+// j*G*S + i*D for taps i < K: only those positions are loaded, each once.
+constexpr int gcd_i(int a, int b) { return b == 0 ? a : gcd_i(b, a % b); }
+
+template <int K, int S, int D, int T>
+struct Window {
+    static constexpr int G = D / gcd_i(S, D);
+    static constexpr int SPAN = (T - 1) * G * S + (K - 1) * D + 1;
+    static constexpr bool used(int p) {
+        for (int j = 0; j < T; ++j)
+            for (int i = 0; i < K; ++i)
+                if (j * G * S + i * D == p) return true;
+        return false;
+    }
+    // last window position needed when only n of the T outputs exist
+    __device__ static __forceinline__ int reach(int n) { return (n - 1) * G * S + (K - 1) * D; }
+};
+
+// 1-D, C % 4 == 0.  Lane -> (n, run of TW outputs, 4 channels); channels vary fastest across lanes
+// so a wavefront reads 1 KiB contiguous per input position.  Runs are numbered (block, phase):
+// block b, phase p holds outputs b*G*TW + p + G*j.
+template <int KW, int SW, int DW, int TW>
+__global__ __launch_bounds__(kDThreads) void dwconv1d_win_kernel(
     const float* __restrict__ I, const float* __restrict__ Kf, float* __restrict__ O,
     int64_t N, int64_t W, int64_t C, int64_t OW, int accumulate, unsigned nblocks) {
+    using Win = Window<KW, SW, DW, TW>;
+    constexpr int G = Win::G;
     const int64_t C4 = C / 4;
-    const int64_t runs = (OW + TW - 1) / TW;
+    const int64_t runs = (OW + G * TW - 1) / (G * TW) * G;
     const int64_t total = N * runs * C4;
     const int64_t idx = (int64_t)xcd_contiguous_id(blockIdx.x, nblocks) * kDThreads + threadIdx.x;
     if (idx >= total) return;
     const int64_t c4 = idx % C4;
     const int64_t run = (idx / C4) % runs;
     const int64_t n = idx / (C4 * runs);
-    const int64_t w0 = run * TW;
-    const int nout = (OW - w0 < TW) ? (int)(OW - w0) : TW;
+    const int64_t w0 = (run / G) * (G * TW) + run % G;
+    if (w0 >= OW) return;
+    const int64_t left = (OW - w0 + G - 1) / G;
+    const int nout = left < TW ? (int)left : TW;
     float4 k[KW];
 #pragma unroll
     for (int i = 0; i < KW; ++i) k[i] = *reinterpret_cast<const float4*>(Kf + i * C + 4 * c4);
-    const float* ip = I + (n * W + w0) * C + 4 * c4;
+    const float* ip = I + (n * W + w0 * SW) * C + 4 * c4;
     float* op = O + (n * OW + w0) * C + 4 * c4;
-    float4 x[TW + KW - 1];
+    float4 x[Win::SPAN];
+    const int reach = Win::reach(nout);
 #pragma unroll
-    for (int i = 0; i < TW + KW - 1; ++i) {
-        x[i] = make_float4(0, 0, 0, 0);
-        if (i < nout + KW - 1) x[i] = *reinterpret_cast<const float4*>(ip + (int64_t)i * C);
+    for (int p = 0; p < Win::SPAN; ++p) {
+        x[p] = make_float4(0, 0, 0, 0);
+        if (Win::used(p) && p <= reach) x[p] = *reinterpret_cast<const float4*>(ip + (int64_t)p * C);
     }
 #pragma unroll
-    for (int o = 0; o < TW; ++o) {
-        if (o < nout) {
-            float4 acc = accumulate ? *reinterpret_cast<const float4*>(op + (int64_t)o * C) : make_float4(0, 0, 0, 0);
+    for (int j = 0; j < TW; ++j) {
+        if (j < nout) {
+            float* q = op + (int64_t)(G * j) * C;
             // the initial accumulator enters last so that overwrite and accumulate share the k-sum
             float4 s = make_float4(0, 0, 0, 0);
 #pragma unroll
-            for (int i = 0; i < KW; ++i) s = fma4(x[o + i], k[i], s);
-            if (accumulate) { s.x += acc.x; s.y += acc.y; s.z += acc.z; s.w += acc.w; }
-            *reinterpret_cast<float4*>(op + (int64_t)o * C) = s;
+            for (int i = 0; i < KW; ++i) s = fma4(x[j * G * SW + i * DW], k[i], s);
+            if (accumulate) {
+                const float4 acc = *reinterpret_cast<const float4*>(q);
+                s.x += acc.x; s.y += acc.y; s.z += acc.z; s.w += acc.w;
+            }
+            *reinterpret_cast<float4*>(q) = s;
         }
     }
 }
 
-// 2-D, stride 1, dilation 1, C % 4 == 0.  Lane -> (n, TH x TW output patch, 4 channels).  The whole
-// (TH+KH-1) x (TW+KW-1) input patch is requested before any arithmetic, so a lane exposes one
-// memory latency, not one per row (measured 27 -> 19 us on the 8x114x114x96 workload against a
+// 2-D, same stride S and dilation D in both dimensions, C % 4 == 0.  Lane -> (n, TH x TW outputs G
+// apart, 4 channels).  The whole input patch is requested before any arithmetic, so a lane exposes
+// one memory latency, not one per row (measured 27 -> 19 us on the 8x114x114x96 workload against a
 // rolling row window).  Outputs are streamed with non-temporal stores.  Plain workgroup order:
 // the XCD-contiguous order measured slightly slower here.
-template <int KH, int KW, int TH, int TW>
-__global__ __launch_bounds__(kDThreads) void dwconv2d_s1_kernel(
+template <int KH, int KW, int S, int D, int TH, int TW>
+__global__ __launch_bounds__(kDThreads) void dwconv2d_win_kernel(
     const float* __restrict__ I, const float* __restrict__ Kf, float* __restrict__ O,
     int64_t N, int64_t H, int64_t W, int64_t C, int64_t OH, int64_t OW, int accumulate) {
+    using WinH = Window<KH, S, D, TH>;
+    using WinW = Window<KW, S, D, TW>;
+    constexpr int G = WinH::G;
     const int64_t C4 = C / 4;
-    const int64_t pw = (OW + TW - 1) / TW, ph = (OH + TH - 1) / TH;
+    const int64_t pw = (OW + G * TW - 1) / (G * TW) * G, ph = (OH + G * TH - 1) / (G * TH) * G;
     const int64_t total = N * ph * pw * C4;
     const int64_t idx = (int64_t)blockIdx.x * kDThreads + threadIdx.x;
     if (idx >= total) return;
@@ -81,19 +115,22 @@ __global__ __launch_bounds__(kDThreads) void dwconv2d_s1_kernel(
     const int64_t bw = (idx / C4) % pw;
     const int64_t bh = (idx / (C4 * pw)) % ph;
     const int64_t n = idx / (C4 * pw * ph);
-    const int64_t h0 = bh * TH, w0 = bw * TW;
-    const int nh = (OH - h0 < TH) ? (int)(OH - h0) : TH;
-    const int nw = (OW - w0 < TW) ? (int)(OW - w0) : TW;
-    const float* ip = I + ((n * H + h0) * W + w0) * C + 4 * c4;
+    const int64_t h0 = (bh / G) * (G * TH) + bh % G, w0 = (bw / G) * (G * TW) + bw % G;
+    if (h0 >= OH || w0 >= OW) return;
+    const int64_t left_h = (OH - h0 + G - 1) / G, left_w = (OW - w0 + G - 1) / G;
+    const int nh = left_h < TH ? (int)left_h : TH;
+    const int nw = left_w < TW ? (int)left_w : TW;
+    const float* ip = I + ((n * H + h0 * S) * W + w0 * S) * C + 4 * c4;
     float* op = O + ((n * OH + h0) * OW + w0) * C + 4 * c4;
-    float4 x[TH + KH - 1][TW + KW - 1];
+    float4 x[WinH::SPAN][WinW::SPAN];
+    const int reach_h = WinH::reach(nh), reach_w = WinW::reach(nw);
 #pragma unroll
-    for (int r = 0; r < TH + KH - 1; ++r)
+    for (int r = 0; r < WinH::SPAN; ++r)
 #pragma unroll
-        for (int i = 0; i < TW + KW - 1; ++i) {
-            x[r][i] = make_float4(0, 0, 0, 0);
-            if (r < nh + KH - 1 && i < nw + KW - 1)
-                x[r][i] = *reinterpret_cast<const float4*>(ip + ((int64_t)r * W + i) * C);
+        for (int c = 0; c < WinW::SPAN; ++c) {
+            x[r][c] = make_float4(0, 0, 0, 0);
+            if (WinH::used(r) && WinW::used(c) && r <= reach_h && c <= reach_w)
+                x[r][c] = *reinterpret_cast<const float4*>(ip + ((int64_t)r * W + c) * C);
         }
     float4 k[KH][KW];
 #pragma unroll
@@ -109,8 +146,8 @@ __global__ __launch_bounds__(kDThreads) void dwconv2d_s1_kernel(
 #pragma unroll
                 for (int a = 0; a < KH; ++a)
 #pragma unroll
-                    for (int b = 0; b < KW; ++b) s = fma4(x[r + a][o + b], k[a][b], s);
-                float* q = op + ((int64_t)r * OW + o) * C;
+                    for (int b = 0; b < KW; ++b) s = fma4(x[r * G * S + a * D][o * G * S + b * D], k[a][b], s);
+                float* q = op + ((int64_t)(G * r) * OW + G * o) * C;
                 if (accumulate) {
                     const float4 acc = *reinterpret_cast<const float4*>(q);
                     s.x += acc.x; s.y += acc.y; s.z += acc.z; s.w += acc.w;
@@ -183,27 +220,41 @@ static int dwconv_dispatch(const float* I, const float* Kf, float* O,
     if (overlaps(I, in_elems * 4, O, out_elems * 4) || overlaps(Kf, KH * KW * C * 4, O, out_elems * 4))
         return LG_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const bool unit = SH == 1 && SW == 1 && DH == 1 && DW == 1;
     const bool vec = (C % 4 == 0) && aligned16(I) && aligned16(Kf) && aligned16(O);
-    if (unit && vec && KH == 1 && KW == 3) {
+    const bool sd12 = SW >= 1 && SW <= 2 && DW >= 1 && DW <= 2;
+    if (vec && KH == 1 && SH == 1 && DH == 1 && sd12 && (KW == 3 || KW == 5 || KW == 7)) {
         constexpr int TW = 4;    // measured best: short runs, many lanes in flight
         // H rows of a 1-D problem are independent images: fold them into N
         const int64_t NN = N * H;
-        const int64_t items = NN * cdiv(OW, TW) * (C / 4);
+        const int64_t G = DW / (SW == DW ? DW : 1);            // D / gcd(S, D) for S, D in {1, 2}
+        const int64_t items = NN * (cdiv(OW, G * TW) * G) * (C / 4);
         const int64_t blocks = cdiv(items, kDThreads);
         if (blocks > kMaxGrid) return LG_ERR_UNSUPPORTED;
-        hipLaunchKernelGGL((dwconv1d_s1_kernel<3, TW>), dim3((unsigned)blocks), dim3(kDThreads), 0, s,
-                           I, Kf, O, NN, W, C, OW, accumulate, (unsigned)blocks);
-        return launch_status();
+#define LG_DW1(K_, S_, D_)                                                                                   \
+        if (KW == K_ && SW == S_ && DW == D_) {                                                              \
+            hipLaunchKernelGGL((dwconv1d_win_kernel<K_, S_, D_, TW>), dim3((unsigned)blocks), dim3(kDThreads), \
+                               0, s, I, Kf, O, NN, W, C, OW, accumulate, (unsigned)blocks);                  \
+            return launch_status();                                                                          \
+        }
+        LG_DW1(3, 1, 1) LG_DW1(3, 2, 1) LG_DW1(3, 1, 2) LG_DW1(3, 2, 2)
+        LG_DW1(5, 1, 1) LG_DW1(5, 2, 1) LG_DW1(5, 1, 2) LG_DW1(5, 2, 2)
+        LG_DW1(7, 1, 1) LG_DW1(7, 2, 1) LG_DW1(7, 1, 2) LG_DW1(7, 2, 2)
+#undef LG_DW1
     }
-    if (unit && vec && KH == 3 && KW == 3) {
-        constexpr int TH = 4, TW = 2;   // small patches: the problem must fill 256 CUs
-        const int64_t items = N * cdiv(OH, TH) * cdiv(OW, TW) * (C / 4);
-        const int64_t blocks = cdiv(items, kDThreads);
-        if (blocks > kMaxGrid) return LG_ERR_UNSUPPORTED;
-        hipLaunchKernelGGL((dwconv2d_s1_kernel<3, 3, TH, TW>), dim3((unsigned)blocks), dim3(kDThreads), 0, s,
-                           I, Kf, O, N, H, W, C, OH, OW, accumulate);
-        return launch_status();
+    if (vec && KH == 3 && KW == 3 && SH == SW && DH == DW && sd12) {
+        const int64_t G = DW / (SW == DW ? DW : 1);
+#define LG_DW2(S_, D_, TH_, TW_)                                                                             \
+        if (SW == S_ && DW == D_) {                                                                          \
+            const int64_t items = N * (cdiv(OH, G * TH_) * G) * (cdiv(OW, G * TW_) * G) * (C / 4);           \
+            const int64_t blocks = cdiv(items, kDThreads);                                                   \
+            if (blocks > kMaxGrid) return LG_ERR_UNSUPPORTED;                                                \
+            hipLaunchKernelGGL((dwconv2d_win_kernel<3, 3, S_, D_, TH_, TW_>), dim3((unsigned)blocks),        \
+                               dim3(kDThreads), 0, s, I, Kf, O, N, H, W, C, OH, OW, accumulate);             \
+            return launch_status();                                                                          \
+        }
+        // patch sizes: small enough that the problem fills 256 CUs and the patch fits in registers
+        LG_DW2(1, 1, 4, 2) LG_DW2(2, 1, 2, 2) LG_DW2(1, 2, 4, 2) LG_DW2(2, 2, 4, 2)
+#undef LG_DW2
     }
     if (vec) {
         const int64_t blocks4 = cdiv(out_elems / 4, kDThreads);

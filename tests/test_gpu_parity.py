@@ -375,6 +375,31 @@ def test_dwconv2d_matches_oracle(lg, lgo, N, H, W, C, KH, KW, st, dl):
     assert_close(run_dw2(lg, I, Kf, st, dl), lgo.dwconv2d_nhwc_hwc(I, Kf, stride=st, dilation=dl), KH * KW, "dwconv2d")
 
 
+# every register-window instantiation (filter width 3, 5, 7; stride and dilation 1 or 2), ragged
+# extents so that the last run of every phase is partial, overwrite and accumulate
+@pytest.mark.parametrize("KW", [3, 5, 7])
+@pytest.mark.parametrize("s,d", [(1, 1), (2, 1), (1, 2), (2, 2)])
+def test_dwconv1d_window_kernels(lg, lgo, KW, s, d):
+    for N, W, C in [(3, 261, 24), (1, (KW - 1) * d + 1, 8), (2, (KW - 1) * d + 1 + 3 * s, 4)]:
+        I, Kf = si.dwconv1d_inputs(134 + KW, N, W, C, KW)
+        ref = lgo.dwconv1d_nwc_wc(I, Kf, stride=s, dilation=d)
+        assert_close(run_dw1(lg, I, Kf, s, d), ref, KW, f"dwconv1d window {(N, W, C, KW, s, d)}")
+        O0 = si.uniform(135, KW, ref.shape, -1, 1)
+        ref2 = O0.copy(); lgo.dwconv1d_nwc_wc(I, Kf, ref2, stride=s, dilation=d, accumulate=True)
+        assert_close(run_dw1(lg, I, Kf, s, d, O0=O0, accumulate=True), ref2, KW, "dwconv1d window accumulate")
+
+
+@pytest.mark.parametrize("s,d", [(1, 1), (2, 1), (1, 2), (2, 2)])
+def test_dwconv2d_window_kernels(lg, lgo, s, d):
+    for N, H, W, C in [(2, 37, 41, 24), (1, 2 * d + 1, 2 * d + 1, 4), (1, 2 * d + 1 + 5 * s, 2 * d + 1 + s, 8)]:
+        I, Kf = si.dwconv2d_inputs(136, N, H, W, C, 3, 3)
+        ref = lgo.dwconv2d_nhwc_hwc(I, Kf, stride=(s, s), dilation=(d, d))
+        assert_close(run_dw2(lg, I, Kf, (s, s), (d, d)), ref, 9, f"dwconv2d window {(N, H, W, C, s, d)}")
+        O0 = si.uniform(137, s, ref.shape, -1, 1)
+        ref2 = O0.copy(); lgo.dwconv2d_nhwc_hwc(I, Kf, ref2, stride=(s, s), dilation=(d, d), accumulate=True)
+        assert_close(run_dw2(lg, I, Kf, (s, s), (d, d), O0=O0, accumulate=True), ref2, 9, "dwconv2d window accumulate")
+
+
 def test_dwconv_accumulate_and_delta(lg, lgo):
     I, Kf = si.dwconv1d_inputs(132, 2, 50, 16, 3)
     O0 = si.uniform(132, 9, (2, 48, 16), -1, 1)
