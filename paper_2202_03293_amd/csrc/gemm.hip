@@ -176,6 +176,14 @@ extern "C" int lg_conv2d_nhwc_hwcf(const float* I, const float* Kf, float* O,
         return LG_ERR_INVALID_ARG;
     if (M >= (int64_t)1 << 31 || F >= (int64_t)1 << 31 || Kg >= (int64_t)1 << 31) return LG_ERR_UNSUPPORTED;
     const bool vec = (C % 4 == 0) && (F % 4 == 0) && aligned16(I) && aligned16(Kf) && aligned16(O);
+    if (KH == 1 && KW == 1 && SH == 1 && SW == 1) {
+        // a 1x1 filter at stride 1 reads every pixel once: the input already is the row-major M x C matrix
+        GemmArgs mm{};
+        mm.A = I; mm.B = Kf; mm.C = O;
+        mm.M = M; mm.N = F; mm.K = C;
+        mm.lda = C; mm.ldb = F; mm.ldc = F;
+        return run_gemm(mm, Layout::NN, vec, accumulate, workspace, workspace_bytes, s);
+    }
     GemmArgs a{};
     a.A = I; a.B = Kf; a.C = O;
     a.M = M; a.N = F; a.K = Kg;

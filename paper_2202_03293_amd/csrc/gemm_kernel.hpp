@@ -150,8 +150,11 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
     const int lq = (t % T::QPR) ^ T::swizzle(r0);
 
     // conv: element offset of GEMM row m = (n, oh, ow) at filter tap (0, 0), channel 0; grows with m
+    // (M, OH, OW < 2^31 -- the host checks -- so the divisions are 32-bit: several times cheaper)
     auto conv_row_base = [&](int64_t m) -> int64_t {
-        const int64_t ow = m % p.g.OW, oh = (m / p.g.OW) % p.g.OH, n = m / (p.g.OW * p.g.OH);
+        const uint32_t mu = (uint32_t)m, OWu = (uint32_t)p.g.OW, OHu = (uint32_t)p.g.OH;
+        const uint32_t q = mu / OWu;
+        const int64_t ow = mu - q * OWu, n = q / OHu, oh = q - (uint32_t)n * OHu;
         return ((n * p.g.H + oh * p.g.SH) * p.g.W + ow * p.g.SW) * p.g.C;
     };
     // R-kind row bases (element offset of the row's k = 0; -1 when the row is outside the matrix)

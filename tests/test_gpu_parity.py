@@ -240,6 +240,9 @@ CONV_SMALL = [
     (2, 1, 40, 8, 12, 1, 5, (1, 2), (1, 3)),        # 1-D convolution as H = KH = 1
     (4, 18, 18, 32, 64, 3, 3, (1, 1), (1, 1)),      # the paper's channel/filter counts (C, F) = (32, 64)
     (1, 40, 40, 16, 136, 3, 3, (1, 1), (1, 1)),
+    (3, 17, 19, 24, 40, 1, 1, (1, 1), (1, 1)),      # 1x1 at stride 1: runs as the plain matmul
+    (2, 33, 31, 64, 64, 1, 1, (1, 1), (2, 3)),      # dilation is irrelevant to a 1x1 filter
+    (2, 9, 9, 5, 3, 1, 1, (1, 1), (1, 1)),
 ]
 
 
