@@ -80,7 +80,48 @@ __global__ __launch_bounds__(kRThreads) void reduce_rows_kernel(
     }
 }
 
-constexpr int kCRowsPerWave = 64;   // rows one lane adds sequentially before the cross-wave tree
+// Short rows (at most 64 accesses per row): a wavefront holds 64 / L rows at once, L = lanes per row
+// (a power of two), and U batches of rows in flight, so no lane idles and each lane has U loads
+// outstanding.  The row sum is a butterfly over the L lanes of a row.
+template <bool VEC>
+__global__ __launch_bounds__(kRThreads) void reduce_rows_short_kernel(
+    const float* __restrict__ in, float* __restrict__ out,
+    int64_t R, int64_t Cn, int64_t ld, int accumulate, int L) {
+    constexpr int W = VEC ? 4 : 1;
+    constexpr int U = 4;
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    const int G = kWave / L;                        // rows per wavefront per batch
+    const int sub = lane % L, rg = lane / L;
+    const int64_t nw = Cn / W;                      // accesses per row (<= L)
+    const int64_t row0 = ((int64_t)blockIdx.x * kRWaves + wave) * (G * U) + rg;
+    float s[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t row = row0 + (int64_t)G * u;
+        s[u] = 0.f;
+        if (row < R && sub < nw) {
+            const float* p = in + row * ld + W * sub;
+            if constexpr (VEC) {
+                const float4 v = load_stream4(p);
+                s[u] = (v.x + v.y) + (v.z + v.w);
+            } else {
+                s[u] = *p;
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        float t = s[u];
+        for (int off = L / 2; off > 0; off >>= 1) t += __shfl_xor(t, off, kWave);
+        const int64_t row = row0 + (int64_t)G * u;
+        if (sub == 0 && row < R) {
+            if (accumulate) t += out[row];
+            out[row] = t;
+        }
+    }
+}
+
+constexpr int kCRowsPerWave = 64;   // fewest rows a workgroup takes (16 per wavefront of a 4-wave workgroup)
 constexpr int kCMaxSplit = 1024;
 
 // Stage 1 of out[j] = sum_i in[i,j]: workgroup (bx, by) sums rows [by*rows_per_wg, ...) of the
@@ -144,24 +185,106 @@ __global__ __launch_bounds__(NTH) void reduce_cols_kernel(
     }
 }
 
-// Stage 2: out[j] (+)= sum_s partial[s][j], in a fixed order (pairwise over four running sums).
-__global__ __launch_bounds__(kRThreads) void reduce_cols_combine_kernel(
+// Stage 1 for narrow inputs (at most 32 accesses per row): L lanes (a power of two) cover a row, so
+// a wavefront reads 64 / L rows per access and no lane idles; the row groups of a wavefront are
+// summed by a butterfly, the wavefronts through LDS as above.  One column strip (blockIdx.x = 0).
+template <bool VEC, int NTH>
+__global__ __launch_bounds__(NTH) void reduce_cols_narrow_kernel(
+    const float* __restrict__ in, float* __restrict__ dst,
+    int64_t R, int64_t Cn, int64_t ld, int64_t rows_per_wg, int64_t ldp, int final_accumulate, int L) {
+    constexpr int W = VEC ? 4 : 1;
+    constexpr int NW = NTH / kWave;
+    constexpr int U = 8;                            // rows in flight per lane
+    __shared__ float part[NW][32 * W];
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    const int G = kWave / L;
+    const int cq = lane % L, rg = lane / L;
+    const int64_t col = (int64_t)cq * W;
+    const int64_t r0 = (int64_t)blockIdx.y * rows_per_wg;
+    const int64_t r1 = (r0 + rows_per_wg < R) ? r0 + rows_per_wg : R;
+    const int64_t step = (int64_t)NW * G;           // rows between a lane's successive accesses
+    float acc[2][W];
+#pragma unroll
+    for (int w = 0; w < W; ++w) acc[0][w] = acc[1][w] = 0.f;
+    if (col < Cn) {
+        const float* p = in + col;
+        int64_t r = r0 + (int64_t)wave * G + rg;
+        for (; r + (U - 1) * step < r1; r += U * step) {
+            float v[U][W];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if constexpr (VEC) {
+                    const float4 q = load_stream4(p + (r + u * step) * ld);
+                    v[u][0] = q.x; v[u][1] = q.y; v[u][2] = q.z; v[u][3] = q.w;
+                } else {
+                    v[u][0] = p[(r + u * step) * ld];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int w = 0; w < W; ++w) acc[u & 1][w] += v[u][w];
+        }
+        for (; r < r1; r += step) {
+            if constexpr (VEC) {
+                const float4 q = load_stream4(p + r * ld);
+                acc[0][0] += q.x; acc[0][1] += q.y; acc[0][2] += q.z; acc[0][3] += q.w;
+            } else {
+                acc[0][0] += p[r * ld];
+            }
+        }
+    }
+#pragma unroll
+    for (int w = 0; w < W; ++w) {
+        float t = acc[0][w] + acc[1][w];
+        for (int off = L; off < kWave; off <<= 1) t += __shfl_xor(t, off, kWave);
+        if (rg == 0) part[wave][cq * W + w] = t;
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < L * W; c += NTH) {
+        if (c < Cn) {
+            float tot = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; w += 4) tot += (part[w][c] + part[w + 1][c]) + (part[w + 2][c] + part[w + 3][c]);
+            float* o = dst + (int64_t)blockIdx.y * ldp + c;
+            if (final_accumulate) tot += *o;
+            *o = tot;
+        }
+    }
+}
+
+// Stage 2: out[j] (+)= sum_s partial[s][j], in a fixed order.  A workgroup owns 64 columns; its NSL
+// split-lanes per column each add every NSL-th partial (four running sums), then a tree in LDS
+// adds the split-lanes.  NSL = 16 when there are many partials (tall narrow inputs), else 4.
+template <int NSL>
+__global__ __launch_bounds__(64 * NSL) void reduce_cols_combine_kernel(
     const float* __restrict__ partial, float* __restrict__ out,
     int64_t Cn, int64_t ldp, int splits, int accumulate) {
-    const int64_t j = (int64_t)blockIdx.x * kRThreads + threadIdx.x;
-    if (j >= Cn) return;
+    __shared__ float part[NSL][64];
+    const int c = threadIdx.x % 64, sl = threadIdx.x / 64;
+    const int64_t j = (int64_t)blockIdx.x * 64 + c;
     float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-    int s = 0;
-    for (; s + 3 < splits; s += 4) {
-        a0 += partial[(int64_t)s * ldp + j];
-        a1 += partial[(int64_t)(s + 1) * ldp + j];
-        a2 += partial[(int64_t)(s + 2) * ldp + j];
-        a3 += partial[(int64_t)(s + 3) * ldp + j];
+    if (j < Cn) {
+        int sp = sl;
+        for (; sp + 3 * NSL < splits; sp += 4 * NSL) {
+            a0 += partial[(int64_t)sp * ldp + j];
+            a1 += partial[(int64_t)(sp + NSL) * ldp + j];
+            a2 += partial[(int64_t)(sp + 2 * NSL) * ldp + j];
+            a3 += partial[(int64_t)(sp + 3 * NSL) * ldp + j];
+        }
+        for (; sp < splits; sp += NSL) a0 += partial[(int64_t)sp * ldp + j];
     }
-    for (; s < splits; ++s) a0 += partial[(int64_t)s * ldp + j];
-    float tot = (a0 + a1) + (a2 + a3);
-    if (accumulate) tot += out[j];
-    out[j] = tot;
+    part[sl][c] = (a0 + a1) + (a2 + a3);
+    __syncthreads();
+    for (int half = NSL / 2; half > 0; half /= 2) {
+        if (sl < half) part[sl][c] += part[sl + half][c];
+        __syncthreads();
+    }
+    if (sl == 0 && j < Cn) {
+        float tot = part[0][c];
+        if (accumulate) tot += out[j];
+        out[j] = tot;
+    }
 }
 
 __global__ void fill_zero_kernel(float* out, int64_t n) {
@@ -173,9 +296,22 @@ struct ColPlan { int64_t splits, rows_per_wg, ldp; bool big; };
 
 static ColPlan plan_cols(int64_t R, int64_t Cn) {
     ColPlan p;
-    p.big = R >= 2048;                                                  // 16-wave workgroups, 512 rows each
-    const int64_t rows_per_wg_min = p.big ? 512 : (int64_t)kCRowsPerWave * kRWaves;
-    int64_t splits = cdiv(R, rows_per_wg_min);
+    const int64_t strips = cdiv(Cn, 256);          // column strips of the 128-bit kernel
+    // 16-wave workgroups over 512 rows each are the fastest shape (measured), as long as they still
+    // make more than a hundred workgroups; otherwise 4-wave workgroups, about 2048 of them, over at
+    // least 64 rows each -- 256 once the strips alone give every CU a workgroup (a second launch to
+    // combine the chunks then costs more than the extra parallelism returns).
+    p.big = R >= 2048 && strips * cdiv(R, 512) >= 128;
+    int64_t rows;
+    if (p.big) {
+        rows = 512;
+    } else {
+        const int64_t want = cdiv(2048, strips);   // row chunks wanted
+        const int64_t least = strips >= 256 ? (int64_t)kCRowsPerWave * kRWaves : kCRowsPerWave;
+        rows = cdiv(R, want);
+        if (rows < least) rows = least;
+    }
+    int64_t splits = cdiv(R, rows);
     if (splits > kCMaxSplit) splits = kCMaxSplit;
     if (splits < 1) splits = 1;
     p.rows_per_wg = cdiv(R, splits);
@@ -195,6 +331,17 @@ extern "C" int lg_reduce_rows(const float* in, float* out, int64_t R, int64_t Cn
     if (Cn > 0 && overlaps(in, ((R - 1) * ld + Cn) * 4, out, R * 4)) return LG_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool vec = Cn > 0 && (Cn % 4 == 0) && (ld % 4 == 0) && aligned16(in);
+    const int64_t accesses = vec ? Cn / 4 : Cn;     // per row
+    if (accesses >= 1 && accesses <= kWave) {
+        int L = 1;
+        while (L < accesses) L *= 2;
+        const int64_t rows_per_wg = (int64_t)kRWaves * (kWave / L) * 4;
+        const int64_t nb = cdiv(R, rows_per_wg);
+        if (nb > kMaxGrid) return LG_ERR_UNSUPPORTED;
+        if (vec) hipLaunchKernelGGL(reduce_rows_short_kernel<true>, dim3((unsigned)nb), dim3(kRThreads), 0, s, in, out, R, Cn, ld, accumulate, L);
+        else     hipLaunchKernelGGL(reduce_rows_short_kernel<false>, dim3((unsigned)nb), dim3(kRThreads), 0, s, in, out, R, Cn, ld, accumulate, L);
+        return launch_status();
+    }
     const bool wg_per_row = Cn >= 4096;
     const int64_t blocks = wg_per_row ? R : cdiv(R, kRWaves);
     if (blocks > kMaxGrid) return LG_ERR_UNSUPPORTED;
@@ -241,19 +388,34 @@ extern "C" int lg_reduce_cols(const float* in, float* out, int64_t R, int64_t Cn
     }
     const bool vec = (Cn % 4 == 0) && (ld % 4 == 0) && aligned16(in);
     const int64_t bx = cdiv(Cn, vec ? 256 : 64);
-    if (bx > kMaxGrid || p.splits > 65535) return LG_ERR_UNSUPPORTED;
+    if (bx > kMaxGrid || cdiv(Cn, 64) > kMaxGrid || p.splits > 65535) return LG_ERR_UNSUPPORTED;
     const dim3 g((unsigned)bx, (unsigned)p.splits), b(kRThreads), b16(1024);
     float* dst = p.splits > 1 ? static_cast<float*>(workspace) : out;
     const int64_t ldp = p.splits > 1 ? p.ldp : 0;
     const int facc = p.splits > 1 ? 0 : accumulate;
+    const int64_t accesses = vec ? Cn / 4 : Cn;     // per row
+    if (accesses <= 32) {                           // narrow: several rows per wavefront access
+        int L = 1;
+        while (L < accesses) L *= 2;
+        const dim3 gn(1, (unsigned)p.splits);
+        if (vec && p.big) hipLaunchKernelGGL((reduce_cols_narrow_kernel<true, 1024>), gn, b16, 0, s, in, dst, R, Cn, ld, p.rows_per_wg, ldp, facc, L);
+        else if (vec)     hipLaunchKernelGGL((reduce_cols_narrow_kernel<true, 256>), gn, b, 0, s, in, dst, R, Cn, ld, p.rows_per_wg, ldp, facc, L);
+        else if (p.big)   hipLaunchKernelGGL((reduce_cols_narrow_kernel<false, 1024>), gn, b16, 0, s, in, dst, R, Cn, ld, p.rows_per_wg, ldp, facc, L);
+        else              hipLaunchKernelGGL((reduce_cols_narrow_kernel<false, 256>), gn, b, 0, s, in, dst, R, Cn, ld, p.rows_per_wg, ldp, facc, L);
+    } else
     if (vec && p.big) hipLaunchKernelGGL((reduce_cols_kernel<true, 1024>), g, b16, 0, s, in, dst, R, Cn, ld, p.rows_per_wg, ldp, facc);
     else if (vec)     hipLaunchKernelGGL((reduce_cols_kernel<true, 256>), g, b, 0, s, in, dst, R, Cn, ld, p.rows_per_wg, ldp, facc);
     else if (p.big)   hipLaunchKernelGGL((reduce_cols_kernel<false, 1024>), g, b16, 0, s, in, dst, R, Cn, ld, p.rows_per_wg, ldp, facc);
     else              hipLaunchKernelGGL((reduce_cols_kernel<false, 256>), g, b, 0, s, in, dst, R, Cn, ld, p.rows_per_wg, ldp, facc);
     if (launch_status() != LG_OK) return LG_ERR_RUNTIME;
     if (p.splits > 1) {
-        hipLaunchKernelGGL(reduce_cols_combine_kernel, dim3((unsigned)cdiv(Cn, kRThreads)), b, 0, s,
-                           static_cast<const float*>(workspace), out, Cn, p.ldp, (int)p.splits, accumulate);
+        const dim3 gc((unsigned)cdiv(Cn, 64));
+        if (p.splits > 16)
+            hipLaunchKernelGGL(reduce_cols_combine_kernel<16>, gc, dim3(1024), 0, s,
+                               static_cast<const float*>(workspace), out, Cn, p.ldp, (int)p.splits, accumulate);
+        else
+            hipLaunchKernelGGL(reduce_cols_combine_kernel<4>, gc, dim3(256), 0, s,
+                               static_cast<const float*>(workspace), out, Cn, p.ldp, (int)p.splits, accumulate);
         return launch_status();
     }
     return LG_OK;

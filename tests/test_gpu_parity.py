@@ -454,7 +454,10 @@ def run_cols(lg, x, out0=None, accumulate=False):
 
 RED_SHAPES = [(250, 960), (1, 1), (7, 5), (64, 4096), (100, 4100), (33, 8191), (513, 64),
               (1000, 3), (5, 20000), (300, 1024), (4096, 8), (129, 260),
-              (2500, 1000), (2049, 260), (4100, 37), (2048, 4096)]
+              (2500, 1000), (2049, 260), (4100, 37), (2048, 4096),
+              # short rows / narrow inputs: several rows per wavefront (128-bit and scalar variants)
+              (70001, 64), (5000, 128), (3001, 100), (9000, 12), (4097, 4), (20000, 1), (777, 31),
+              (2600, 33), (1500, 256), (999, 63), (100003, 2)]
 
 
 @pytest.mark.parametrize("R,Cn", RED_SHAPES)
