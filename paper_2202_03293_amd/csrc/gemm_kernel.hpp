@@ -79,7 +79,7 @@ struct GemmArgs {
 
 // BM x BN output tile per workgroup, BK-deep k-slices, WM x WN register tile per wavefront.
 // MINW = wavefronts per SIMD the register allocation must leave room for (what LDS lets a CU hold).
-template <int BM_, int BN_, int BK_, int WM_, int WN_, int MINW_, int STAGES_ = 3>
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int MINW_, int STAGES_ = 3, bool KTAIL_ = true>
 struct Tile {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MINW = MINW_;
     static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN;
@@ -95,6 +95,10 @@ struct Tile {
     // publishes slices one step early, so a wave fetches the first fragments of the next slice
     // while it still multiplies the current one (see the main loop).
     static constexpr int STAGES = STAGES_;
+    // Whether a k tail (slab depth not a multiple of BK) may follow the transfer ring as one
+    // register-staged slice, or sends the whole tile down the register-staged path.  The big tile
+    // opts out: the state the tail keeps alive across the ring does not fit its register budget.
+    static constexpr bool KTAIL = KTAIL_;
     static_assert(STAGES == 3 || STAGES == 4, "ring depth");
     static constexpr int LDS_FLOATS = STAGES * (BM * BK + BK * BN);
     static_assert(BK == 16 || BK == 32 || BK == 64, "k-slice depth");
@@ -542,10 +546,17 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
         a_small = (int64_t)(TA ? BK : BM) * p.lda * 4 < lim;
     }
     const bool b_small = (int64_t)(TB ? BN : BK) * p.ldb * 4 < lim;
-    const bool interior = VEC && a_small && b_small && (m0 + BM <= p.M) && (n0 + BN <= p.N) &&
-                          ((kend - kbeg) % BK == 0);
-    if (nslices > 0) {
-        if (interior && T::STAGES == 4) {
+    // Interior tiles run their whole slices through the transfer rings below and a k tail (a slab whose
+    // depth is not a multiple of BK) as one last predicated, register-staged slice.
+    // (the flag is wave-uniform; readfirstlane says so to the compiler where 32-bit divisions left it
+    // in vector registers, so that the branches below stay scalar)
+    const bool interior = __builtin_amdgcn_readfirstlane(
+        (int)(VEC && a_small && b_small && (m0 + BM <= p.M) && (n0 + BN <= p.N) &&
+              (T::KTAIL || (kend - kbeg) % BK == 0))) != 0;
+    const int nring = interior ? (int)((kend - kbeg) / BK) : 0;
+    const bool ktail = T::KTAIL && interior && (kend - kbeg) % BK != 0;
+    {
+        if (nring > 0 && T::STAGES == 4) {
             // Ring of four LDS stages, transfers three slices ahead.  The barrier that ends step s makes
             // slice s+2 visible (each wave first waits for its own transfers of that slice), so during
             // step s+1 every wave may already read slice s+2.  It also guarantees that nobody still
@@ -553,40 +564,40 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
             constexpr int L = APT + BPT;           // transfers per slice per wave
             init_full();
             issue_slice(0);
-            if (nslices > 1) issue_slice(1);
-            if (nslices > 2) { issue_slice(2); dma_wait<L>(); } else { dma_wait<0>(); }
+            if (nring > 1) issue_slice(1);
+            if (nring > 2) { issue_slice(2); dma_wait<L>(); } else { dma_wait<0>(); }
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
             fetch_R(0, 0);
             fetch_C(0, 0, 0);
             auto step = [&](auto stage_c, int s) {
                 constexpr int stage = decltype(stage_c)::value;
-                if (s + 3 < nslices) issue_slice((stage + 3) % 4);
+                if (s + 3 < nring) issue_slice((stage + 3) % 4);
                 compute_slice_ahead(stage, (stage + 1) % 4, stage & 1);
-                if (s + 2 < nslices) {
-                    if (s + 3 < nslices) dma_wait<L>(); else dma_wait<0>();
+                if (s + 2 < nring) {
+                    if (s + 3 < nring) dma_wait<L>(); else dma_wait<0>();
                     __builtin_amdgcn_s_barrier();
                     asm volatile("" ::: "memory");
                 }
             };
             int s = 0;
-            for (; s + 4 <= nslices; s += 4) {
+            for (; s + 4 <= nring; s += 4) {
                 step(std::integral_constant<int, 0>{}, s);
                 step(std::integral_constant<int, 1>{}, s + 1);
                 step(std::integral_constant<int, 2>{}, s + 2);
                 step(std::integral_constant<int, 3>{}, s + 3);
             }
-            if (s < nslices) step(std::integral_constant<int, 0>{}, s);
-            if (s + 1 < nslices) step(std::integral_constant<int, 1>{}, s + 1);
-            if (s + 2 < nslices) step(std::integral_constant<int, 2>{}, s + 2);
-        } else if (interior) {
+            if (s < nring) step(std::integral_constant<int, 0>{}, s);
+            if (s + 1 < nring) step(std::integral_constant<int, 1>{}, s + 1);
+            if (s + 2 < nring) step(std::integral_constant<int, 2>{}, s + 2);
+        } else if (nring > 0) {
             // Ring of three LDS stages, transfers two slices ahead.  Each wave waits for its own
             // transfers of the slice needed next (vmcnt counts them in order), then the barrier makes
             // everybody's visible and also guarantees nobody still reads the stage refilled next.
             constexpr int L = APT + BPT;           // transfers per slice per wave
             init_full();
             issue_slice(0);
-            if (nslices > 1) {
+            if (nring > 1) {
                 issue_slice(1);
                 dma_wait<L>();
             } else {
@@ -598,24 +609,24 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
             // lane constant plus an immediate (no vector ALU work per slice).
             auto step = [&](auto stage_c, int s) {
                 constexpr int stage = decltype(stage_c)::value;
-                if (s + 2 < nslices) issue_slice((stage + 2) % 3);
+                if (s + 2 < nring) issue_slice((stage + 2) % 3);
                 compute_slice(stage);
-                if (s + 1 < nslices) {
-                    if (s + 2 < nslices) dma_wait<L>(); else dma_wait<0>();
+                if (s + 1 < nring) {
+                    if (s + 2 < nring) dma_wait<L>(); else dma_wait<0>();
                     __builtin_amdgcn_s_barrier();
                     asm volatile("" ::: "memory");
                 }
             };
             int s = 0;
-            for (; s + 3 <= nslices; s += 3) {
+            for (; s + 3 <= nring; s += 3) {
                 step(std::integral_constant<int, 0>{}, s);
                 step(std::integral_constant<int, 1>{}, s + 1);
                 step(std::integral_constant<int, 2>{}, s + 2);
             }
-            if (s < nslices) step(std::integral_constant<int, 0>{}, s);
-            if (s + 1 < nslices) step(std::integral_constant<int, 1>{}, s + 1);
-        } else {
-            // Edge tiles, k tails, unaligned operands: registers -> LDS, two of the ring's stages.
+            if (s < nring) step(std::integral_constant<int, 0>{}, s);
+            if (s + 1 < nring) step(std::integral_constant<int, 1>{}, s + 1);
+        } else if (!interior && nslices > 0) {
+            // Edge tiles, unaligned operands: registers -> LDS, two of the ring's stages.
             load_slice_edge(kbeg);
             store_slice(0);
             __syncthreads();
@@ -626,6 +637,13 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
                 if (more) store_slice((s + 1) & 1);
                 __syncthreads();
             }
+        }
+        if (ktail) {
+            if (nring > 0) __syncthreads();        // every wave is done with the ring's stages
+            load_slice_edge(kbeg + (int64_t)nring * BK);
+            store_slice(0);
+            __syncthreads();
+            compute_slice(0);
         }
     }
 
@@ -688,7 +706,7 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
 // slice of barrier skew and LDS latency that only other resident workgroups hide (less with the
 // four-stage ring, which fetches across the barrier).  The big tile keeps three stages: a fourth
 // would cost it its second workgroup per CU.
-using Tile0 = Tile<128, 256, 16, 64, 128, 2>;      // waves of 64x128
+using Tile0 = Tile<128, 256, 16, 64, 128, 2, 3, false>;   // waves of 64x128
 using Tile1 = Tile<128, 128, 16, 32, 128, 2, 4>;   // waves of 32x128
 using Tile2 = Tile<128, 64, 16, 32, 64, 3, 4>;     // waves of 32x64 (narrow outputs, e.g. F = 64)
 using Tile3 = Tile<64, 64, 16, 32, 32, 4, 4>;      // waves of 32x32 (small problems)
@@ -724,6 +742,9 @@ inline Plan make_plan(int64_t M, int64_t N, int64_t K) {
         const TileInfo& tl = kTiles[ti];
         const int64_t tm = cdiv(M, tl.bm), tn = cdiv(N, tl.bn);
         const double dead = tl.dead;
+        // tile 0 has no k-tail handling: a k that is not a multiple of its slice depth sends every
+        // tile down the register-staged path
+        const double slow = (ti == 0 && K % tl.bk != 0) ? 1.25 : 1.0;
         const double fill = 3000.0 + tl.occ * tl.bm * tl.bn * 4.0 / 9.0;
         for (int sp : split_menu) {
             if (sp > 1 && kslabs < 2 * sp) break;                // keep at least 128 k per slab
@@ -736,7 +757,7 @@ inline Plan make_plan(int64_t M, int64_t N, int64_t K) {
             const int64_t full = per_cu / tl.occ, rest = per_cu % tl.occ;
             double clocks = (double)full * (nslices * (tl.occ * tl.mfma / tl.eff + dead / tl.occ) + fill);
             if (rest) clocks += nslices * (rest * tl.mfma / tl.eff + dead / rest) + fill;
-            double cost = clocks / clk + 4e-6;
+            double cost = slow * clocks / clk + 4e-6;
             if (splits > 1) cost += 2.0 * splits * M * N * 4.0 / 3.0e12 + 5e-6;
             if (cost < best_cost) {
                 best_cost = cost;

@@ -48,6 +48,9 @@ MATMUL_SHAPES = [
     (33, 4096, 8),
     (2048, 2048, 192), (1024, 1024, 320), (1020, 1000, 264), (2048, 1024, 100),   # mid-size tiles, deep slices
     (6272, 512, 256), (16384, 512, 128),
+    # whole tiles whose k is not a multiple of the slice depth: transfer ring + one predicated tail slice
+    (256, 256, 1000), (512, 384, 2052), (256, 512, 72), (128, 128, 20), (128, 128, 12), (1024, 1024, 1028),
+    (4096, 4096, 56), (2048, 1024, 4104),
 ]
 
 
@@ -243,6 +246,9 @@ CONV_SMALL = [
     (3, 17, 19, 24, 40, 1, 1, (1, 1), (1, 1)),      # 1x1 at stride 1: runs as the plain matmul
     (2, 33, 31, 64, 64, 1, 1, (1, 1), (2, 3)),      # dilation is irrelevant to a 1x1 filter
     (2, 9, 9, 5, 3, 1, 1, (1, 1), (1, 1)),
+    (4, 34, 34, 24, 64, 3, 3, (1, 1), (1, 1)),      # K = 216: thirteen whole slices and a tail of 8
+    (4, 20, 20, 20, 128, 3, 3, (2, 2), (1, 1)),     # K = 180
+    (2, 40, 40, 36, 64, 5, 5, (1, 1), (2, 2)),      # K = 900
 ]
 
 
