@@ -277,19 +277,31 @@ def main():
     # ------------------------------------------------------------------ the paper's small sweep
     if args.sweep:
         def per_launch_us(call, batch=20, reps=7):
+            """(eager, graph): microseconds per launch from batches of back-to-back launches, issued one
+            by one through the Python binding and replayed from a HIP graph of the same batch."""
             for _ in range(batch):
                 call()
             torch.cuda.synchronize()
-            ts = []
-            for _ in range(reps):
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record(stream)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
                 for _ in range(batch):
                     call()
-                b.record(stream)
-                torch.cuda.synchronize()
-                ts.append(a.elapsed_time(b) * 1e3 / batch)
-            return float(np.median(ts))
+
+            def timed(run):
+                ts = []
+                for _ in range(reps):
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record(stream)
+                    run()
+                    b.record(stream)
+                    torch.cuda.synchronize()
+                    ts.append(a.elapsed_time(b) * 1e3 / batch)
+                return float(np.median(ts))
+
+            def eager():
+                for _ in range(batch):
+                    call()
+            return timed(eager), timed(graph.replay)
 
         sweep = []
         for size in (16, 20, 32, 40, 55, 64, 128):
@@ -301,20 +313,20 @@ def main():
                 if ow > 0:
                     O1s = torch.empty((1, ow, 64), device="cuda")
                     w1s = ws(lg.lg_conv1d_workspace_bytes(1, size, 32, 3, 64, st, dl))
-                    us = per_launch_us(lambda: lg.lg_conv1d_nwc_wcf(I1s, K1s, O1s, stride=st, dilation=dl, workspace=w1s))
-                    sweep.append(dict(op="conv1d", size=size, stride=st, dilation=dl, us=us,
-                                      gflops=2.0 * ow * 64 * 3 * 32 / us / 1e3))
+                    us, ug = per_launch_us(lambda: lg.lg_conv1d_nwc_wcf(I1s, K1s, O1s, stride=st, dilation=dl, workspace=w1s))
+                    sweep.append(dict(op="conv1d", size=size, stride=st, dilation=dl, us=us, us_graph=ug,
+                                      gflops=2.0 * ow * 64 * 3 * 32 / ug / 1e3))
                     I2s = dev(si.uniform(5, 2, (1, size, size, 32), -1, 1)); K2s = dev(si.uniform(5, 3, (3, 3, 32, 64), -1, 1))
                     O2s = torch.empty((1, ow, ow, 64), device="cuda")
                     w2s = ws(lg.lg_conv2d_workspace_bytes(1, size, size, 32, 3, 3, 64, st, st, dl, dl))
-                    us = per_launch_us(lambda: lg.lg_conv2d_nhwc_hwcf(I2s, K2s, O2s, stride=(st, st), dilation=(dl, dl),
-                                                                     workspace=w2s))
-                    sweep.append(dict(op="conv2d", size=size, stride=st, dilation=dl, us=us,
-                                      gflops=2.0 * ow * ow * 64 * 9 * 32 / us / 1e3))
+                    us, ug = per_launch_us(lambda: lg.lg_conv2d_nhwc_hwcf(I2s, K2s, O2s, stride=(st, st), dilation=(dl, dl),
+                                                                         workspace=w2s))
+                    sweep.append(dict(op="conv2d", size=size, stride=st, dilation=dl, us=us, us_graph=ug,
+                                      gflops=2.0 * ow * ow * 64 * 9 * 32 / ug / 1e3))
                     Kd = dev(si.uniform(5, 4, (3, 32), -1, 1)); Od = torch.empty((1, ow, 32), device="cuda")
-                    us = per_launch_us(lambda: lg.lg_dwconv1d_nwc_wc(I1s, Kd, Od, stride=st, dilation=dl))
-                    sweep.append(dict(op="dwconv1d", size=size, stride=st, dilation=dl, us=us,
-                                      gbps=4.0 * (ow * 32 + 3 * 32 + size * 32) / us / 1e3))
+                    us, ug = per_launch_us(lambda: lg.lg_dwconv1d_nwc_wc(I1s, Kd, Od, stride=st, dilation=dl))
+                    sweep.append(dict(op="dwconv1d", size=size, stride=st, dilation=dl, us=us, us_graph=ug,
+                                      gbps=4.0 * (ow * 32 + 3 * 32 + size * 32) / ug / 1e3))
         out["sweep"] = sweep
 
     # ------------------------------------------------------------------ CPU oracle baseline
