@@ -288,31 +288,44 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
         return (uint32_t)((((int64_t)cv_kh * p.g.DH * p.g.W + (int64_t)cv_kw * p.g.DW) * p.g.C + cv_c) * 4);
     };
 
-    auto r_loff = [&](int64_t ld, uint32_t* loff, auto per_c) {      // R-kind lane offsets from (row0, kbeg)
+    // Tiles on the M or N boundary use the transfers too: a lane whose row or column lies outside the
+    // matrix fetches the last valid row / column quad instead (in bounds, and what it feeds are
+    // accumulators the epilogue never stores).  `valid` = rows (columns) of the tile inside the matrix.
+    auto r_loff = [&](int64_t ld, uint32_t* loff, int64_t valid, auto per_c) {   // R-kind lane offsets from (row0, kbeg)
 #pragma unroll
-        for (int i = 0; i < decltype(per_c)::value; ++i)
-            loff[i] = (uint32_t)(((int64_t)(r0 + i * T::ROW_STEP) * ld + 4 * lq) * 4);
+        for (int i = 0; i < decltype(per_c)::value; ++i) {
+            int64_t r = r0 + i * T::ROW_STEP;
+            if (r >= valid) r = valid - 1;
+            loff[i] = (uint32_t)((r * ld + 4 * lq) * 4);
+        }
     };
-    auto c_loff = [&](int64_t ld, uint32_t* loff, auto per_c, auto cols_c) {   // C-kind, from (kbeg, col0)
+    auto c_loff = [&](int64_t ld, uint32_t* loff, int64_t valid, auto per_c, auto cols_c) {   // C-kind, from (kbeg, col0)
         constexpr int CQ = decltype(cols_c)::value / 4;
 #pragma unroll
         for (int i = 0; i < decltype(per_c)::value; ++i) {
             const int q = t + i * NTH;
-            loff[i] = (uint32_t)(((int64_t)(q / CQ) * ld + 4 * (q % CQ)) * 4);
+            int64_t c = 4 * (q % CQ);
+            if (c >= valid) c = valid - 4;             // valid is a multiple of 4 on this path
+            loff[i] = (uint32_t)(((int64_t)(q / CQ) * ld + c) * 4);
         }
     };
+    const int64_t m_valid = (p.M - m0 < BM) ? p.M - m0 : BM;
+    const int64_t n_valid = (p.N - n0 < BN) ? p.N - n0 : BN;
     auto init_full = [&]() {
         if constexpr (CONV) {
             // lane offsets are relative to the tile's first row, so only the tile has to span < 2 GiB
             const int64_t base0 = to_scalar(conv_row_base(m0));
             a_base += base0 * 4;
+            auto conv_base_clamped = [&](int i) -> int64_t {   // row base of the lane's i-th row, or of row M-1
+                return a_rowbase[TA ? 0 : i] >= 0 ? a_rowbase[TA ? 0 : i] : conv_row_base(p.M - 1);
+            };
             if (conv_uniform) {
                 su_c = (int)(kbeg % p.g.C);
                 su_kw = (int)((kbeg / p.g.C) % p.g.KW);
                 const int64_t kh = kbeg / (p.g.C * p.g.KW);
                 su_off = (uint32_t)(((kh * p.g.DH * p.g.W + (int64_t)su_kw * p.g.DW) * p.g.C + su_c) * 4);
 #pragma unroll
-                for (int i = 0; i < APT; ++i) a_loff[i] = (uint32_t)((a_rowbase[i] - base0) * 4) + 16u * lq;
+                for (int i = 0; i < APT; ++i) a_loff[i] = (uint32_t)((conv_base_clamped(i) - base0) * 4) + 16u * lq;
             } else {
                 const int64_t k = kbeg + 4 * lq;
                 cv_c = (int)(k % p.g.C);
@@ -320,25 +333,25 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
                 cv_kh = (int)(k / (p.g.C * p.g.KW));
                 cv_off = cv_offset();
 #pragma unroll
-                for (int i = 0; i < APT; ++i) a_loff[i] = (uint32_t)((a_rowbase[i] - base0) * 4);
+                for (int i = 0; i < APT; ++i) a_loff[i] = (uint32_t)((conv_base_clamped(i) - base0) * 4);
             }
         } else if constexpr (TA) {
             a_base += (kbeg * p.lda + m0) * 4;
             a_adv = (int64_t)BK * p.lda * 4;
-            c_loff(p.lda, a_loff, std::integral_constant<int, APT>{}, std::integral_constant<int, BM>{});
+            c_loff(p.lda, a_loff, m_valid, std::integral_constant<int, APT>{}, std::integral_constant<int, BM>{});
         } else {
             a_base += (m0 * p.lda + kbeg) * 4;
             a_adv = BK * 4;
-            r_loff(p.lda, a_loff, std::integral_constant<int, APT>{});
+            r_loff(p.lda, a_loff, m_valid, std::integral_constant<int, APT>{});
         }
         if constexpr (TB) {
             b_base += (n0 * p.ldb + kbeg) * 4;
             b_adv = BK * 4;
-            r_loff(p.ldb, b_loff, std::integral_constant<int, BPT>{});
+            r_loff(p.ldb, b_loff, n_valid, std::integral_constant<int, BPT>{});
         } else {
             b_base += (kbeg * p.ldb + n0) * 4;
             b_adv = (int64_t)BK * p.ldb * 4;
-            c_loff(p.ldb, b_loff, std::integral_constant<int, BPT>{}, std::integral_constant<int, BN>{});
+            c_loff(p.ldb, b_loff, n_valid, std::integral_constant<int, BPT>{}, std::integral_constant<int, BN>{});
         }
     };
     // Start the transfer of the next slice into LDS stage `buf`.
@@ -538,7 +551,7 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
     const int64_t lim = (int64_t)1 << 31;
     bool a_small;
     if constexpr (CONV) {      // rows of the tile x the filter's reach, from the tile's first row
-        const int64_t last = (m0 + BM <= p.M) ? m0 + BM - 1 : m0;
+        const int64_t last = (m0 + BM <= p.M) ? m0 + BM - 1 : p.M - 1;
         const int64_t kh_taps = p.K / (p.g.KW * p.g.C);
         const int64_t reach = ((kh_taps - 1) * p.g.DH * p.g.W + (p.g.KW - 1) * p.g.DW + 1) * p.g.C;
         a_small = (conv_row_base(last) - conv_row_base(m0) + reach + BK) * 4 < lim;
@@ -546,13 +559,13 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
         a_small = (int64_t)(TA ? BK : BM) * p.lda * 4 < lim;
     }
     const bool b_small = (int64_t)(TB ? BN : BK) * p.ldb * 4 < lim;
-    // Interior tiles run their whole slices through the transfer rings below and a k tail (a slab whose
-    // depth is not a multiple of BK) as one last predicated, register-staged slice.
+    // Aligned operands ("interior", boundary tiles included, see r_loff) run their whole slices through
+    // the transfer rings below and a k tail (a slab whose depth is not a multiple of BK) as one last
+    // predicated, register-staged slice.
     // (the flag is wave-uniform; readfirstlane says so to the compiler where 32-bit divisions left it
     // in vector registers, so that the branches below stay scalar)
     const bool interior = __builtin_amdgcn_readfirstlane(
-        (int)(VEC && a_small && b_small && (m0 + BM <= p.M) && (n0 + BN <= p.N) &&
-              (T::KTAIL || (kend - kbeg) % BK == 0))) != 0;
+        (int)(VEC && a_small && b_small && (T::KTAIL || (kend - kbeg) % BK == 0))) != 0;
     const int nring = interior ? (int)((kend - kbeg) / BK) : 0;
     const bool ktail = T::KTAIL && interior && (kend - kbeg) % BK != 0;
     {
@@ -626,7 +639,7 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
             if (s < nring) step(std::integral_constant<int, 0>{}, s);
             if (s + 1 < nring) step(std::integral_constant<int, 1>{}, s + 1);
         } else if (!interior && nslices > 0) {
-            // Edge tiles, unaligned operands: registers -> LDS, two of the ring's stages.
+            // Unaligned operands (and spans past 32-bit offsets): registers -> LDS, two of the ring's stages.
             load_slice_edge(kbeg);
             store_slice(0);
             __syncthreads();
