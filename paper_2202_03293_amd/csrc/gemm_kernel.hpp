@@ -47,6 +47,13 @@ __device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t 
                  :: "s"(lds), "v"(voff), "s"(base) : "memory");
 }
 
+// The same with 4 bytes per lane (lane l's word lands at lds + 4*l): for operands whose rows are not
+// 16-byte aligned.  Four times the instructions for the same bytes.
+__device__ __forceinline__ void dma4(const void* base, uint32_t voff, uint32_t lds) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                 :: "s"(lds), "v"(voff), "s"(base) : "memory");
+}
+
 // Wait until at most N of this wave's global->LDS transfers are still in flight.
 template <int N>
 __device__ __forceinline__ void dma_wait() {
@@ -269,7 +276,9 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
     // here: they take issue slots from the matrix pipe, which small tiles feel).
     const char* a_base = reinterpret_cast<const char*>(p.A);
     const char* b_base = reinterpret_cast<const char*>(p.B);
-    uint32_t a_loff[APT], b_loff[BPT];
+    // transfers per lane per slice: one per float4 of the slice (aligned operands), one per float otherwise
+    constexpr int APD = VEC ? APT : 4 * APT, BPD = VEC ? BPT : 4 * BPT;
+    uint32_t a_loff[APD], b_loff[BPD];
     int64_t a_adv = 0, b_adv = 0;                  // bytes per k-slice
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 
@@ -292,21 +301,45 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
     // matrix fetches the last valid row / column quad instead (in bounds, and what it feeds are
     // accumulators the epilogue never stores).  `valid` = rows (columns) of the tile inside the matrix.
     auto r_loff = [&](int64_t ld, uint32_t* loff, int64_t valid, auto per_c) {   // R-kind lane offsets from (row0, kbeg)
+        if constexpr (VEC) {
 #pragma unroll
-        for (int i = 0; i < decltype(per_c)::value; ++i) {
-            int64_t r = r0 + i * T::ROW_STEP;
-            if (r >= valid) r = valid - 1;
-            loff[i] = (uint32_t)((r * ld + 4 * lq) * 4);
+            for (int i = 0; i < decltype(per_c)::value; ++i) {
+                int64_t r = r0 + i * T::ROW_STEP;
+                if (r >= valid) r = valid - 1;
+                loff[i] = (uint32_t)((r * ld + 4 * lq) * 4);
+            }
+        } else {
+            // float number f = t + i*NTH of the slice sits at LDS float offset f: row f / BK, physical
+            // quad (f % BK) / 4, element f % 4 -- the lane fetches the logical quad's element
+#pragma unroll
+            for (int i = 0; i < 4 * decltype(per_c)::value; ++i) {
+                const int f = t + i * NTH;
+                int64_t r = f / BK;
+                const int kq = (((f % BK) / 4) ^ T::swizzle((int)r)) * 4 + f % 4;
+                if (r >= valid) r = valid - 1;
+                loff[i] = (uint32_t)((r * ld + kq) * 4);
+            }
         }
     };
     auto c_loff = [&](int64_t ld, uint32_t* loff, int64_t valid, auto per_c, auto cols_c) {   // C-kind, from (kbeg, col0)
-        constexpr int CQ = decltype(cols_c)::value / 4;
+        if constexpr (VEC) {
+            constexpr int CQ = decltype(cols_c)::value / 4;
 #pragma unroll
-        for (int i = 0; i < decltype(per_c)::value; ++i) {
-            const int q = t + i * NTH;
-            int64_t c = 4 * (q % CQ);
-            if (c >= valid) c = valid - 4;             // valid is a multiple of 4 on this path
-            loff[i] = (uint32_t)(((int64_t)(q / CQ) * ld + c) * 4);
+            for (int i = 0; i < decltype(per_c)::value; ++i) {
+                const int q = t + i * NTH;
+                int64_t c = 4 * (q % CQ);
+                if (c >= valid) c = valid - 4;         // valid is a multiple of 4 on this path
+                loff[i] = (uint32_t)(((int64_t)(q / CQ) * ld + c) * 4);
+            }
+        } else {
+            constexpr int COLS = decltype(cols_c)::value;
+#pragma unroll
+            for (int i = 0; i < 4 * decltype(per_c)::value; ++i) {
+                const int f = t + i * NTH;
+                int64_t c = f % COLS;
+                if (c >= valid) c = valid - 1;
+                loff[i] = (uint32_t)(((int64_t)(f / COLS) * ld + c) * 4);
+            }
         }
     };
     const int64_t m_valid = (p.M - m0 < BM) ? p.M - m0 : BM;
@@ -324,8 +357,19 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
                 su_kw = (int)((kbeg / p.g.C) % p.g.KW);
                 const int64_t kh = kbeg / (p.g.C * p.g.KW);
                 su_off = (uint32_t)(((kh * p.g.DH * p.g.W + (int64_t)su_kw * p.g.DW) * p.g.C + su_c) * 4);
+                if constexpr (VEC) {
 #pragma unroll
-                for (int i = 0; i < APT; ++i) a_loff[i] = (uint32_t)((conv_base_clamped(i) - base0) * 4) + 16u * lq;
+                    for (int i = 0; i < APT; ++i) a_loff[i] = (uint32_t)((conv_base_clamped(i) - base0) * 4) + 16u * lq;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < APD; ++i) {
+                        const int f = t + i * NTH;
+                        const int r = f / BK;
+                        const int kq = (((f % BK) / 4) ^ T::swizzle(r)) * 4 + f % 4;
+                        const int64_t m = (m0 + r < p.M) ? m0 + r : p.M - 1;
+                        a_loff[i] = (uint32_t)((conv_row_base(m) - base0 + kq) * 4);
+                    }
+                }
             } else {
                 const int64_t k = kbeg + 4 * lq;
                 cv_c = (int)(k % p.g.C);
@@ -353,22 +397,30 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
             b_adv = (int64_t)BK * p.ldb * 4;
             c_loff(p.ldb, b_loff, n_valid, std::integral_constant<int, BPT>{}, std::integral_constant<int, BN>{});
         }
+        // the transfer instruction takes its base from scalar registers: pin both there once, so that
+        // the per-slice advances below are scalar adds whatever else uses the operand pointers
+        a_base = reinterpret_cast<const char*>(to_scalar(reinterpret_cast<int64_t>(a_base)));
+        b_base = reinterpret_cast<const char*>(to_scalar(reinterpret_cast<int64_t>(b_base)));
     };
     // Start the transfer of the next slice into LDS stage `buf`.
     auto issue_slice = [&](int buf) {
-        float* as = As + buf * (BM * BK) + 4 * 64 * wave_u;
-        float* bs = Bs + buf * (BK * BN) + 4 * 64 * wave_u;
+        constexpr int WORDS = VEC ? 4 : 1;         // floats per lane per transfer
+        float* as = As + buf * (BM * BK) + WORDS * 64 * wave_u;
+        float* bs = Bs + buf * (BK * BN) + WORDS * 64 * wave_u;
+        auto dma = [&](const void* base, uint32_t voff, uint32_t lds_a) __attribute__((always_inline)) {
+            if constexpr (VEC) dma16(base, voff, lds_a); else dma4(base, voff, lds_a);
+        };
         if (CONV && conv_uniform) {
             const char* ab = a_base + su_off;
 #pragma unroll
-            for (int i = 0; i < APT; ++i) dma16(ab, a_loff[i], lds_addr(as + 4 * i * NTH));
+            for (int i = 0; i < APD; ++i) dma(ab, a_loff[i], lds_addr(as + WORDS * i * NTH));
         } else {
             const uint32_t ko = CONV ? cv_off : 0u;
 #pragma unroll
-            for (int i = 0; i < APT; ++i) dma16(a_base, a_loff[i] + ko, lds_addr(as + 4 * i * NTH));
+            for (int i = 0; i < APD; ++i) dma(a_base, a_loff[i] + ko, lds_addr(as + WORDS * i * NTH));
         }
 #pragma unroll
-        for (int i = 0; i < BPT; ++i) dma16(b_base, b_loff[i], lds_addr(bs + 4 * i * NTH));
+        for (int i = 0; i < BPD; ++i) dma(b_base, b_loff[i], lds_addr(bs + WORDS * i * NTH));
         if (CONV && conv_uniform) {
             su_c += BK;
             const bool w1 = su_c >= cvC;
@@ -559,13 +611,16 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
         a_small = (int64_t)(TA ? BK : BM) * p.lda * 4 < lim;
     }
     const bool b_small = (int64_t)(TB ? BN : BK) * p.ldb * 4 < lim;
-    // Aligned operands ("interior", boundary tiles included, see r_loff) run their whole slices through
-    // the transfer rings below and a k tail (a slab whose depth is not a multiple of BK) as one last
-    // predicated, register-staged slice.
+    // All tiles (boundary tiles included, see r_loff) run their whole slices through the transfer rings
+    // below -- 16 bytes per lane for aligned operands, 4 otherwise -- and a k tail (a slab whose depth
+    // is not a multiple of BK) as one last predicated, register-staged slice.  Left to the
+    // register-staged path: spans beyond 32-bit offsets, and unaligned convolutions whose channel
+    // count is not a multiple of BK.
     // (the flag is wave-uniform; readfirstlane says so to the compiler where 32-bit divisions left it
     // in vector registers, so that the branches below stay scalar)
     const bool interior = __builtin_amdgcn_readfirstlane(
-        (int)(VEC && a_small && b_small && (T::KTAIL || (kend - kbeg) % BK == 0))) != 0;
+        (int)(a_small && b_small && (T::KTAIL || (kend - kbeg) % BK == 0) &&
+              (VEC || !CONV || conv_uniform))) != 0;
     const int nring = interior ? (int)((kend - kbeg) / BK) : 0;
     const bool ktail = T::KTAIL && interior && (kend - kbeg) % BK != 0;
     {
@@ -574,7 +629,7 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
             // slice s+2 visible (each wave first waits for its own transfers of that slice), so during
             // step s+1 every wave may already read slice s+2.  It also guarantees that nobody still
             // reads slice s, whose stage the transfer issued in step s+1 refills.
-            constexpr int L = APT + BPT;           // transfers per slice per wave
+            constexpr int L = APD + BPD;           // transfers per slice per wave
             init_full();
             issue_slice(0);
             if (nring > 1) issue_slice(1);
@@ -607,7 +662,7 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
             // Ring of three LDS stages, transfers two slices ahead.  Each wave waits for its own
             // transfers of the slice needed next (vmcnt counts them in order), then the barrier makes
             // everybody's visible and also guarantees nobody still reads the stage refilled next.
-            constexpr int L = APT + BPT;           // transfers per slice per wave
+            constexpr int L = APD + BPD;           // transfers per slice per wave
             init_full();
             issue_slice(0);
             if (nring > 1) {
@@ -639,7 +694,7 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
             if (s < nring) step(std::integral_constant<int, 0>{}, s);
             if (s + 1 < nring) step(std::integral_constant<int, 1>{}, s + 1);
         } else if (!interior && nslices > 0) {
-            // Unaligned operands (and spans past 32-bit offsets): registers -> LDS, two of the ring's stages.
+            // Registers -> LDS, two of the ring's stages.
             load_slice_edge(kbeg);
             store_slice(0);
             __syncthreads();
