@@ -111,7 +111,8 @@ struct Tile {
     static_assert(BK == 16 || BK == 32 || BK == 64, "k-slice depth");
     static_assert(NB == 1 || NB == 2 || NB == 4, "wave tile width must be 32, 64 or 128");
     static_assert((BM * BK / 4) % THREADS == 0 && (BK * BN / 4) % THREADS == 0, "slice must divide over the workgroup");
-    static_assert(THREADS % QPR == 0 && ROW_STEP % 8 == 0, "a lane's R-kind rows must share one swizzle");
+    static_assert(THREADS % QPR == 0 && ROW_STEP % 8 == 0 && (THREADS / BK) % 8 == 0,
+                  "a lane's R-kind rows must share one swizzle");
 
     // R-kind LDS position (in floats) of the float4 holding k = 4q .. 4q+3 of row r.  Rows are BK
     // floats; the quad index is XOR-ed with row bits so that 8 consecutive rows reading the same
@@ -352,32 +353,35 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
             auto conv_base_clamped = [&](int i) -> int64_t {   // row base of the lane's i-th row, or of row M-1
                 return a_rowbase[TA ? 0 : i] >= 0 ? a_rowbase[TA ? 0 : i] : conv_row_base(p.M - 1);
             };
+            // The lane's k position inside a slice is the same for all its transfers: the logical quad
+            // lq (aligned operands), or -- one float per transfer -- element t % 4 of the logical quad at
+            // physical position t % BK (the rows of a lane's transfers are NTH / BK apart, which leaves
+            // the swizzle unchanged).
+            const int row_t = t / BK;
+            const int lk = VEC ? 4 * lq : (((t % BK) / 4) ^ T::swizzle(row_t)) * 4 + t % 4;
+            auto lane_row_base = [&](int i) -> int64_t {
+                if constexpr (VEC) {
+                    return conv_base_clamped(i);
+                } else {
+                    const int64_t m = m0 + row_t + i * (NTH / BK);
+                    return conv_row_base(m < p.M ? m : p.M - 1);
+                }
+            };
             if (conv_uniform) {
                 su_c = (int)(kbeg % p.g.C);
                 su_kw = (int)((kbeg / p.g.C) % p.g.KW);
                 const int64_t kh = kbeg / (p.g.C * p.g.KW);
                 su_off = (uint32_t)(((kh * p.g.DH * p.g.W + (int64_t)su_kw * p.g.DW) * p.g.C + su_c) * 4);
-                if constexpr (VEC) {
 #pragma unroll
-                    for (int i = 0; i < APT; ++i) a_loff[i] = (uint32_t)((conv_base_clamped(i) - base0) * 4) + 16u * lq;
-                } else {
-#pragma unroll
-                    for (int i = 0; i < APD; ++i) {
-                        const int f = t + i * NTH;
-                        const int r = f / BK;
-                        const int kq = (((f % BK) / 4) ^ T::swizzle(r)) * 4 + f % 4;
-                        const int64_t m = (m0 + r < p.M) ? m0 + r : p.M - 1;
-                        a_loff[i] = (uint32_t)((conv_row_base(m) - base0 + kq) * 4);
-                    }
-                }
+                for (int i = 0; i < APD; ++i) a_loff[i] = (uint32_t)((lane_row_base(i) - base0 + lk) * 4);
             } else {
-                const int64_t k = kbeg + 4 * lq;
+                const int64_t k = kbeg + lk;
                 cv_c = (int)(k % p.g.C);
                 cv_kw = (int)((k / p.g.C) % p.g.KW);
                 cv_kh = (int)(k / (p.g.C * p.g.KW));
                 cv_off = cv_offset();
 #pragma unroll
-                for (int i = 0; i < APT; ++i) a_loff[i] = (uint32_t)((conv_base_clamped(i) - base0) * 4);
+                for (int i = 0; i < APD; ++i) a_loff[i] = (uint32_t)((lane_row_base(i) - base0) * 4);
             }
         } else if constexpr (TA) {
             a_base += (kbeg * p.lda + m0) * 4;
@@ -614,13 +618,11 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
     // All tiles (boundary tiles included, see r_loff) run their whole slices through the transfer rings
     // below -- 16 bytes per lane for aligned operands, 4 otherwise -- and a k tail (a slab whose depth
     // is not a multiple of BK) as one last predicated, register-staged slice.  Left to the
-    // register-staged path: spans beyond 32-bit offsets, and unaligned convolutions whose channel
-    // count is not a multiple of BK.
+    // register-staged path: spans beyond 32-bit offsets.
     // (the flag is wave-uniform; readfirstlane says so to the compiler where 32-bit divisions left it
     // in vector registers, so that the branches below stay scalar)
     const bool interior = __builtin_amdgcn_readfirstlane(
-        (int)(a_small && b_small && (T::KTAIL || (kend - kbeg) % BK == 0) &&
-              (VEC || !CONV || conv_uniform))) != 0;
+        (int)(a_small && b_small && (T::KTAIL || (kend - kbeg) % BK == 0))) != 0;
     const int nring = interior ? (int)((kend - kbeg) / BK) : 0;
     const bool ktail = T::KTAIL && interior && (kend - kbeg) % BK != 0;
     {
