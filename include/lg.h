@@ -95,6 +95,39 @@ int lg_matmul_t(const float *A, const float *B, float *C,
 int lg_matmul_plan(int64_t M, int64_t N, int64_t K, int *block_m, int *block_n, int *k_splits);
 
 /*
+ * The decomposition as a parameter (the paper's transformations take their tile sizes as
+ * parameters and leave the choice to a search, Sections 3.2 and 4.1; here the menu of compiled
+ * decompositions is numbered and the default entry points above pick from it with a cost
+ * model).  These calls run one chosen entry of the menu on any shape: for autotuning by
+ * measurement, and so that tests can hold every kernel variant to every shape.
+ *
+ *   lg_gemm_variants()       number of menu entries; variants are 0 .. that - 1.
+ *   lg_gemm_variant_info()   workgroup block block_m x block_n, k depth per step block_k, and
+ *                            k_parts: into how many parts a workgroup cuts the k range among
+ *                            its own wavefronts (1 for the LDS-tiled kernels).  Any output
+ *                            pointer may be NULL.  LG_ERR_INVALID_ARG for an unknown variant.
+ *   lg_matmul_variant()      lg_matmul_t with the variant and the number of k-slabs across
+ *                            workgroups (k_splits >= 1; the register-direct variants -- those
+ *                            with block_m = 16 -- take only 1).  Slabs are whole multiples of
+ *                            64 k, so fewer slabs than asked for may run.
+ *   lg_conv2d_nhwc_hwcf_variant()   lg_conv2d_nhwc_hwcf likewise.
+ *   lg_gemm_variant_workspace_bytes()   workspace those two need for (M, N, K) -- for the
+ *                            convolution M = N*OH*OW, N = F, K = KH*KW*C -- 0 when k_splits
+ *                            runs as one slab; same alignment rule as lg_matmul's workspace.
+ * Arguments, layouts, ownership and errors are those of lg_matmul_t / lg_conv2d_nhwc_hwcf;
+ * an unknown variant or a k_splits the variant does not take is LG_ERR_INVALID_ARG.
+ */
+int lg_gemm_variants(void);
+int lg_gemm_variant_info(int variant, int *block_m, int *block_n, int *block_k, int *k_parts);
+size_t lg_gemm_variant_workspace_bytes(int64_t M, int64_t N, int64_t K, int variant, int k_splits);
+int lg_matmul_variant(const float *A, const float *B, float *C,
+                      int64_t M, int64_t N, int64_t K,
+                      int64_t lda, int64_t ldb, int64_t ldc,
+                      int transA, int transB, int accumulate,
+                      int variant, int k_splits,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * 2-D convolution, Section 4.6.2 equation (2-D), NHWC input, HWCF filter:
  *     O[n,h,w,f] (+)= sum_{kh,kw,c} I[n, h*SH + kh*DH, w*SW + kw*DW, c] * Kf[kh,kw,c,f]
  * (cross-correlation: the filter is not flipped).  I is dense [N,H,W,C], Kf is
@@ -109,6 +142,13 @@ int lg_conv2d_nhwc_hwcf(const float *I, const float *Kf, float *O,
                         int64_t KH, int64_t KW, int64_t F,
                         int64_t SH, int64_t SW, int64_t DH, int64_t DW,
                         int accumulate, void *workspace, size_t workspace_bytes, void *stream);
+int lg_conv2d_nhwc_hwcf_variant(const float *I, const float *Kf, float *O,
+                                int64_t N, int64_t H, int64_t W, int64_t C,
+                                int64_t KH, int64_t KW, int64_t F,
+                                int64_t SH, int64_t SW, int64_t DH, int64_t DW,
+                                int accumulate, int variant, int k_splits,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
 size_t lg_conv2d_workspace_bytes(int64_t N, int64_t H, int64_t W, int64_t C,
                                  int64_t KH, int64_t KW, int64_t F,
                                  int64_t SH, int64_t SW, int64_t DH, int64_t DW);

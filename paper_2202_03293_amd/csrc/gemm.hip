@@ -27,11 +27,38 @@ __global__ __launch_bounds__(256) void fill_zero_2d_kernel(float* C, int64_t M, 
     C[m * ldc + (idx - m * N)] = 0.f;
 }
 
-enum class Layout { NN, CONV, TN, NT };
+// The menu a caller may pick from by number: the six tiles, then the register-direct kernel with
+// blocks 16 x {16, 32, 64} and {1, 2, 4} k parts per workgroup.
+constexpr int kNumVariants = kNumTiles + 9;
 
-static int run_gemm(GemmArgs a, Layout layout, bool vec, int user_accumulate, void* workspace,
+// The plan of a forced variant; false when the numbers make no sense.
+static bool forced_plan(int64_t M, int64_t N, int64_t K, int variant, int k_splits, Plan* out) {
+    if (variant < 0 || variant >= kNumVariants || k_splits < 1 || k_splits > 65535) return false;
+    Plan pl{};
+    if (variant >= kNumTiles) {
+        static const int pow2[3] = {1, 2, 4};
+        if (k_splits != 1) return false;
+        pl.direct_nbw = pow2[(variant - kNumTiles) / 3];
+        pl.direct_ks = pow2[(variant - kNumTiles) % 3];
+        pl.splits = 1;
+    } else {
+        const TileInfo& tl = kTiles[variant];
+        pl.tile = variant;
+        pl.tiles_m = cdiv(M, tl.bm);
+        pl.tiles_n = cdiv(N, tl.bn);
+        pl.k_per_split = cdiv(cdiv(K, kKGran), k_splits) * kKGran;
+        pl.splits = cdiv(K, pl.k_per_split);       // <= k_splits: slabs are whole multiples of the granule
+    }
+    *out = pl;
+    return true;
+}
+
+static int run_plan(GemmArgs a, Layout layout, bool vec, const Plan& pl, int user_accumulate, void* workspace,
                     size_t workspace_bytes, hipStream_t s) {
-    const Plan pl = make_plan(a.M, a.N, a.K);
+    if (pl.direct_nbw > 0) {
+        a.accumulate = user_accumulate;
+        return launch_direct(a, layout, pl.direct_nbw, pl.direct_ks, s);
+    }
     const size_t need = plan_workspace(pl, a.M, a.N);
     if (need > 0) {
         if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
@@ -68,6 +95,15 @@ static int run_gemm(GemmArgs a, Layout layout, bool vec, int user_accumulate, vo
     return LG_OK;
 }
 
+// variant < 0: the planner decides
+static int run_gemm(const GemmArgs& a, Layout layout, bool vec, int user_accumulate, void* workspace,
+                    size_t workspace_bytes, hipStream_t s, int variant = -1, int k_splits = 1) {
+    Plan pl{};
+    if (variant < 0) pl = make_plan(a.M, a.N, a.K);
+    else if (!forced_plan(a.M, a.N, a.K, variant, k_splits, &pl)) return LG_ERR_INVALID_ARG;
+    return run_plan(a, layout, vec, pl, user_accumulate, workspace, workspace_bytes, s);
+}
+
 static int zero_output(float* C, int64_t M, int64_t N, int64_t ldc, hipStream_t s) {
     const int64_t blocks = cdiv(M * N, 256);
     if (blocks > kMaxGrid) return LG_ERR_UNSUPPORTED;
@@ -81,9 +117,10 @@ extern "C" int lg_matmul_plan(int64_t M, int64_t N, int64_t K, int* block_m, int
     using namespace lg;
     if (M <= 0 || N <= 0 || K <= 0) return LG_ERR_INVALID_ARG;
     const Plan pl = make_plan(M, N, K);
-    if (block_m) *block_m = kTiles[pl.tile].bm;
-    if (block_n) *block_n = kTiles[pl.tile].bn;
-    if (k_splits) *k_splits = (int)pl.splits;
+    const bool direct = pl.direct_nbw > 0;
+    if (block_m) *block_m = direct ? 16 : kTiles[pl.tile].bm;
+    if (block_n) *block_n = direct ? 16 * pl.direct_nbw : kTiles[pl.tile].bn;
+    if (k_splits) *k_splits = direct ? 1 : (int)pl.splits;
     return LG_OK;
 }
 
@@ -93,37 +130,12 @@ extern "C" size_t lg_matmul_workspace_bytes(int64_t M, int64_t N, int64_t K) {
     return plan_workspace(make_plan(M, N, K), M, N);
 }
 
-extern "C" int lg_matmul(const float* A, const float* B, float* C,
-                         int64_t M, int64_t N, int64_t K,
-                         int64_t lda, int64_t ldb, int64_t ldc,
-                         int accumulate, void* workspace, size_t workspace_bytes, void* stream) {
-    using namespace lg;
-    if (M < 0 || N < 0 || K < 0 || lda < K || ldb < N || ldc < N) return LG_ERR_INVALID_ARG;
-    if (M == 0 || N == 0) return LG_OK;
-    if (!C || (K > 0 && (!A || !B))) return LG_ERR_INVALID_ARG;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const int64_t c_bytes = ((M - 1) * ldc + N) * 4;
-    if (K == 0) return accumulate ? LG_OK : zero_output(C, M, N, ldc, s);
-    if (overlaps(A, ((M - 1) * lda + K) * 4, C, c_bytes) || overlaps(B, ((K - 1) * ldb + N) * 4, C, c_bytes))
-        return LG_ERR_INVALID_ARG;
-    if (M >= (int64_t)1 << 31 || N >= (int64_t)1 << 31 || K >= (int64_t)1 << 31) return LG_ERR_UNSUPPORTED;
-    const bool vec = (K % 4 == 0) && (N % 4 == 0) && (lda % 4 == 0) && (ldb % 4 == 0) && (ldc % 4 == 0) &&
-                     aligned16(A) && aligned16(B) && aligned16(C);
-    GemmArgs a{};
-    a.A = A; a.B = B; a.C = C;
-    a.M = M; a.N = N; a.K = K;
-    a.lda = lda; a.ldb = ldb; a.ldc = ldc;
-    return run_gemm(a, Layout::NN, vec, accumulate, workspace, workspace_bytes, s);
-}
+namespace lg {
 
-extern "C" int lg_matmul_t(const float* A, const float* B, float* C,
-                           int64_t M, int64_t N, int64_t K,
-                           int64_t lda, int64_t ldb, int64_t ldc,
-                           int transA, int transB,
-                           int accumulate, void* workspace, size_t workspace_bytes, void* stream) {
-    using namespace lg;
-    if (!transA && !transB)
-        return lg_matmul(A, B, C, M, N, K, lda, ldb, ldc, accumulate, workspace, workspace_bytes, stream);
+// C (+)= op(A) op(B) in any of the three layouts; variant < 0 leaves the choice of kernel to the planner.
+static int matmul_impl(const float* A, const float* B, float* C, int64_t M, int64_t N, int64_t K,
+                       int64_t lda, int64_t ldb, int64_t ldc, int transA, int transB, int accumulate,
+                       void* workspace, size_t workspace_bytes, void* stream, int variant, int k_splits) {
     if (M < 0 || N < 0 || K < 0 || ldc < N) return LG_ERR_INVALID_ARG;
     const int64_t a_rows = transA ? K : M, a_cols = transA ? M : K;     // stored shape of A
     const int64_t b_rows = transB ? N : K, b_cols = transB ? K : N;     // stored shape of B
@@ -144,7 +156,58 @@ extern "C" int lg_matmul_t(const float* A, const float* B, float* C,
     a.A = A; a.B = B; a.C = C;
     a.M = M; a.N = N; a.K = K;
     a.lda = lda; a.ldb = ldb; a.ldc = ldc;
-    return run_gemm(a, transA ? Layout::TN : Layout::NT, vec, accumulate, workspace, workspace_bytes, s);
+    const Layout layout = transA ? Layout::TN : transB ? Layout::NT : Layout::NN;
+    return run_gemm(a, layout, vec, accumulate, workspace, workspace_bytes, s, variant, k_splits);
+}
+
+}  // namespace lg
+
+extern "C" int lg_matmul(const float* A, const float* B, float* C,
+                         int64_t M, int64_t N, int64_t K,
+                         int64_t lda, int64_t ldb, int64_t ldc,
+                         int accumulate, void* workspace, size_t workspace_bytes, void* stream) {
+    return lg::matmul_impl(A, B, C, M, N, K, lda, ldb, ldc, 0, 0, accumulate, workspace, workspace_bytes, stream, -1, 1);
+}
+
+extern "C" int lg_matmul_t(const float* A, const float* B, float* C,
+                           int64_t M, int64_t N, int64_t K,
+                           int64_t lda, int64_t ldb, int64_t ldc,
+                           int transA, int transB,
+                           int accumulate, void* workspace, size_t workspace_bytes, void* stream) {
+    return lg::matmul_impl(A, B, C, M, N, K, lda, ldb, ldc, transA, transB, accumulate, workspace, workspace_bytes,
+                           stream, -1, 1);
+}
+
+extern "C" int lg_gemm_variants(void) { return lg::kNumVariants; }
+
+extern "C" int lg_gemm_variant_info(int variant, int* block_m, int* block_n, int* block_k, int* k_parts) {
+    using namespace lg;
+    Plan pl{};
+    if (!forced_plan(1, 1, 1, variant, 1, &pl)) return LG_ERR_INVALID_ARG;
+    const bool direct = pl.direct_nbw > 0;
+    if (block_m) *block_m = direct ? 16 : kTiles[variant].bm;
+    if (block_n) *block_n = direct ? 16 * pl.direct_nbw : kTiles[variant].bn;
+    if (block_k) *block_k = direct ? 16 : kTiles[variant].bk;
+    if (k_parts) *k_parts = direct ? pl.direct_ks : 1;
+    return LG_OK;
+}
+
+extern "C" size_t lg_gemm_variant_workspace_bytes(int64_t M, int64_t N, int64_t K, int variant, int k_splits) {
+    using namespace lg;
+    Plan pl{};
+    if (M <= 0 || N <= 0 || K <= 0 || !forced_plan(M, N, K, variant, k_splits, &pl)) return 0;
+    return pl.direct_nbw > 0 ? 0 : plan_workspace(pl, M, N);
+}
+
+extern "C" int lg_matmul_variant(const float* A, const float* B, float* C,
+                                 int64_t M, int64_t N, int64_t K,
+                                 int64_t lda, int64_t ldb, int64_t ldc,
+                                 int transA, int transB, int accumulate,
+                                 int variant, int k_splits,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+    if (variant < 0) return LG_ERR_INVALID_ARG;
+    return lg::matmul_impl(A, B, C, M, N, K, lda, ldb, ldc, transA, transB, accumulate, workspace, workspace_bytes,
+                           stream, variant, k_splits);
 }
 
 extern "C" size_t lg_conv2d_workspace_bytes(int64_t N, int64_t H, int64_t W, int64_t C,
@@ -157,12 +220,14 @@ extern "C" size_t lg_conv2d_workspace_bytes(int64_t N, int64_t H, int64_t W, int
     return plan_workspace(make_plan(M, F, KH * KW * C), M, F);
 }
 
-extern "C" int lg_conv2d_nhwc_hwcf(const float* I, const float* Kf, float* O,
-                                   int64_t N, int64_t H, int64_t W, int64_t C,
-                                   int64_t KH, int64_t KW, int64_t F,
-                                   int64_t SH, int64_t SW, int64_t DH, int64_t DW,
-                                   int accumulate, void* workspace, size_t workspace_bytes, void* stream) {
-    using namespace lg;
+namespace lg {
+
+static int conv2d_impl(const float* I, const float* Kf, float* O,
+                       int64_t N, int64_t H, int64_t W, int64_t C,
+                       int64_t KH, int64_t KW, int64_t F,
+                       int64_t SH, int64_t SW, int64_t DH, int64_t DW,
+                       int accumulate, void* workspace, size_t workspace_bytes, void* stream,
+                       int variant, int k_splits) {
     if (N < 0 || H < 0 || W < 0 || C < 0 || KH < 1 || KW < 1 || F < 0) return LG_ERR_INVALID_ARG;
     if (SH < 1 || SW < 1 || DH < 1 || DW < 1) return LG_ERR_INVALID_ARG;
     if (N == 0 || F == 0) return LG_OK;
@@ -182,14 +247,36 @@ extern "C" int lg_conv2d_nhwc_hwcf(const float* I, const float* Kf, float* O,
         mm.A = I; mm.B = Kf; mm.C = O;
         mm.M = M; mm.N = F; mm.K = C;
         mm.lda = C; mm.ldb = F; mm.ldc = F;
-        return run_gemm(mm, Layout::NN, vec, accumulate, workspace, workspace_bytes, s);
+        return run_gemm(mm, Layout::NN, vec, accumulate, workspace, workspace_bytes, s, variant, k_splits);
     }
     GemmArgs a{};
     a.A = I; a.B = Kf; a.C = O;
     a.M = M; a.N = F; a.K = Kg;
     a.lda = 0; a.ldb = F; a.ldc = F;
     a.g = ConvGeom{H, W, C, KW, SH, SW, DH, DW, OH, OW};
-    return run_gemm(a, Layout::CONV, vec, accumulate, workspace, workspace_bytes, s);
+    return run_gemm(a, Layout::CONV, vec, accumulate, workspace, workspace_bytes, s, variant, k_splits);
+}
+
+}  // namespace lg
+
+extern "C" int lg_conv2d_nhwc_hwcf(const float* I, const float* Kf, float* O,
+                                   int64_t N, int64_t H, int64_t W, int64_t C,
+                                   int64_t KH, int64_t KW, int64_t F,
+                                   int64_t SH, int64_t SW, int64_t DH, int64_t DW,
+                                   int accumulate, void* workspace, size_t workspace_bytes, void* stream) {
+    return lg::conv2d_impl(I, Kf, O, N, H, W, C, KH, KW, F, SH, SW, DH, DW, accumulate, workspace, workspace_bytes,
+                           stream, -1, 1);
+}
+
+extern "C" int lg_conv2d_nhwc_hwcf_variant(const float* I, const float* Kf, float* O,
+                                           int64_t N, int64_t H, int64_t W, int64_t C,
+                                           int64_t KH, int64_t KW, int64_t F,
+                                           int64_t SH, int64_t SW, int64_t DH, int64_t DW,
+                                           int accumulate, int variant, int k_splits,
+                                           void* workspace, size_t workspace_bytes, void* stream) {
+    if (variant < 0) return LG_ERR_INVALID_ARG;
+    return lg::conv2d_impl(I, Kf, O, N, H, W, C, KH, KW, F, SH, SW, DH, DW, accumulate, workspace, workspace_bytes,
+                           stream, variant, k_splits);
 }
 
 extern "C" size_t lg_conv1d_workspace_bytes(int64_t N, int64_t W, int64_t C, int64_t KW, int64_t F,

@@ -792,6 +792,8 @@ static const TileInfo kTiles[kNumTiles] = {
 struct Plan {
     int tile;          // index into kTiles
     int64_t tiles_m, tiles_n, splits, k_per_split;
+    int direct_nbw;    // > 0: the register-direct kernel (gemm_direct.hip) with blocks 16 x 16*direct_nbw ...
+    int direct_ks;     // ... and the k range cut into this many parts inside a workgroup; `tile` etc. unused
 };
 
 constexpr int kCUs = 256;
@@ -835,6 +837,32 @@ inline Plan make_plan(int64_t M, int64_t N, int64_t K) {
             }
         }
     }
+    // The register-direct kernel (gemm_direct.hip): blocks of 16 x 16*nbw per wavefront, the k range
+    // cut into ks parts inside a workgroup.  Fitted to launches replayed from a graph: a wavefront
+    // alone on its SIMD takes 0.05 + 0.09*nbw us per 16-deep k chunk (load latency it cannot hide
+    // and the dependent MFMA chain); wavefronts beyond one per SIMD queue up; operands come from
+    // the caches at ~10 TB/s over the whole chip, the output goes out at the same price; against
+    // the tiled kernel's launch constant above it starts 3 us ahead (no staging ring to fill, no
+    // barrier, a short epilogue).
+    for (int nbw = 1; nbw <= 4; nbw *= 2) {
+        for (int ks = 1; ks <= 4; ks *= 2) {
+            const int64_t groups = cdiv(cdiv(M, 16), 4 / ks) * cdiv(N, 16 * nbw);
+            if (groups > kMaxGrid) continue;
+            const double waves = (double)cdiv(M, 16) * (double)cdiv(N, 16 * nbw) * ks;
+            const double chunks = (double)cdiv(cdiv(K, 16), ks);
+            const double per_wave = chunks * (0.05e-6 + 0.09e-6 * nbw);
+            const double queued = (double)cdiv((int64_t)waves, 4 * kCUs);
+            const double bytes = waves * chunks * 16.0 * (16 + 16 * nbw) * 4.0 + 2.0 * M * N * 4.0;
+            const double cost = 7e-6 + per_wave * queued + bytes / 10e12 + (ks > 1 ? 0.3e-6 : 0.0);
+            if (cost < best_cost) {
+                best_cost = cost;
+                best = Plan{};
+                best.splits = 1;
+                best.direct_nbw = nbw;
+                best.direct_ks = ks;
+            }
+        }
+    }
     return best;
 }
 
@@ -870,6 +898,11 @@ static void launch_planned(const GemmArgs& a, const Plan& pl, bool vec, hipStrea
     }
 #undef LG_LAUNCH
 }
+
+enum class Layout { NN, CONV, TN, NT };
+
+// The register-direct kernel for small and skinny problems (gemm_direct.hip); returns an LG_* status.
+int launch_direct(const GemmArgs& a, Layout layout, int nbw, int ks, hipStream_t s);
 
 // Implemented in gemm.hip (AB and convolution) and gemm_t.hip (A^T B, A B^T).
 void launch_nn(const GemmArgs& a, const Plan& pl, bool vec, hipStream_t s);

@@ -20,6 +20,11 @@ _SIGNATURES = {
     "lg_matmul_t": (_int, [_vp, _vp, _vp] + [_i64] * 6 + [_int, _int, _int, _vp, _sz, _vp]),
     "lg_matmul_workspace_bytes": (_sz, [_i64] * 3),
     "lg_matmul_plan": (_int, [_i64] * 3 + [ctypes.POINTER(_int)] * 3),
+    "lg_gemm_variants": (_int, []),
+    "lg_gemm_variant_info": (_int, [_int] + [ctypes.POINTER(_int)] * 4),
+    "lg_gemm_variant_workspace_bytes": (_sz, [_i64] * 3 + [_int, _int]),
+    "lg_matmul_variant": (_int, [_vp, _vp, _vp] + [_i64] * 6 + [_int] * 5 + [_vp, _sz, _vp]),
+    "lg_conv2d_nhwc_hwcf_variant": (_int, [_vp, _vp, _vp] + [_i64] * 11 + [_int] * 3 + [_vp, _sz, _vp]),
     "lg_conv2d_nhwc_hwcf": (_int, [_vp, _vp, _vp] + [_i64] * 11 + [_int, _vp, _sz, _vp]),
     "lg_conv2d_workspace_bytes": (_sz, [_i64] * 11),
     "lg_conv1d_nwc_wcf": (_int, [_vp, _vp, _vp] + [_i64] * 7 + [_int, _vp, _sz, _vp]),
@@ -146,6 +151,57 @@ def lg_matmul_t(A, B, C, trans_a=False, trans_b=False, accumulate=False, workspa
     _check("lg_matmul_t", lib().lg_matmul_t(_ptr(A), _ptr(B), _ptr(C), M, N, K, _ld(A), _ld(B), _ld(C),
                                             int(trans_a), int(trans_b), int(accumulate), wp, wb, _stream(stream)))
     return C
+
+
+def lg_gemm_variants():
+    """Number of compiled GEMM decompositions; variants are numbered from 0."""
+    return lib().lg_gemm_variants()
+
+
+def lg_gemm_variant_info(variant):
+    """(block_m, block_n, block_k, k_parts) of a variant."""
+    v = [_int() for _ in range(4)]
+    _check("lg_gemm_variant_info", lib().lg_gemm_variant_info(variant, *[ctypes.byref(x) for x in v]))
+    return tuple(x.value for x in v)
+
+
+def lg_gemm_variant_workspace_bytes(M, N, K, variant, k_splits=1):
+    return lib().lg_gemm_variant_workspace_bytes(M, N, K, variant, k_splits)
+
+
+def lg_matmul_variant(A, B, C, variant, k_splits=1, trans_a=False, trans_b=False, accumulate=False,
+                      workspace=None, stream=None):
+    """lg_matmul_t run by one chosen kernel variant and k-split instead of the planner's choice."""
+    M, N = C.shape
+    K = A.shape[0] if trans_a else A.shape[1]
+    if tuple(A.shape) != ((K, M) if trans_a else (M, K)) or tuple(B.shape) != ((N, K) if trans_b else (K, N)):
+        raise ValueError("matmul shapes do not agree")
+    wp, wb = _ws(workspace)
+    _check("lg_matmul_variant",
+           lib().lg_matmul_variant(_ptr(A), _ptr(B), _ptr(C), M, N, K, _ld(A), _ld(B), _ld(C), int(trans_a),
+                                   int(trans_b), int(accumulate), variant, k_splits, wp, wb, _stream(stream)))
+    return C
+
+
+def lg_conv2d_nhwc_hwcf_variant(I, Kf, O, variant, k_splits=1, stride=(1, 1), dilation=(1, 1), accumulate=False,
+                                workspace=None, stream=None):
+    """lg_conv2d_nhwc_hwcf run by one chosen kernel variant and k-split."""
+    N, H, W, C = I.shape
+    KH, KW, C2, F = Kf.shape
+    if C != C2:
+        raise ValueError("channel extents do not agree")
+    for t in (I, Kf, O):
+        _dense(t)
+    OH = lg_conv_out_extent(H, KH, stride[0], dilation[0])
+    OW = lg_conv_out_extent(W, KW, stride[1], dilation[1])
+    if tuple(O.shape) != (N, OH, OW, F):
+        raise ValueError(f"output must have shape {(N, OH, OW, F)}")
+    wp, wb = _ws(workspace)
+    _check("lg_conv2d_nhwc_hwcf_variant",
+           lib().lg_conv2d_nhwc_hwcf_variant(_ptr(I), _ptr(Kf), _ptr(O), N, H, W, C, KH, KW, F,
+                                             stride[0], stride[1], dilation[0], dilation[1],
+                                             int(accumulate), variant, k_splits, wp, wb, _stream(stream)))
+    return O
 
 
 def lg_conv2d_workspace_bytes(N, H, W, C, KH, KW, F, SH=1, SW=1, DH=1, DW=1):

@@ -1,0 +1,109 @@
+"""GPU parity of every GEMM kernel variant on shapes the planner would never give it: each of the
+six LDS tiles (with and without a k-split) and each register-direct variant runs ragged, tiny and
+unaligned matmuls in the three layouts and convolutions with aligned and odd channel counts,
+against the CPU oracle on the same seeded inputs, between canary guard bands."""
+import numpy as np
+import pytest
+import torch
+
+import seeded_inputs as si
+from gpu_util import Guarded, assert_close, dev, workspace
+
+pytestmark = pytest.mark.gpu
+
+N_VARIANTS = 15            # checked against the library in test_variant_menu
+
+
+@pytest.fixture(scope="module")
+def lg():
+    import paper_2202_03293_amd as pkg
+    pkg.lib()
+    return pkg
+
+
+def test_variant_menu(lg):
+    assert lg.lg_gemm_variants() == N_VARIANTS
+    infos = [lg.lg_gemm_variant_info(v) for v in range(N_VARIANTS)]
+    assert len(set(infos)) == N_VARIANTS                     # all different
+    assert sum(1 for bm, bn, bk, kp in infos if bm == 16) == 9
+    with pytest.raises(lg.LgError):
+        lg.lg_gemm_variant_info(N_VARIANTS)
+    a = torch.zeros((4, 4), device="cuda")
+    with pytest.raises(lg.LgError):
+        lg.lg_matmul_variant(a, a.clone(), torch.empty((4, 4), device="cuda"), N_VARIANTS)
+    with pytest.raises(lg.LgError):                          # the register-direct variants take no k-split
+        lg.lg_matmul_variant(a, a.clone(), torch.empty((4, 4), device="cuda"), N_VARIANTS - 1, k_splits=2)
+
+
+# (M, N, K, layout, accumulate, padded leading dimensions)
+MATMUL_SHAPES = [
+    (1, 1, 1, "nn", False, False),
+    (17, 33, 5, "nn", True, False),
+    (100, 70, 130, "nn", False, True),
+    (64, 64, 288, "nn", False, False),
+    (131, 257, 67, "tn", False, False),
+    (96, 48, 200, "tn", True, True),
+    (75, 130, 150, "nt", False, False),
+    (128, 32, 272, "nt", True, True),
+    (300, 20, 27, "nn", False, False),
+]
+
+
+@pytest.mark.parametrize("variant", range(N_VARIANTS))
+@pytest.mark.parametrize("M,N,K,layout,accumulate,padded", MATMUL_SHAPES)
+def test_matmul_every_variant(lg, lgo, variant, M, N, K, layout, accumulate, padded):
+    direct = lg.lg_gemm_variant_info(variant)[0] == 16
+    A, B = si.matmul_inputs(1200 + M, M, N, K, case=K % 7)
+    C0 = si.uniform(1201, N, (M, N), -1, 1) if accumulate else None
+    ref = lgo.matmul(A, B, C0.copy(), accumulate=True) if accumulate else lgo.matmul(A, B)
+    As = np.ascontiguousarray(A.T) if layout == "tn" else A
+    Bs = np.ascontiguousarray(B.T) if layout == "nt" else B
+    pad = 4 if padded else 0
+
+    def padded_dev(x):
+        if not pad:
+            return dev(x)
+        full = torch.full((x.shape[0], x.shape[1] + pad), float("nan"), device="cuda")
+        full[:, :x.shape[1]] = dev(x)
+        return full[:, :x.shape[1]]
+
+    Ad, Bd = padded_dev(As), padded_dev(Bs)
+    for k_splits in ((1,) if direct else (1, 3)):
+        out = Guarded((M, N), init=C0 if accumulate else np.full((M, N), np.nan, np.float32))
+        ws = workspace(lg.lg_gemm_variant_workspace_bytes(M, N, K, variant, k_splits))
+        lg.lg_matmul_variant(Ad, Bd, out.t, variant, k_splits, trans_a=layout == "tn", trans_b=layout == "nt",
+                             accumulate=accumulate, workspace=ws)
+        torch.cuda.synchronize()
+        out.check()
+        assert_close(out.host(), ref, K, f"variant {variant} splits {k_splits} {layout} {(M, N, K)}")
+
+
+# (N, H, W, C, F, KH, KW, stride, dilation, accumulate)
+CONV_SHAPES = [
+    (2, 12, 13, 3, 20, 3, 3, (1, 1), (1, 1), False),      # three channels: every quad straddles taps
+    (1, 16, 16, 32, 64, 3, 3, (1, 1), (1, 1), False),     # the paper's batch-1 sweep shape
+    (3, 11, 17, 20, 33, 2, 3, (2, 1), (1, 2), True),      # C % 4 == 0, C % 16 != 0, odd F
+    (2, 9, 9, 7, 5, 5, 4, (1, 2), (1, 1), False),
+    (1, 20, 20, 16, 16, 1, 1, (1, 1), (1, 1), True),      # 1x1, stride 1: runs as a plain matmul
+    (2, 15, 15, 8, 24, 1, 1, (2, 2), (1, 1), False),      # 1x1, strided
+]
+
+
+@pytest.mark.parametrize("variant", range(N_VARIANTS))
+@pytest.mark.parametrize("N,H,W,C,F,KH,KW,st,dl,accumulate", CONV_SHAPES)
+def test_conv2d_every_variant(lg, lgo, variant, N, H, W, C, F, KH, KW, st, dl, accumulate):
+    direct = lg.lg_gemm_variant_info(variant)[0] == 16
+    I, Kf = si.conv2d_inputs(1210 + C, N, H, W, C, F, KH, KW)
+    OH, OW = lg.lg_conv_out_extent(H, KH, st[0], dl[0]), lg.lg_conv_out_extent(W, KW, st[1], dl[1])
+    O0 = si.uniform(1211, F, (N, OH, OW, F), -1, 1) if accumulate else None
+    ref = lgo.conv2d_nhwc_hwcf(I, Kf, O0.copy(), stride=st, dilation=dl, accumulate=True) if accumulate \
+        else lgo.conv2d_nhwc_hwcf(I, Kf, stride=st, dilation=dl)
+    Id, Kd = dev(I), dev(Kf)
+    for k_splits in ((1,) if direct else (1, 2)):
+        out = Guarded((N, OH, OW, F), init=O0 if accumulate else np.full((N, OH, OW, F), np.nan, np.float32))
+        ws = workspace(lg.lg_gemm_variant_workspace_bytes(N * OH * OW, F, KH * KW * C, variant, k_splits))
+        lg.lg_conv2d_nhwc_hwcf_variant(Id, Kd, out.t, variant, k_splits, stride=st, dilation=dl,
+                                       accumulate=accumulate, workspace=ws)
+        torch.cuda.synchronize()
+        out.check()
+        assert_close(out.host(), ref, KH * KW * C, f"variant {variant} splits {k_splits} conv {(N, H, W, C, F, KH, KW)}")
