@@ -57,7 +57,7 @@ static int run_plan(GemmArgs a, Layout layout, bool vec, const Plan& pl, int use
                     size_t workspace_bytes, hipStream_t s) {
     if (pl.direct_nbw > 0) {
         a.accumulate = user_accumulate;
-        return launch_direct(a, layout, pl.direct_nbw, pl.direct_ks, s);
+        return launch_direct(a, layout, pl.direct_nbw, pl.direct_ks, vec, s);
     }
     const size_t need = plan_workspace(pl, a.M, a.N);
     if (need > 0) {
@@ -99,8 +99,21 @@ static int run_plan(GemmArgs a, Layout layout, bool vec, const Plan& pl, int use
 static int run_gemm(const GemmArgs& a, Layout layout, bool vec, int user_accumulate, void* workspace,
                     size_t workspace_bytes, hipStream_t s, int variant = -1, int k_splits = 1) {
     Plan pl{};
-    if (variant < 0) pl = make_plan(a.M, a.N, a.K);
-    else if (!forced_plan(a.M, a.N, a.K, variant, k_splits, &pl)) return LG_ERR_INVALID_ARG;
+    if (variant < 0) {
+        pl = make_plan(a.M, a.N, a.K);
+        // the planner knows extents, not pitches: operands padded past the direct kernel's reach
+        // run on the smallest tile, unsplit (which needs no workspace either)
+        if (pl.direct_nbw > 0 && !direct_can_run(a, layout)) forced_plan(a.M, a.N, a.K, 3, 1, &pl);
+        // Operands that turn out unaligned (the planner saw only extents): one float per load costs
+        // the wider blocks more registers than they have, and more than one round of small blocks
+        // is the tiled kernel's business.
+        if (pl.direct_nbw > 0 && !vec) {
+            if (cdiv(a.M, 16) * cdiv(a.N, 16) * pl.direct_ks > 4 * kCUs) forced_plan(a.M, a.N, a.K, 3, 1, &pl);
+            else pl.direct_nbw = 1;
+        }
+    } else if (!forced_plan(a.M, a.N, a.K, variant, k_splits, &pl)) {
+        return LG_ERR_INVALID_ARG;
+    }
     return run_plan(a, layout, vec, pl, user_accumulate, workspace, workspace_bytes, s);
 }
 

@@ -27,12 +27,15 @@ struct DirectFrag {
     float b[NBW][4];       // B[chunk + 4g + j][column of block nb]
 };
 
-// LAYOUT: 0 = AB, 1 = convolution, 2 = A^T B, 3 = A B^T.  a_vec / b_vec: the operand that is
-// contiguous along k may be fetched 16 bytes at a time (row pitch and base 16-byte aligned).
-template <int LAYOUT, int NBW>
-__global__ __launch_bounds__(256) void gemm_direct_kernel(GemmArgs p, int ks, int a_vec, int b_vec) {
+// LAYOUT: 0 = AB, 1 = convolution, 2 = A^T B, 3 = A B^T.  VEC: every operand may be accessed 16 bytes
+// at a time along its contiguous axis (bases and row pitches 16-byte aligned, N a multiple of 4;
+// convolution: C a multiple of 4); otherwise every access is one float.  A compile-time switch on
+// purpose: a run-time test inside the fetch splits it into basic blocks, and the compiler then
+// waits for all loads in flight at every join.
+template <int LAYOUT, int NBW, bool VEC>
+__global__ __launch_bounds__(256, NBW == 1 ? 4 : NBW == 2 ? 3 : 2) void gemm_direct_kernel(GemmArgs p, int ks) {
     constexpr bool CONV = LAYOUT == 1, TA = LAYOUT == 2, TB = LAYOUT == 3;
-    constexpr int PD = NBW == 1 ? 8 : NBW == 2 ? 6 : 4;      // k chunks in flight per wavefront
+    constexpr int PD = (VEC || NBW == 1) ? 4 : 2;             // k chunks per register set (one-float loads take an offset register each)
     __shared__ float red[4][NBW * 4][kWave];
 
     const int lane = threadIdx.x % kWave;
@@ -53,27 +56,65 @@ __global__ __launch_bounds__(256) void gemm_direct_kernel(GemmArgs p, int ks, in
     const int tail = (active && ke > kb) ? (int)((ke - kb) % 16) : 0;
 
     // Rows and columns outside the matrix are fetched from the last valid one (in bounds; what they
-    // feed is never stored).
+    // feed is never stored).  Block nb of a lane owns column n0 + NBW*c + nb (c = lane % 16): the
+    // NBW columns of a lane are neighbours in memory, one vector load or store wide.
     const int64_t mrow = (m0 + r < p.M) ? m0 + r : p.M - 1;
     int64_t ncol[NBW];
 #pragma unroll
     for (int nb = 0; nb < NBW; ++nb) {
-        const int64_t n = n0 + 16 * nb + r;
+        const int64_t n = n0 + NBW * r + nb;
         ncol[nb] = n < p.N ? n : p.N - 1;
     }
-    int64_t a_row = 0;                                         // element offset of the row's k = 0
+    // whole groups of NBW columns lie inside or outside the matrix when N % NBW == 0
+    constexpr bool row_vec = NBW > 1 && VEC;
+    const int64_t ngroup = (n0 + NBW * r < p.N) ? n0 + NBW * r : p.N - NBW;   // used when row_vec
+
+    // Addresses are a wave-uniform base that advances by one chunk (16 k) per fetch -- chunks are
+    // fetched in ascending order -- plus a per-lane 32-bit byte offset that never changes: scalar
+    // adds per chunk, no vector ALU work and one register per distinct offset.  (The host sends
+    // operands of 4 GiB or more to the tiled kernel.)
+    const char* a_s = reinterpret_cast<const char*>(p.A);
+    const char* b_s = reinterpret_cast<const char*>(p.B);
+    int64_t a_step, b_step;
+    uint32_t a_voff[TA ? 4 : 1];
+    uint32_t b_voff[TB ? NBW : 4];
     if constexpr (CONV) {
         const uint32_t mu = (uint32_t)mrow, OWu = (uint32_t)p.g.OW, OHu = (uint32_t)p.g.OH;
         const uint32_t q = mu / OWu;
         const int64_t ow = mu - q * OWu, n = q / OHu, oh = q - (uint32_t)n * OHu;
-        a_row = ((n * p.g.H + oh * p.g.SH) * p.g.W + ow * p.g.SW) * p.g.C;
-    } else if constexpr (!TA) {
-        a_row = mrow * p.lda;
+        a_voff[0] = (uint32_t)((((n * p.g.H + oh * p.g.SH) * p.g.W + ow * p.g.SW) * p.g.C) * 4);   // tap (0, 0), channel 0
+        a_step = 0;
+    } else if constexpr (TA) {
+        a_s += kb * p.lda * 4;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a_voff[j] = (uint32_t)(((4 * g + j) * p.lda + mrow) * 4);
+        a_step = 64 * p.lda;
+    } else {
+        a_s += kb * 4;
+        a_voff[0] = (uint32_t)((mrow * p.lda + 4 * g) * 4);
+        a_step = 64;
     }
+    if constexpr (TB) {
+        b_s += kb * 4;
+#pragma unroll
+        for (int nb = 0; nb < NBW; ++nb) b_voff[nb] = (uint32_t)((ncol[nb] * p.ldb + 4 * g) * 4);
+        b_step = 64;
+    } else {
+        b_s += kb * p.ldb * 4;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) b_voff[j] = (uint32_t)(((4 * g + j) * p.ldb + (row_vec ? ngroup : 0)) * 4);
+        b_step = 64 * p.ldb;
+    }
+    uint32_t ncol4[NBW];                                       // column byte offsets for the one-float path
+#pragma unroll
+    for (int nb = 0; nb < NBW; ++nb) ncol4[nb] = (uint32_t)(ncol[nb] * 4);
+    int64_t kcur = kb + 4 * g;                                 // the lane's first k of the next chunk
+    auto ldf = [](const char* base, uint32_t off) { return *reinterpret_cast<const float*>(base + off); };
+    auto ldf4 = [](const char* base, uint32_t off) { return *reinterpret_cast<const float4*>(base + off); };
 
     // Convolution: k -> filter tap (kh, kw) and channel c.  A lane walks its k positions chunk by
     // chunk (one position when it fetches 16 bytes, which never straddle a tap as C % 4 == 0 then;
-    // four otherwise).  Chunks are loaded in ascending order, so the walk only moves forward.
+    // four otherwise).
     int wc[4] = {0, 0, 0, 0}, wkw[4] = {0, 0, 0, 0}, wkh[4] = {0, 0, 0, 0};
     const int cvC = (int)p.g.C, cvKW = (int)p.g.KW;
     if constexpr (CONV) {
@@ -86,8 +127,9 @@ __global__ __launch_bounds__(256) void gemm_direct_kernel(GemmArgs p, int ks, in
             wkw[j] = (int)(tap - (uint32_t)wkh[j] * (uint32_t)cvKW);
         }
     }
-    auto tap_offset = [&](int j) -> int64_t {
-        return ((int64_t)wkh[j] * p.g.DH * p.g.W + (int64_t)wkw[j] * p.g.DW) * p.g.C + wc[j];
+    const uint32_t tap_kh = (uint32_t)(p.g.DH * p.g.W * p.g.C * 4), tap_kw = (uint32_t)(p.g.DW * p.g.C * 4);
+    auto tap_offset = [&](int j) -> uint32_t {                 // bytes from the row's tap (0, 0), channel 0
+        return (uint32_t)wkh[j] * tap_kh + (uint32_t)wkw[j] * tap_kw + (uint32_t)wc[j] * 4u;
     };
     auto walk_on = [&](int j) {
         wc[j] += 16;
@@ -97,65 +139,71 @@ __global__ __launch_bounds__(256) void gemm_direct_kernel(GemmArgs p, int ks, in
         }
     };
 
-    // Fetch the chunk at kc.  FULL: all 16 k lie inside the range; otherwise every element is
+    // Fetch the next chunk.  FULL: all 16 k lie inside the range; otherwise every element is
     // predicated on k < ke and reads as zero beyond (both operands, so that no NaN of an operand
     // leaks through a zero of the other).
-    auto load = [&](DirectFrag<NBW>& f, int64_t kc, auto full_c) {
+    auto load = [&](DirectFrag<NBW>& f, auto full_c) {
         constexpr bool FULL = decltype(full_c)::value;
-        const int64_t k0 = kc + 4 * g;
-        if constexpr (TA) {
+        if constexpr (CONV) {
+            if constexpr (VEC) {
+                const uint32_t off = a_voff[0] + tap_offset(0);
+                if constexpr (FULL) {
+                    const float4 v = ldf4(a_s, off);
+                    f.a[0] = v.x; f.a[1] = v.y; f.a[2] = v.z; f.a[3] = v.w;
+                    walk_on(0);
+                } else {                                       // the ragged chunk of a 16-byte walker
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                f.a[j] = (FULL || k0 + j < ke) ? p.A[(k0 + j) * p.lda + mrow] : 0.f;
-        } else if constexpr (CONV) {
-            if (FULL && a_vec) {
-                const float4 v = *reinterpret_cast<const float4*>(p.A + a_row + tap_offset(0));
-                f.a[0] = v.x; f.a[1] = v.y; f.a[2] = v.z; f.a[3] = v.w;
-                walk_on(0);
+                    for (int j = 0; j < 4; ++j) f.a[j] = (kcur + j < ke) ? ldf(a_s, off + 4 * j) : 0.f;
+                }
             } else {
-                if (a_vec) {                                   // the ragged chunk of a 16-byte walker
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        f.a[j] = (k0 + j < ke) ? p.A[a_row + tap_offset(0) + j] : 0.f;
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        f.a[j] = (FULL || k0 + j < ke) ? p.A[a_row + tap_offset(j)] : 0.f;
-                        walk_on(j);
-                    }
+                for (int j = 0; j < 4; ++j) {
+                    f.a[j] = (FULL || kcur + j < ke) ? ldf(a_s, a_voff[0] + tap_offset(j)) : 0.f;
+                    walk_on(j);
                 }
             }
+        } else if constexpr (TA) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) f.a[j] = (FULL || kcur + j < ke) ? ldf(a_s, a_voff[j]) : 0.f;
         } else {
-            const float* ap = p.A + a_row + k0;
-            if (FULL && a_vec) {
-                const float4 v = *reinterpret_cast<const float4*>(ap);
+            if constexpr (FULL && VEC) {
+                const float4 v = ldf4(a_s, a_voff[0]);
                 f.a[0] = v.x; f.a[1] = v.y; f.a[2] = v.z; f.a[3] = v.w;
             } else {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) f.a[j] = (FULL || k0 + j < ke) ? ap[j] : 0.f;
+                for (int j = 0; j < 4; ++j) f.a[j] = (FULL || kcur + j < ke) ? ldf(a_s, a_voff[0] + 4 * j) : 0.f;
             }
         }
+        a_s += a_step;
         if constexpr (TB) {
 #pragma unroll
             for (int nb = 0; nb < NBW; ++nb) {
-                const float* bp = p.B + ncol[nb] * p.ldb + k0;
-                if (FULL && b_vec) {
-                    const float4 v = *reinterpret_cast<const float4*>(bp);
+                if constexpr (FULL && VEC) {
+                    const float4 v = ldf4(b_s, b_voff[nb]);
                     f.b[nb][0] = v.x; f.b[nb][1] = v.y; f.b[nb][2] = v.z; f.b[nb][3] = v.w;
                 } else {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) f.b[nb][j] = (FULL || k0 + j < ke) ? bp[j] : 0.f;
+                    for (int j = 0; j < 4; ++j) f.b[nb][j] = (FULL || kcur + j < ke) ? ldf(b_s, b_voff[nb] + 4 * j) : 0.f;
                 }
             }
         } else {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const bool ok = FULL || k0 + j < ke;
-                const float* bp = p.B + (k0 + j) * p.ldb;
+                const bool ok = FULL || kcur + j < ke;
+                if constexpr (row_vec && NBW == 4) {
+                    const float4 v = ok ? ldf4(b_s, b_voff[j]) : make_float4(0.f, 0.f, 0.f, 0.f);
+                    f.b[0][j] = v.x; f.b[1][j] = v.y; f.b[2][j] = v.z; f.b[3][j] = v.w;
+                } else if constexpr (row_vec && NBW == 2) {
+                    const float2 v = ok ? *reinterpret_cast<const float2*>(b_s + b_voff[j]) : make_float2(0.f, 0.f);
+                    f.b[0][j] = v.x; f.b[1][j] = v.y;
+                } else {
 #pragma unroll
-                for (int nb = 0; nb < NBW; ++nb) f.b[nb][j] = ok ? bp[ncol[nb]] : 0.f;
+                    for (int nb = 0; nb < NBW; ++nb) f.b[nb][j] = ok ? ldf(b_s, b_voff[j] + ncol4[nb]) : 0.f;
+                }
             }
         }
+        b_s += b_step;
+        kcur += 16;
     };
 
     floatx4 acc[NBW];
@@ -169,39 +217,62 @@ __global__ __launch_bounds__(256) void gemm_direct_kernel(GemmArgs p, int ks, in
                 acc[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a[j], f.b[nb][j], acc[nb], 0, 0, 0);
     };
 
-    if (nfull > 0 || tail > 0) {
+    {
         constexpr std::true_type whole{};
         constexpr std::false_type ragged{};
-        DirectFrag<NBW> f[PD], ft;
+        // Two register sets of PD chunks each.  While one set is multiplied the other is in flight, so
+        // every wait is for loads issued a whole set of multiplies earlier.  (Refilling chunk by
+        // chunk would keep more loads in flight, but the compiler's wait insertion then drains
+        // everything at the head of the loop; with whole sets the drain it inserts there is the
+        // wait that is needed anyway.)
+        DirectFrag<NBW> f0[PD], f1[PD], ft;
+        auto load_set = [&](DirectFrag<NBW>* f) {
+#pragma unroll
+            for (int s = 0; s < PD; ++s) load(f[s], whole);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        auto mma_set = [&](const DirectFrag<NBW>* f) {
+#pragma unroll
+            for (int s = 0; s < PD; ++s) mma(f[s]);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        const int sets = nfull / PD;
+        int left = nfull;                                      // whole chunks not yet loaded
+        if (sets >= 2) {
+            load_set(f0);
+            int done = 0;                                      // sets multiplied; set `done` is in flight in f0
+            while (done + 2 < sets) {
+                load_set(f1);
+                mma_set(f0);
+                load_set(f0);
+                mma_set(f1);
+                done += 2;
+            }
+            if (done + 1 < sets) {
+                load_set(f1);
+                mma_set(f0);
+                mma_set(f1);
+            } else {
+                mma_set(f0);
+            }
+            left = nfull - sets * PD;                          // < PD
+        }
+        // What is left (fewer than 2*PD whole chunks, then the ragged one): all in flight at once,
+        // then multiplied.
 #pragma unroll
         for (int s = 0; s < PD; ++s)
-            if (s < nfull) load(f[s], kb + 16 * s, whole);
-        // a short range has all its whole chunks in flight now: send the ragged one after them
-        const bool tail_early = tail > 0 && nfull <= PD;
-        if (tail_early) load(ft, kb + 16 * (int64_t)nfull, ragged);
-        int c0 = 0;
-        for (; c0 + 2 * PD <= nfull; c0 += PD) {
-#pragma unroll
-            for (int s = 0; s < PD; ++s) {
-                mma(f[s]);
-                load(f[s], kb + 16 * (int64_t)(c0 + s + PD), whole);
-            }
-        }
-        const int rem = nfull - c0;                            // < 2 * PD chunks left, min(rem, PD) in flight
-#pragma unroll
-        for (int s = 0; s < PD; ++s) {
-            if (s < rem) {
-                mma(f[s]);
-                if (s + PD < rem) load(f[s], kb + 16 * (int64_t)(c0 + s + PD), whole);
-            }
-        }
+            if (s < left) load(f0[s], whole);
 #pragma unroll
         for (int s = 0; s < PD; ++s)
-            if (s + PD < rem) mma(f[s]);
-        if (tail > 0) {
-            if (!tail_early) load(ft, kb + 16 * (int64_t)nfull, ragged);
-            mma(ft);
-        }
+            if (s + PD < left) load(f1[s], whole);
+        if (tail > 0) load(ft, ragged);
+#pragma unroll
+        for (int s = 0; s < PD; ++s)
+            if (s < left) mma(f0[s]);
+#pragma unroll
+        for (int s = 0; s < PD; ++s)
+            if (s + PD < left) mma(f1[s]);
+        if (tail > 0) mma(ft);
     }
 
     // partial sums of the k parts: part 0 adds parts 1 .. ks-1 in that order
@@ -222,49 +293,85 @@ __global__ __launch_bounds__(256) void gemm_direct_kernel(GemmArgs p, int ks, in
         }
     }
     if (!active || kpart != 0) return;
-    // accumulator register i of a lane is C[m0 + 4g + i][n0 + 16 nb + lane % 16]
+    // accumulator register i of block nb is C[m0 + 4g + i][n0 + NBW*(lane % 16) + nb]
+    constexpr bool out_vec = NBW > 1 && VEC;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int64_t m = m0 + 4 * g + i;
         if (m >= p.M) continue;
+        float* cp = p.C + m * p.ldc + n0 + NBW * r;
+        if (out_vec) {
+            if (n0 + NBW * r >= p.N) continue;
+            if constexpr (NBW == 4) {
+                float4 v = make_float4(acc[0][i], acc[1][i], acc[2][i], acc[3][i]);
+                if (p.accumulate) {
+                    const float4 o = *reinterpret_cast<const float4*>(cp);
+                    v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+                }
+                *reinterpret_cast<float4*>(cp) = v;
+            } else if constexpr (NBW == 2) {
+                float2 v = make_float2(acc[0][i], acc[1][i]);
+                if (p.accumulate) {
+                    const float2 o = *reinterpret_cast<const float2*>(cp);
+                    v.x += o.x; v.y += o.y;
+                }
+                *reinterpret_cast<float2*>(cp) = v;
+            }
+        } else {
 #pragma unroll
-        for (int nb = 0; nb < NBW; ++nb) {
-            const int64_t n = n0 + 16 * nb + r;
-            if (n >= p.N) continue;
-            float* cp = p.C + m * p.ldc + n;
-            *cp = p.accumulate ? *cp + acc[nb][i] : acc[nb][i];
+            for (int nb = 0; nb < NBW; ++nb) {
+                if (n0 + NBW * r + nb >= p.N) continue;
+                cp[nb] = p.accumulate ? cp[nb] + acc[nb][i] : acc[nb][i];
+            }
         }
     }
 }
 
 template <int LAYOUT>
-static int launch_direct_layout(GemmArgs a, int nbw, int ks, bool a_vec, bool b_vec, hipStream_t s) {
+static int launch_direct_layout(GemmArgs a, int nbw, int ks, bool vec, hipStream_t s) {
     const int64_t row_groups = cdiv(cdiv(a.M, 16), 4 / ks);
     const int64_t col_groups = cdiv(a.N, 16 * nbw);
     if (row_groups * col_groups > kMaxGrid) return LG_ERR_UNSUPPORTED;
     a.tiles_m = (unsigned)row_groups;
     a.tiles_n = (unsigned)col_groups;
     const dim3 grid((unsigned)(row_groups * col_groups)), block(256);
+#define LG_DIRECT(NBW)                                                                                  \
+    do {                                                                                                \
+        if (vec) hipLaunchKernelGGL((gemm_direct_kernel<LAYOUT, NBW, true>), grid, block, 0, s, a, ks); \
+        else     hipLaunchKernelGGL((gemm_direct_kernel<LAYOUT, NBW, false>), grid, block, 0, s, a, ks); \
+    } while (0)
     switch (nbw) {
-        case 1: hipLaunchKernelGGL((gemm_direct_kernel<LAYOUT, 1>), grid, block, 0, s, a, ks, (int)a_vec, (int)b_vec); break;
-        case 2: hipLaunchKernelGGL((gemm_direct_kernel<LAYOUT, 2>), grid, block, 0, s, a, ks, (int)a_vec, (int)b_vec); break;
-        default: hipLaunchKernelGGL((gemm_direct_kernel<LAYOUT, 4>), grid, block, 0, s, a, ks, (int)a_vec, (int)b_vec); break;
+        case 1: LG_DIRECT(1); break;
+        case 2: LG_DIRECT(2); break;
+        default: LG_DIRECT(4); break;
     }
+#undef LG_DIRECT
     return launch_status();
 }
 
-int launch_direct(const GemmArgs& a, Layout layout, int nbw, int ks, hipStream_t s) {
-    if ((nbw != 1 && nbw != 2 && nbw != 4) || (ks != 1 && ks != 2 && ks != 4)) return LG_ERR_INVALID_ARG;
+// The kernel addresses its operands with 32-bit byte offsets.
+bool direct_can_run(const GemmArgs& a, Layout layout) {
+    const int64_t lim = (int64_t)1 << 32, ld_lim = (int64_t)1 << 26;
+    int64_t a_bytes, b_bytes;
     switch (layout) {
-        case Layout::NN:
-            return launch_direct_layout<0>(a, nbw, ks, a.lda % 4 == 0 && aligned16(a.A), false, s);
-        case Layout::CONV:
-            return launch_direct_layout<1>(a, nbw, ks, a.g.C % 4 == 0 && aligned16(a.A), false, s);
-        case Layout::TN:
-            return launch_direct_layout<2>(a, nbw, ks, false, false, s);
-        default:
-            return launch_direct_layout<3>(a, nbw, ks, a.lda % 4 == 0 && aligned16(a.A),
-                                           a.ldb % 4 == 0 && aligned16(a.B), s);
+        case Layout::CONV: a_bytes = a.M / (a.g.OH * a.g.OW) * a.g.H * a.g.W * a.g.C * 4; break;
+        case Layout::TN: a_bytes = ((a.K - 1) * a.lda + a.M) * 4; break;
+        default: a_bytes = ((a.M - 1) * a.lda + a.K) * 4; break;
+    }
+    b_bytes = layout == Layout::NT ? ((a.N - 1) * a.ldb + a.K) * 4 : ((a.K - 1) * a.ldb + a.N) * 4;
+    return a_bytes < lim && b_bytes < lim && a.lda < ld_lim && a.ldb < ld_lim;
+}
+
+// `vec`: the caller's alignment verdict for the tiled kernel (all bases and pitches 16-byte aligned,
+// K and N multiples of 4, convolution: C a multiple of 4) holds for this kernel too.
+int launch_direct(const GemmArgs& a, Layout layout, int nbw, int ks, bool vec, hipStream_t s) {
+    if ((nbw != 1 && nbw != 2 && nbw != 4) || (ks != 1 && ks != 2 && ks != 4)) return LG_ERR_INVALID_ARG;
+    if (!direct_can_run(a, layout)) return LG_ERR_UNSUPPORTED;
+    switch (layout) {
+        case Layout::NN: return launch_direct_layout<0>(a, nbw, ks, vec, s);
+        case Layout::CONV: return launch_direct_layout<1>(a, nbw, ks, vec, s);
+        case Layout::TN: return launch_direct_layout<2>(a, nbw, ks, vec, s);
+        default: return launch_direct_layout<3>(a, nbw, ks, vec, s);
     }
 }
 

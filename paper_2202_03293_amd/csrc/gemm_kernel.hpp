@@ -838,22 +838,32 @@ inline Plan make_plan(int64_t M, int64_t N, int64_t K) {
         }
     }
     // The register-direct kernel (gemm_direct.hip): blocks of 16 x 16*nbw per wavefront, the k range
-    // cut into ks parts inside a workgroup.  Fitted to launches replayed from a graph: a wavefront
-    // alone on its SIMD takes 0.05 + 0.09*nbw us per 16-deep k chunk (load latency it cannot hide
-    // and the dependent MFMA chain); wavefronts beyond one per SIMD queue up; operands come from
-    // the caches at ~10 TB/s over the whole chip, the output goes out at the same price; against
-    // the tiled kernel's launch constant above it starts 3 us ahead (no staging ring to fill, no
-    // barrier, a short epilogue).
-    for (int nbw = 1; nbw <= 4; nbw *= 2) {
+    // cut into ks parts inside a workgroup.  Fitted to launches replayed from a graph.  A wavefront
+    // alone on its SIMD takes 0.05 + 0.07*nbw us per 16-deep k chunk (load latency it does not hide
+    // plus the dependent MFMA chain, 0.053*nbw us of which is the matrix pipe); the register budget
+    // lets 4 / 3 / 2 wavefronts (nbw = 1 / 2 / 4) share a SIMD and overlap their stalls; operands
+    // come from the caches at ~15 TB/s over the whole chip (~9 TB/s once wavefronts queue behind one
+    // another and contend for them) and the output costs the same; against
+    // the tiled kernel's launch constant above it starts 1.1 us ahead (no staging ring to fill, no
+    // barriers, a short epilogue).  Extents that rule out 16-byte accesses (K or N not a multiple
+    // of 4) leave only the one-float path, which is worth it for a single round of small blocks.
+    const bool one_float = (K % 4 != 0) || (N % 4 != 0);
+    for (int nbw = 1; nbw <= (one_float ? 1 : 4); nbw *= 2) {
+        const int occ = nbw == 1 ? 4 : nbw == 2 ? 3 : 2;
         for (int ks = 1; ks <= 4; ks *= 2) {
             const int64_t groups = cdiv(cdiv(M, 16), 4 / ks) * cdiv(N, 16 * nbw);
             if (groups > kMaxGrid) continue;
             const double waves = (double)cdiv(M, 16) * (double)cdiv(N, 16 * nbw) * ks;
+            if (one_float && waves > 4 * kCUs) continue;
             const double chunks = (double)cdiv(cdiv(K, 16), ks);
-            const double per_wave = chunks * (0.05e-6 + 0.09e-6 * nbw);
-            const double queued = (double)cdiv((int64_t)waves, 4 * kCUs);
+            const double per_simd = (double)cdiv((int64_t)waves, 4 * kCUs);
+            const double chain = chunks * (0.05e-6 + 0.07e-6 * nbw) * (one_float ? 1.7 : 1.0) * (double)cdiv((int64_t)per_simd, occ);
+            const double pipe = per_simd * chunks * 0.053e-6 * nbw;
             const double bytes = waves * chunks * 16.0 * (16 + 16 * nbw) * 4.0 + 2.0 * M * N * 4.0;
-            const double cost = 7e-6 + per_wave * queued + bytes / 10e12 + (ks > 1 ? 0.3e-6 : 0.0);
+            double cost = chain > pipe ? chain : pipe;
+            const double cache_rate = waves <= 4 * kCUs ? 15e12 : 9e12;
+            if (bytes / cache_rate > cost) cost = bytes / cache_rate;
+            cost += 6.9e-6 + (ks > 1 ? 0.3e-6 : 0.0);
             if (cost < best_cost) {
                 best_cost = cost;
                 best = Plan{};
@@ -902,7 +912,8 @@ static void launch_planned(const GemmArgs& a, const Plan& pl, bool vec, hipStrea
 enum class Layout { NN, CONV, TN, NT };
 
 // The register-direct kernel for small and skinny problems (gemm_direct.hip); returns an LG_* status.
-int launch_direct(const GemmArgs& a, Layout layout, int nbw, int ks, hipStream_t s);
+int launch_direct(const GemmArgs& a, Layout layout, int nbw, int ks, bool vec, hipStream_t s);
+bool direct_can_run(const GemmArgs& a, Layout layout);     // operands within its 32-bit offsets?
 
 // Implemented in gemm.hip (AB and convolution) and gemm_t.hip (A^T B, A B^T).
 void launch_nn(const GemmArgs& a, const Plan& pl, bool vec, hipStream_t s);
