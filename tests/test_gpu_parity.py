@@ -122,16 +122,30 @@ def test_matmul_is_deterministic(lg):
 
 
 def test_matmul_workspace_errors(lg):
-    M, N, K = 256, 256, 4096
+    # a shape the planner splits along k (found, not assumed: the plan is the library's business)
+    shape = next((s for s in [(784, 512, 4608), (512, 1024, 8192), (1024, 1024, 16384), (640, 640, 32768)]
+                  if lg.lg_matmul_workspace_bytes(*s) > 0), None)
+    assert shape is not None, "no candidate shape is split along k"
+    M, N, K = shape
     need = lg.lg_matmul_workspace_bytes(M, N, K)
-    if need == 0:
-        pytest.skip("this shape is not split")
     A = torch.zeros((M, K), device="cuda"); B = torch.zeros((K, N), device="cuda"); C = torch.zeros((M, N), device="cuda")
     with pytest.raises(lg.LgError) as e:
         lg.lg_matmul(A, B, C)
     assert e.value.status == -3
     with pytest.raises(lg.LgError):
         lg.lg_matmul(A, B, C, workspace=workspace(need - 4))
+    # and with the split forced on a small shape
+    need = lg.lg_gemm_variant_workspace_bytes(256, 256, 1024, 3, 4)
+    assert need == 4 * 256 * 256 * 4
+    A = torch.zeros((256, 1024), device="cuda"); B = torch.zeros((1024, 256), device="cuda"); C = torch.zeros((256, 256), device="cuda")
+    with pytest.raises(lg.LgError) as e:
+        lg.lg_matmul_variant(A, B, C, 3, 4)
+    assert e.value.status == -3
+    with pytest.raises(lg.LgError):
+        lg.lg_matmul_variant(A, B, C, 3, 4, workspace=workspace(need - 4))
+    lg.lg_matmul_variant(A, B, C, 3, 4, workspace=workspace(need))
+    sync()
+    assert bool((C == 0).all())
 
 
 @pytest.mark.parametrize("case,shape", list(enumerate(si.MATMUL_SWEEP)))
