@@ -22,6 +22,7 @@
 //       NB blocks and the epilogue finds NB adjacent columns of a row in one lane (128-bit stores).
 #pragma once
 #include "lg_common.hpp"
+#include "gemm_plan.hpp"
 #include <type_traits>
 
 namespace lg {
@@ -769,116 +770,16 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
     }
 }
 
-// ---- the tile menu and the planner (host) ---------------------------------------------------------
-// All tiles: 4 wavefronts, one per SIMD.  `occ` = workgroups of that tile a CU can hold (LDS and
-// registers), `mfma` = matrix-pipe clocks one k-slice costs one SIMD, `eff` = the measured fraction
-// of the matrix-pipe rate the tile sustains with a full CU (clock-normalised), `dead` = clocks per
-// slice of barrier skew and LDS latency that only other resident workgroups hide (less with the
-// four-stage ring, which fetches across the barrier).  The big tile keeps three stages: a fourth
-// would cost it its second workgroup per CU.
+// ---- the tile menu ----------------------------------------------------------------------------------
+// All tiles: 4 wavefronts, one per SIMD.  The big tile keeps three LDS stages: a fourth would cost it
+// its second workgroup per CU.  The host-side table of these tiles (same order) and the planner
+// that picks among them are in gemm_plan.hpp.
 using Tile0 = Tile<128, 256, 16, 64, 128, 2, 3, false>;   // waves of 64x128
 using Tile1 = Tile<128, 128, 16, 32, 128, 2, 4>;   // waves of 32x128
 using Tile2 = Tile<128, 64, 16, 32, 64, 3, 4>;     // waves of 32x64 (narrow outputs, e.g. F = 64)
 using Tile3 = Tile<64, 64, 16, 32, 32, 4, 4>;      // waves of 32x32 (small problems)
 using Tile4 = Tile<64, 128, 32, 32, 64, 2>;        // waves of 32x64, deeper slices (mid-size problems)
 using Tile5 = Tile<64, 64, 32, 32, 32, 2, 4>;      // waves of 32x32, deeper slices
-
-struct TileInfo { int bm, bn, bk, occ, mfma; double eff, dead; };
-constexpr int kNumTiles = 6;
-static const TileInfo kTiles[kNumTiles] = {
-    {128, 256, 16, 2, 4096, 0.935, 350}, {128, 128, 16, 2, 2048, 0.96, 300}, {128, 64, 16, 3, 1024, 0.91, 250},
-    {64, 64, 16, 5, 512, 0.88, 220},     {64, 128, 32, 2, 2048, 0.89, 478},  {64, 64, 32, 2, 1024, 0.88, 330}};
-
-struct Plan {
-    int tile;          // index into kTiles
-    int64_t tiles_m, tiles_n, splits, k_per_split;
-    int direct_nbw;    // > 0: the register-direct kernel (gemm_direct.hip) with blocks 16 x 16*direct_nbw ...
-    int direct_ks;     // ... and the k range cut into this many parts inside a workgroup; `tile` etc. unused
-};
-
-constexpr int kCUs = 256;
-constexpr int kKGran = 64;   // split-k slabs are multiples of this (a multiple of every tile's BK)
-
-// Pick (tile, k-split) with a cost model fitted to measurements on this part: when c workgroups
-// share a CU, one k-slice of all of them takes  c * mfma / eff + dead / c  clocks.  Each round of
-// workgroups on a CU also pays `fill`: start-up, and the output write, which is HBM-bound because
-// the workgroups of a round reach their epilogues together (~9 bytes per clock per CU).  The busiest CU decides; a launch costs ~4 us of fill and drain;
-// split-k adds the partial-sum traffic and a second launch.
-inline Plan make_plan(int64_t M, int64_t N, int64_t K) {
-    const double clk = 2.4e9;
-    const int64_t kslabs = cdiv(K, kKGran);
-    static const int split_menu[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
-    Plan best{};
-    double best_cost = 1e300;
-    for (int ti = 0; ti < kNumTiles; ++ti) {
-        const TileInfo& tl = kTiles[ti];
-        const int64_t tm = cdiv(M, tl.bm), tn = cdiv(N, tl.bn);
-        const double dead = tl.dead;
-        // tile 0 has no k-tail handling: a k that is not a multiple of its slice depth sends every
-        // tile down the register-staged path
-        const double slow = (ti == 0 && K % tl.bk != 0) ? 1.25 : 1.0;
-        const double fill = 3000.0 + tl.occ * tl.bm * tl.bn * 4.0 / 9.0;
-        for (int sp : split_menu) {
-            if (sp > 1 && kslabs < 2 * sp) break;                // keep at least 128 k per slab
-            const int64_t kps = cdiv(kslabs, sp) * kKGran;
-            const int64_t splits = cdiv(K, kps);
-            if (splits != sp && sp > 1) continue;                // same plan as a smaller menu entry
-            const int64_t wgs = tm * tn * splits;
-            const double nslices = (double)cdiv(kps < K ? kps : K, tl.bk);
-            const int64_t per_cu = cdiv(wgs, kCUs);              // workgroups on the busiest CU
-            const int64_t full = per_cu / tl.occ, rest = per_cu % tl.occ;
-            double clocks = (double)full * (nslices * (tl.occ * tl.mfma / tl.eff + dead / tl.occ) + fill);
-            if (rest) clocks += nslices * (rest * tl.mfma / tl.eff + dead / rest) + fill;
-            double cost = slow * clocks / clk + 4e-6;
-            if (splits > 1) cost += 2.0 * splits * M * N * 4.0 / 3.0e12 + 5e-6;
-            if (cost < best_cost) {
-                best_cost = cost;
-                best.tile = ti; best.tiles_m = tm; best.tiles_n = tn; best.splits = splits; best.k_per_split = kps;
-            }
-        }
-    }
-    // The register-direct kernel (gemm_direct.hip): blocks of 16 x 16*nbw per wavefront, the k range
-    // cut into ks parts inside a workgroup.  Fitted to launches replayed from a graph.  A wavefront
-    // alone on its SIMD takes 0.05 + 0.07*nbw us per 16-deep k chunk (load latency it does not hide
-    // plus the dependent MFMA chain, 0.053*nbw us of which is the matrix pipe); the register budget
-    // lets 4 / 3 / 2 wavefronts (nbw = 1 / 2 / 4) share a SIMD and overlap their stalls; operands
-    // come from the caches at ~15 TB/s over the whole chip (~9 TB/s once wavefronts queue behind one
-    // another and contend for them) and the output costs the same; against
-    // the tiled kernel's launch constant above it starts 1.1 us ahead (no staging ring to fill, no
-    // barriers, a short epilogue).  Extents that rule out 16-byte accesses (K or N not a multiple
-    // of 4) leave only the one-float path, which is worth it for a single round of small blocks.
-    const bool one_float = (K % 4 != 0) || (N % 4 != 0);
-    for (int nbw = 1; nbw <= (one_float ? 1 : 4); nbw *= 2) {
-        const int occ = nbw == 1 ? 4 : nbw == 2 ? 3 : 2;
-        for (int ks = 1; ks <= 4; ks *= 2) {
-            const int64_t groups = cdiv(cdiv(M, 16), 4 / ks) * cdiv(N, 16 * nbw);
-            if (groups > kMaxGrid) continue;
-            const double waves = (double)cdiv(M, 16) * (double)cdiv(N, 16 * nbw) * ks;
-            if (one_float && waves > 4 * kCUs) continue;
-            const double chunks = (double)cdiv(cdiv(K, 16), ks);
-            const double per_simd = (double)cdiv((int64_t)waves, 4 * kCUs);
-            const double chain = chunks * (0.05e-6 + 0.07e-6 * nbw) * (one_float ? 1.7 : 1.0) * (double)cdiv((int64_t)per_simd, occ);
-            const double pipe = per_simd * chunks * 0.053e-6 * nbw;
-            const double bytes = waves * chunks * 16.0 * (16 + 16 * nbw) * 4.0 + 2.0 * M * N * 4.0;
-            double cost = chain > pipe ? chain : pipe;
-            const double cache_rate = waves <= 4 * kCUs ? 15e12 : 9e12;
-            if (bytes / cache_rate > cost) cost = bytes / cache_rate;
-            cost += 6.9e-6 + (ks > 1 ? 0.3e-6 : 0.0);
-            if (cost < best_cost) {
-                best_cost = cost;
-                best = Plan{};
-                best.splits = 1;
-                best.direct_nbw = nbw;
-                best.direct_ks = ks;
-            }
-        }
-    }
-    return best;
-}
-
-inline size_t plan_workspace(const Plan& pl, int64_t M, int64_t N) {
-    return pl.splits > 1 ? (size_t)(pl.splits * M * N) * sizeof(float) : 0;
-}
 
 template <class T, bool VEC, bool CONV, bool TA, bool TB>
 static void launch_gemm(const GemmArgs& a, unsigned splits, hipStream_t s) {
