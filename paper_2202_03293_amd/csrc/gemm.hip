@@ -107,7 +107,7 @@ static int run_gemm(const GemmArgs& a, Layout layout, bool vec, int user_accumul
         // Operands that turn out unaligned (the planner saw only extents): one float per load costs
         // the wider blocks more registers than they have, and more than one round of small blocks
         // is the tiled kernel's business.
-        if (pl.direct_nbw > 0 && !vec) {
+        if (pl.direct_nbw > 0 && !vec && a.K % 4 == 0 && a.N % 4 == 0) {
             if (cdiv(a.M, 16) * cdiv(a.N, 16) * pl.direct_ks > 4 * kCUs) forced_plan(a.M, a.N, a.K, 3, 1, &pl);
             else pl.direct_nbw = 1;
         }

@@ -74,15 +74,17 @@ inline Plan make_plan(int64_t M, int64_t N, int64_t K) {
     // another and contend for them) and the output costs the same; against
     // the tiled kernel's launch constant above it starts 1.1 us ahead (no staging ring to fill, no
     // barriers, a short epilogue).  Extents that rule out 16-byte accesses (K or N not a multiple
-    // of 4) leave only the one-float path, which is worth it for a single round of small blocks.
+    // of 4) leave only the one-float path, which is worth it for a single round of small blocks,
+    // or when the contraction is one or two chunks deep (a 3x3 filter over three channels), where
+    // the tiled kernel spends its time filling and draining its ring.
     const bool one_float = (K % 4 != 0) || (N % 4 != 0);
-    for (int nbw = 1; nbw <= (one_float ? 1 : 4); nbw *= 2) {
+    for (int nbw = 1; nbw <= (one_float ? 2 : 4); nbw *= 2) {
         const int occ = nbw == 1 ? 4 : nbw == 2 ? 3 : 2;
         for (int ks = 1; ks <= 4; ks *= 2) {
             const int64_t groups = cdiv(cdiv(M, 16), 4 / ks) * cdiv(N, 16 * nbw);
             if (groups > kMaxGrid) continue;
             const double waves = (double)cdiv(M, 16) * (double)cdiv(N, 16 * nbw) * ks;
-            if (one_float && waves > 4 * kCUs) continue;
+            if (one_float && waves > 4 * kCUs && K > 32) continue;
             const double chunks = (double)cdiv(cdiv(K, 16), ks);
             const double per_simd = (double)cdiv((int64_t)waves, 4 * kCUs);
             const double chain = chunks * (0.05e-6 + 0.07e-6 * nbw) * (one_float ? 1.7 : 1.0) * (double)cdiv((int64_t)per_simd, occ);
