@@ -115,7 +115,10 @@ int lg_matmul_plan(int64_t M, int64_t N, int64_t K, int *block_m, int *block_n, 
  *                            convolution M = N*OH*OW, N = F, K = KH*KW*C -- 0 when k_splits
  *                            runs as one slab; same alignment rule as lg_matmul's workspace.
  * Arguments, layouts, ownership and errors are those of lg_matmul_t / lg_conv2d_nhwc_hwcf;
- * an unknown variant or a k_splits the variant does not take is LG_ERR_INVALID_ARG.
+ * an unknown variant or a k_splits the variant does not take is LG_ERR_INVALID_ARG.  The
+ * register-direct variants address their operands with 32-bit byte offsets: asked to run
+ * an A or B of 4 GiB or more, or a leading dimension of 2^26 or more, they return
+ * LG_ERR_UNSUPPORTED (the default entry points never pick them for such operands).
  */
 int lg_gemm_variants(void);
 int lg_gemm_variant_info(int variant, int *block_m, int *block_n, int *block_k, int *k_parts);

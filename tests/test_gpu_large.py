@@ -98,3 +98,24 @@ def test_conv_input_past_2_31_bytes(lg, lgo, N, H, W, C):
         ref = lgo.conv2d_nhwc_hwcf(np.ascontiguousarray(I[n:n + 1].cpu().numpy()), Kh)
         assert_close(O[n:n + 1].cpu().numpy(), ref, KH * KW * C, f"conv image {n}")
     assert bool(torch.isfinite(O).all())
+
+
+def test_matmul_with_rows_256_mib_apart(lg, lgo):
+    """A small problem whose A rows are 2^26 floats apart (a 12.9 GB allocation): the planner's pick for
+    the extents is the register-direct kernel, whose 32-bit offsets do not reach that far, so the
+    call must run on the tiled kernel's 64-bit path instead; forcing the direct kernel is refused."""
+    M, N, K, lda = 48, 40, 72, 2 ** 26
+    assert lg.lg_matmul_plan(M, N, K)[0] == 16
+    g = torch.Generator(device="cuda").manual_seed(9)
+    buf = torch.empty((M, lda), device="cuda")
+    A = buf[:, :K]
+    A.copy_(torch.rand((M, K), device="cuda", generator=g) * 2 - 1)
+    B = torch.rand((K, N), device="cuda", generator=g) * 2 - 1
+    C = torch.full((M, N), float("nan"), device="cuda")
+    lg.lg_matmul(A, B, C); sync()
+    ref = lgo.matmul(np.ascontiguousarray(A.cpu().numpy()), B.cpu().numpy())
+    assert_close(C.cpu().numpy(), ref, K, "matmul with lda = 2^26")
+    direct = next(v for v in range(lg.lg_gemm_variants()) if lg.lg_gemm_variant_info(v)[0] == 16)
+    with pytest.raises(lg.LgError) as e:
+        lg.lg_matmul_variant(A, B, C, direct)
+    assert e.value.status == -2          # LG_ERR_UNSUPPORTED
