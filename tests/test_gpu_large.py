@@ -119,3 +119,21 @@ def test_matmul_with_rows_256_mib_apart(lg, lgo):
     with pytest.raises(lg.LgError) as e:
         lg.lg_matmul_variant(A, B, C, direct)
     assert e.value.status == -2          # LG_ERR_UNSUPPORTED
+
+
+def test_first_layer_conv_many_rounds_of_small_blocks(lg, lgo):
+    """Three input channels, 3x3 filter: a contraction of 27, which the planner gives to the
+    register-direct kernel on its one-float path -- here as 25 000 blocks, many rounds of the chip.
+    The first and the last image are checked against the oracle element by element."""
+    N, H, W, C, F = 8, 226, 226, 3, 32
+    assert lg.lg_matmul_plan(N * 224 * 224, F, 27)[0] == 16
+    g = torch.Generator(device="cuda").manual_seed(10)
+    I = torch.rand((N, H, W, C), device="cuda", generator=g) * 2 - 1
+    Kf = torch.rand((3, 3, C, F), device="cuda", generator=g) * 2 - 1
+    O = torch.full((N, 224, 224, F), float("nan"), device="cuda")
+    lg.lg_conv2d_nhwc_hwcf(I, Kf, O); sync()
+    Kh = Kf.cpu().numpy()
+    for n in (0, N - 1):
+        ref = lgo.conv2d_nhwc_hwcf(np.ascontiguousarray(I[n:n + 1].cpu().numpy()), Kh)
+        assert_close(O[n:n + 1].cpu().numpy(), ref, 27, f"conv image {n}")
+    assert bool(torch.isfinite(O).all())
