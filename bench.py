@@ -13,6 +13,7 @@ against their own rooflines are under `ops`; `roofline` describes the dominant k
 GEMM tile the 8192^3 matmul runs on) and `cpu_baseline` the CPU oracle timed on a bounded sample.
 """
 import argparse
+import math
 import json
 import os
 import sys
@@ -327,6 +328,16 @@ def main():
                     us, ug = per_launch_us(lambda: lg.lg_dwconv1d_nwc_wc(I1s, Kd, Od, stride=st, dilation=dl))
                     sweep.append(dict(op="dwconv1d", size=size, stride=st, dilation=dl, us=us, us_graph=ug,
                                       gbps=4.0 * (ow * 32 + 3 * 32 + size * 32) / ug / 1e3))
+        # 2-D depthwise at the batch-1 MobileNet layer sizes of Section 4.7 (output extent x channels)
+        for size, C in ((112, 32), (112, 64), (56, 128), (28, 256), (14, 512), (7, 1024)):
+            for st, dl in ((1, 1), (2, 1), (1, 2), (2, 2)):
+                H = (size - 1) * st + 2 * dl + 1
+                Id2 = dev(si.uniform(5, 5, (1, H, H, C), -1, 1)); Kd2 = dev(si.uniform(5, 6, (3, 3, C), -1, 1))
+                Od2 = torch.empty((1, size, size, C), device="cuda")
+                us, ug = per_launch_us(lambda: lg.lg_dwconv2d_nhwc_hwc(Id2, Kd2, Od2, stride=(st, st), dilation=(dl, dl)))
+                g = math.gcd(st, dl)
+                sweep.append(dict(op="dwconv2d", size=size, channels=C, stride=st, dilation=dl, us=us, us_graph=ug,
+                                  gbps=4.0 * (size * size * C + 9 * C + H * H * C / (g * g)) / ug / 1e3))
         out["sweep"] = sweep
 
     # ------------------------------------------------------------------ CPU oracle baseline

@@ -423,6 +423,18 @@ def test_dwconv2d_window_kernels(lg, lgo, s, d):
         assert_close(run_dw2(lg, I, Kf, (s, s), (d, d), O0=O0, accumulate=True), ref2, 9, "dwconv2d window accumulate")
 
 
+# the 2-D depthwise sizes of Section 4.7: batch-1 MobileNet layers (output extent x channels), each
+# at strides and dilations 1 and 2
+@pytest.mark.parametrize("size,C", [(112, 32), (112, 64), (56, 128), (28, 256), (14, 512), (7, 1024)])
+@pytest.mark.parametrize("s,d", [(1, 1), (2, 1), (1, 2), (2, 2)])
+def test_dwconv2d_mobilenet_layers(lg, lgo, size, C, s, d):
+    H = (size - 1) * s + 2 * d + 1
+    I, Kf = si.dwconv2d_inputs(138 + C, 1, H, H, C, 3, 3)
+    ref = lgo.dwconv2d_nhwc_hwc(I, Kf, stride=(s, s), dilation=(d, d))
+    assert ref.shape == (1, size, size, C)
+    assert_close(run_dw2(lg, I, Kf, (s, s), (d, d)), ref, 9, f"dwconv2d {size}x{size}x{C} s{s} d{d}")
+
+
 def test_dwconv_accumulate_and_delta(lg, lgo):
     I, Kf = si.dwconv1d_inputs(132, 2, 50, 16, 3)
     O0 = si.uniform(132, 9, (2, 48, 16), -1, 1)
