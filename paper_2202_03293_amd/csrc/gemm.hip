@@ -57,7 +57,7 @@ static int run_plan(GemmArgs a, Layout layout, bool vec, const Plan& pl, int use
                     size_t workspace_bytes, hipStream_t s) {
     if (pl.direct_nbw > 0) {
         a.accumulate = user_accumulate;
-        return launch_direct(a, layout, pl.direct_nbw, pl.direct_ks, vec, s);
+        return launch_direct(a, layout, pl.direct_nbw, pl.direct_ks, s);
     }
     const size_t need = plan_workspace(pl, a.M, a.N);
     if (need > 0) {

@@ -27,15 +27,24 @@ struct DirectFrag {
     float b[NBW][4];       // B[chunk + 4g + j][column of block nb]
 };
 
-// LAYOUT: 0 = AB, 1 = convolution, 2 = A^T B, 3 = A B^T.  VEC: every operand may be accessed 16 bytes
-// at a time along its contiguous axis (bases and row pitches 16-byte aligned, N a multiple of 4;
-// convolution: C a multiple of 4); otherwise every access is one float.  A compile-time switch on
-// purpose: a run-time test inside the fetch splits it into basic blocks, and the compiler then
-// waits for all loads in flight at every join.
-template <int LAYOUT, int NBW, bool VEC>
-__global__ __launch_bounds__(256, NBW == 1 ? 4 : NBW == 2 ? 3 : 2) void gemm_direct_kernel(GemmArgs p, int ks) {
+// LAYOUT: 0 = AB, 1 = convolution, 2 = A^T B, 3 = A B^T.  AVEC: A may be fetched 16 bytes at a time
+// along k (base and row pitch 16-byte aligned; convolution: C a multiple of 4); BCVEC: the same for
+// B and C along their contiguous axis (N a multiple of 4 as well); otherwise every access to that
+// operand is one float.  Compile-time switches on purpose: a run-time test inside the fetch splits
+// it into basic blocks, and the compiler then waits for all loads in flight at every join.  A
+// convolution over three channels into a multiple of four filters is the (false, true) case.
+// Convolutions with K = KH*KW*C up to kTapTable get the byte offset of every k from the row's tap
+// (0, 0), channel 0 as a table from the host (through the kernel arguments into LDS) instead of
+// walking (kh, kw, c) per lane: the walk starts with integer divisions, which at three channels
+// cost more instructions than the loads and multiplies of the whole block.
+constexpr int kTapTable = 512;
+struct DirectTaps { uint32_t off[kTapTable + 16]; };          // + one chunk of zeros for lanes past K
+
+template <int LAYOUT, int NBW, bool AVEC, bool BCVEC, bool TABLE>
+__device__ __forceinline__ void gemm_direct_body(const GemmArgs& p, int ks, const uint32_t* taps) {
     constexpr bool CONV = LAYOUT == 1, TA = LAYOUT == 2, TB = LAYOUT == 3;
-    constexpr int PD = (VEC || NBW == 1) ? 4 : 2;             // k chunks per register set (one-float loads take an offset register each)
+    static_assert(!TABLE || CONV, "the tap table belongs to the convolution");
+    constexpr int PD = (BCVEC || NBW == 1) ? 4 : 2;             // k chunks per register set (one-float loads take an offset register each)
     __shared__ float red[4][NBW * 4][kWave];
 
     const int lane = threadIdx.x % kWave;
@@ -66,7 +75,7 @@ __global__ __launch_bounds__(256, NBW == 1 ? 4 : NBW == 2 ? 3 : 2) void gemm_dir
         ncol[nb] = n < p.N ? n : p.N - 1;
     }
     // whole groups of NBW columns lie inside or outside the matrix when N % NBW == 0
-    constexpr bool row_vec = NBW > 1 && VEC;
+    constexpr bool row_vec = NBW > 1 && BCVEC;
     const int64_t ngroup = (n0 + NBW * r < p.N) ? n0 + NBW * r : p.N - NBW;   // used when row_vec
 
     // Addresses are a wave-uniform base that advances by one chunk (16 k) per fetch -- chunks are
@@ -117,7 +126,7 @@ __global__ __launch_bounds__(256, NBW == 1 ? 4 : NBW == 2 ? 3 : 2) void gemm_dir
     // four otherwise).
     int wc[4] = {0, 0, 0, 0}, wkw[4] = {0, 0, 0, 0}, wkh[4] = {0, 0, 0, 0};
     const int cvC = (int)p.g.C, cvKW = (int)p.g.KW;
-    if constexpr (CONV) {
+    if constexpr (CONV && !TABLE) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const uint32_t k = (uint32_t)(kb + 4 * g + j);
@@ -129,9 +138,11 @@ __global__ __launch_bounds__(256, NBW == 1 ? 4 : NBW == 2 ? 3 : 2) void gemm_dir
     }
     const uint32_t tap_kh = (uint32_t)(p.g.DH * p.g.W * p.g.C * 4), tap_kw = (uint32_t)(p.g.DW * p.g.C * 4);
     auto tap_offset = [&](int j) -> uint32_t {                 // bytes from the row's tap (0, 0), channel 0
-        return (uint32_t)wkh[j] * tap_kh + (uint32_t)wkw[j] * tap_kw + (uint32_t)wc[j] * 4u;
+        if constexpr (TABLE) return taps[kcur + j];
+        else return (uint32_t)wkh[j] * tap_kh + (uint32_t)wkw[j] * tap_kw + (uint32_t)wc[j] * 4u;
     };
     auto walk_on = [&](int j) {
+        if constexpr (TABLE) return;
         wc[j] += 16;
         while (wc[j] >= cvC) {
             wc[j] -= cvC;
@@ -145,7 +156,7 @@ __global__ __launch_bounds__(256, NBW == 1 ? 4 : NBW == 2 ? 3 : 2) void gemm_dir
     auto load = [&](DirectFrag<NBW>& f, auto full_c) {
         constexpr bool FULL = decltype(full_c)::value;
         if constexpr (CONV) {
-            if constexpr (VEC) {
+            if constexpr (AVEC) {
                 const uint32_t off = a_voff[0] + tap_offset(0);
                 if constexpr (FULL) {
                     const float4 v = ldf4(a_s, off);
@@ -166,7 +177,7 @@ __global__ __launch_bounds__(256, NBW == 1 ? 4 : NBW == 2 ? 3 : 2) void gemm_dir
 #pragma unroll
             for (int j = 0; j < 4; ++j) f.a[j] = (FULL || kcur + j < ke) ? ldf(a_s, a_voff[j]) : 0.f;
         } else {
-            if constexpr (FULL && VEC) {
+            if constexpr (FULL && AVEC) {
                 const float4 v = ldf4(a_s, a_voff[0]);
                 f.a[0] = v.x; f.a[1] = v.y; f.a[2] = v.z; f.a[3] = v.w;
             } else {
@@ -178,7 +189,7 @@ __global__ __launch_bounds__(256, NBW == 1 ? 4 : NBW == 2 ? 3 : 2) void gemm_dir
         if constexpr (TB) {
 #pragma unroll
             for (int nb = 0; nb < NBW; ++nb) {
-                if constexpr (FULL && VEC) {
+                if constexpr (FULL && BCVEC) {
                     const float4 v = ldf4(b_s, b_voff[nb]);
                     f.b[nb][0] = v.x; f.b[nb][1] = v.y; f.b[nb][2] = v.z; f.b[nb][3] = v.w;
                 } else {
@@ -294,7 +305,7 @@ __global__ __launch_bounds__(256, NBW == 1 ? 4 : NBW == 2 ? 3 : 2) void gemm_dir
     }
     if (!active || kpart != 0) return;
     // accumulator register i of block nb is C[m0 + 4g + i][n0 + NBW*(lane % 16) + nb]
-    constexpr bool out_vec = NBW > 1 && VEC;
+    constexpr bool out_vec = NBW > 1 && BCVEC;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int64_t m = m0 + 4 * g + i;
@@ -327,18 +338,58 @@ __global__ __launch_bounds__(256, NBW == 1 ? 4 : NBW == 2 ? 3 : 2) void gemm_dir
     }
 }
 
+template <int LAYOUT, int NBW, bool AVEC, bool BCVEC>
+__global__ __launch_bounds__(256, NBW == 1 ? 4 : NBW == 2 ? 3 : 2) void gemm_direct_kernel(GemmArgs p, int ks) {
+    gemm_direct_body<LAYOUT, NBW, AVEC, BCVEC, false>(p, ks, nullptr);
+}
+
+template <int NBW, bool AVEC, bool BCVEC>
+__global__ __launch_bounds__(256, NBW == 1 ? 4 : NBW == 2 ? 3 : 2) void gemm_direct_conv_table_kernel(
+    GemmArgs p, int ks, DirectTaps host_taps) {
+    __shared__ uint32_t taps[kTapTable + 16];
+    for (int i = threadIdx.x; i < kTapTable + 16; i += 256) taps[i] = host_taps.off[i];
+    __syncthreads();
+    gemm_direct_body<1, NBW, AVEC, BCVEC, true>(p, ks, taps);
+}
+
+// a_vec / bc_vec: see the kernel.  The mixed case exists for the convolution only (three input
+// channels, aligned filter and output); elsewhere an unaligned A sends everything down the
+// one-float path.
 template <int LAYOUT>
-static int launch_direct_layout(GemmArgs a, int nbw, int ks, bool vec, hipStream_t s) {
+static int launch_direct_layout(GemmArgs a, int nbw, int ks, bool a_vec, bool bc_vec, hipStream_t s) {
     const int64_t row_groups = cdiv(cdiv(a.M, 16), 4 / ks);
     const int64_t col_groups = cdiv(a.N, 16 * nbw);
     if (row_groups * col_groups > kMaxGrid) return LG_ERR_UNSUPPORTED;
     a.tiles_m = (unsigned)row_groups;
     a.tiles_n = (unsigned)col_groups;
     const dim3 grid((unsigned)(row_groups * col_groups)), block(256);
-#define LG_DIRECT(NBW)                                                                                  \
-    do {                                                                                                \
-        if (vec) hipLaunchKernelGGL((gemm_direct_kernel<LAYOUT, NBW, true>), grid, block, 0, s, a, ks); \
-        else     hipLaunchKernelGGL((gemm_direct_kernel<LAYOUT, NBW, false>), grid, block, 0, s, a, ks); \
+    if constexpr (LAYOUT == 1) {
+        if (a.K <= kTapTable) {
+            DirectTaps taps{};
+            for (int64_t k = 0; k < a.K; ++k) {
+                const int64_t c = k % a.g.C, tap = k / a.g.C, kw = tap % a.g.KW, kh = tap / a.g.KW;
+                taps.off[k] = (uint32_t)(((kh * a.g.DH * a.g.W + kw * a.g.DW) * a.g.C + c) * 4);
+            }
+#define LG_DIRECT_TABLE(NBW)                                                                                                 \
+    do {                                                                                                                     \
+        if (a_vec && bc_vec) hipLaunchKernelGGL((gemm_direct_conv_table_kernel<NBW, true, true>), grid, block, 0, s, a, ks, taps);   \
+        else if (bc_vec)     hipLaunchKernelGGL((gemm_direct_conv_table_kernel<NBW, false, true>), grid, block, 0, s, a, ks, taps);  \
+        else                 hipLaunchKernelGGL((gemm_direct_conv_table_kernel<NBW, false, false>), grid, block, 0, s, a, ks, taps); \
+    } while (0)
+            switch (nbw) {
+                case 1: LG_DIRECT_TABLE(1); break;
+                case 2: LG_DIRECT_TABLE(2); break;
+                default: LG_DIRECT_TABLE(4); break;
+            }
+#undef LG_DIRECT_TABLE
+            return launch_status();
+        }
+    }
+    const bool all_vec = a_vec && bc_vec;
+#define LG_DIRECT(NBW)                                                                                              \
+    do {                                                                                                            \
+        if (all_vec) hipLaunchKernelGGL((gemm_direct_kernel<LAYOUT, NBW, true, true>), grid, block, 0, s, a, ks);   \
+        else         hipLaunchKernelGGL((gemm_direct_kernel<LAYOUT, NBW, false, false>), grid, block, 0, s, a, ks); \
     } while (0)
     switch (nbw) {
         case 1: LG_DIRECT(1); break;
@@ -362,16 +413,19 @@ bool direct_can_run(const GemmArgs& a, Layout layout) {
     return a_bytes < lim && b_bytes < lim && a.lda < ld_lim && a.ldb < ld_lim;
 }
 
-// `vec`: the caller's alignment verdict for the tiled kernel (all bases and pitches 16-byte aligned,
-// K and N multiples of 4, convolution: C a multiple of 4) holds for this kernel too.
-int launch_direct(const GemmArgs& a, Layout layout, int nbw, int ks, bool vec, hipStream_t s) {
+// Alignment verdicts, per operand (the tiled kernel's single verdict also wants K a multiple of 4,
+// which whole 16-deep chunks do not need).
+int launch_direct(const GemmArgs& a, Layout layout, int nbw, int ks, hipStream_t s) {
     if ((nbw != 1 && nbw != 2 && nbw != 4) || (ks != 1 && ks != 2 && ks != 4)) return LG_ERR_INVALID_ARG;
     if (!direct_can_run(a, layout)) return LG_ERR_UNSUPPORTED;
+    const bool c_ok = a.ldc % 4 == 0 && a.N % 4 == 0 && aligned16(a.C);
+    const bool a_row_ok = a.lda % 4 == 0 && aligned16(a.A);
+    const bool b_row_ok = a.ldb % 4 == 0 && aligned16(a.B);
     switch (layout) {
-        case Layout::NN: return launch_direct_layout<0>(a, nbw, ks, vec, s);
-        case Layout::CONV: return launch_direct_layout<1>(a, nbw, ks, vec, s);
-        case Layout::TN: return launch_direct_layout<2>(a, nbw, ks, vec, s);
-        default: return launch_direct_layout<3>(a, nbw, ks, vec, s);
+        case Layout::NN: return launch_direct_layout<0>(a, nbw, ks, a_row_ok, b_row_ok && c_ok, s);
+        case Layout::CONV: return launch_direct_layout<1>(a, nbw, ks, a.g.C % 4 == 0 && aligned16(a.A), b_row_ok && c_ok, s);
+        case Layout::TN: return launch_direct_layout<2>(a, nbw, ks, b_row_ok && c_ok, b_row_ok && c_ok, s);   // A is never fetched along k
+        default: return launch_direct_layout<3>(a, nbw, ks, a_row_ok, b_row_ok && c_ok, s);
     }
 }
 

@@ -813,7 +813,7 @@ static void launch_planned(const GemmArgs& a, const Plan& pl, bool vec, hipStrea
 enum class Layout { NN, CONV, TN, NT };
 
 // The register-direct kernel for small and skinny problems (gemm_direct.hip); returns an LG_* status.
-int launch_direct(const GemmArgs& a, Layout layout, int nbw, int ks, bool vec, hipStream_t s);
+int launch_direct(const GemmArgs& a, Layout layout, int nbw, int ks, hipStream_t s);
 bool direct_can_run(const GemmArgs& a, Layout layout);     // operands within its 32-bit offsets?
 
 // Implemented in gemm.hip (AB and convolution) and gemm_t.hip (A^T B, A B^T).

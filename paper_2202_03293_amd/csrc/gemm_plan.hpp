@@ -78,7 +78,7 @@ inline Plan make_plan(int64_t M, int64_t N, int64_t K) {
     // or when the contraction is one or two chunks deep (a 3x3 filter over three channels), where
     // the tiled kernel spends its time filling and draining its ring.
     const bool one_float = (K % 4 != 0) || (N % 4 != 0);
-    for (int nbw = 1; nbw <= (one_float ? 2 : 4); nbw *= 2) {
+    for (int nbw = 1; nbw <= ((N % 4 != 0) ? 2 : 4); nbw *= 2) {
         const int occ = nbw == 1 ? 4 : nbw == 2 ? 3 : 2;
         for (int ks = 1; ks <= 4; ks *= 2) {
             const int64_t groups = cdiv(cdiv(M, 16), 4 / ks) * cdiv(N, 16 * nbw);

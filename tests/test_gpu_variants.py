@@ -86,6 +86,10 @@ CONV_SHAPES = [
     (2, 9, 9, 7, 5, 5, 4, (1, 2), (1, 1), False),
     (1, 20, 20, 16, 16, 1, 1, (1, 1), (1, 1), True),      # 1x1, stride 1: runs as a plain matmul
     (2, 15, 15, 8, 24, 1, 1, (2, 2), (1, 1), False),      # 1x1, strided
+    # contractions past 512: the register-direct kernel walks the taps per lane instead of reading
+    # the host's table of tap offsets
+    (1, 9, 10, 64, 16, 3, 3, (1, 1), (1, 1), False),      # K = 576, aligned
+    (2, 8, 8, 63, 9, 3, 3, (1, 1), (1, 2), True),         # K = 567, nothing aligned
 ]
 
 
