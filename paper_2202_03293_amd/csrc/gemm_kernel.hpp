@@ -69,22 +69,6 @@ __device__ __forceinline__ int64_t to_scalar(int64_t v) {
     return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
-struct ConvGeom {        // implicit-GEMM A operand: row m -> (n, oh, ow), column k -> (kh, kw, c)
-    int64_t H, W, C, KW, SH, SW, DH, DW, OH, OW;
-};
-
-struct GemmArgs {
-    const float* A;      // AB, A B^T: M x K (row stride lda).  A^T B: K x M.  conv: NHWC input
-    const float* B;      // AB, A^T B: K x N (row stride ldb).  A B^T: N x K
-    float* C;            // M x N, row stride ldc (or split-k partials: slab z at C + z*M*ldc)
-    int64_t M, N, K;
-    int64_t lda, ldb, ldc;
-    int64_t k_per_split; // multiple of the tile's BK; slab z covers k in [z*k_per_split, min(K, (z+1)*k_per_split))
-    int accumulate;      // only honoured when the grid has one k-slab
-    unsigned tiles_m, tiles_n;
-    ConvGeom g;
-};
-
 // BM x BN output tile per workgroup, BK-deep k-slices, WM x WN register tile per wavefront.
 // MINW = wavefronts per SIMD the register allocation must leave room for (what LDS lets a CU hold).
 template <int BM_, int BN_, int BK_, int WM_, int WN_, int MINW_, int STAGES_ = 3, bool KTAIL_ = true>
@@ -809,12 +793,6 @@ static void launch_planned(const GemmArgs& a, const Plan& pl, bool vec, hipStrea
     }
 #undef LG_LAUNCH
 }
-
-enum class Layout { NN, CONV, TN, NT };
-
-// The register-direct kernel for small and skinny problems (gemm_direct.hip); returns an LG_* status.
-int launch_direct(const GemmArgs& a, Layout layout, int nbw, int ks, hipStream_t s);
-bool direct_can_run(const GemmArgs& a, Layout layout);     // operands within its 32-bit offsets?
 
 // Implemented in gemm.hip (AB and convolution) and gemm_t.hip (A^T B, A B^T).
 void launch_nn(const GemmArgs& a, const Plan& pl, bool vec, hipStream_t s);

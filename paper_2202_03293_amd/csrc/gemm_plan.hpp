@@ -1,10 +1,33 @@
-// Host side of the GEMM kernels: the table of compiled tiles (gemm_kernel.hpp instantiates them in
-// this order), the plan of one launch, and the cost model that picks tile, k-split or the
-// register-direct kernel (gemm_direct.hip) for a shape.  No device code here.
+// Host side of the GEMM kernels: the argument block both kernels take, the table of compiled tiles
+// (gemm_kernel.hpp instantiates them in this order), the plan of one launch, and the cost model that
+// picks tile, k-split or the register-direct kernel (gemm_direct.hip) for a shape.  No device code
+// here.
 #pragma once
 #include "lg_common.hpp"
 
 namespace lg {
+
+struct ConvGeom {        // implicit-GEMM A operand: row m -> (n, oh, ow), column k -> (kh, kw, c)
+    int64_t H, W, C, KW, SH, SW, DH, DW, OH, OW;
+};
+
+struct GemmArgs {
+    const float* A;      // AB, A B^T: M x K (row stride lda).  A^T B: K x M.  conv: NHWC input
+    const float* B;      // AB, A^T B: K x N (row stride ldb).  A B^T: N x K
+    float* C;            // M x N, row stride ldc (or split-k partials: slab z at C + z*M*ldc)
+    int64_t M, N, K;
+    int64_t lda, ldb, ldc;
+    int64_t k_per_split; // multiple of the tile's BK; slab z covers k in [z*k_per_split, min(K, (z+1)*k_per_split))
+    int accumulate;      // only honoured when the grid has one k-slab
+    unsigned tiles_m, tiles_n;
+    ConvGeom g;
+};
+
+enum class Layout { NN, CONV, TN, NT };
+
+// The register-direct kernel for small and skinny problems (gemm_direct.hip); returns an LG_* status.
+int launch_direct(const GemmArgs& a, Layout layout, int nbw, int ks, hipStream_t s);
+bool direct_can_run(const GemmArgs& a, Layout layout);     // operands within its 32-bit offsets?
 
 // One row per tile of gemm_kernel.hpp's menu.  `occ` = workgroups of that tile a CU can hold (LDS and
 // registers), `mfma` = matrix-pipe clocks one k-slice costs one SIMD, `eff` = the measured fraction
