@@ -10,7 +10,10 @@ constexpr int kCopyUnroll = 4;   // 128-bit accesses in flight per lane
 
 // out[i,j] = in[i,j].  VEC: rows are whole 128-bit words and everything is 16-byte aligned; the
 // stream is marked non-temporal on both sides (nothing is reused, keep it out of the caches).
-template <bool VEC>
+// FLAT: both sides are dense (row pitch = row length), so the matrix is one long row and no lane
+// has to divide its index by the row length (a 64-bit division costs more than the copy of a small
+// matrix).
+template <bool VEC, bool STREAM = true, bool FLAT = false>
 __global__ __launch_bounds__(kCopyThreads) void copy2d_kernel(
     const uint32_t* __restrict__ in, uint32_t* __restrict__ out,
     int64_t R, int64_t Cn, int64_t ld_in, int64_t ld_out) {
@@ -26,14 +29,18 @@ __global__ __launch_bounds__(kCopyThreads) void copy2d_kernel(
             const int64_t idx = base + (int64_t)u * kCopyThreads;
             dst[u] = -1;
             if (idx < total) {
-                const int64_t r = idx / per_row, c = idx - r * per_row;
-                v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(in + r * ld_in + 4 * c));
+                const int64_t r = FLAT ? 0 : idx / per_row, c = idx - r * per_row;
+                const u32x4* src = reinterpret_cast<const u32x4*>(in + r * ld_in + 4 * c);
+                if constexpr (STREAM) v[u] = __builtin_nontemporal_load(src); else v[u] = *src;
                 dst[u] = r * ld_out + 4 * c;
             }
         }
 #pragma unroll
         for (int u = 0; u < kCopyUnroll; ++u)
-            if (dst[u] >= 0) __builtin_nontemporal_store(v[u], reinterpret_cast<u32x4*>(out + dst[u]));
+            if (dst[u] >= 0) {
+                if constexpr (STREAM) __builtin_nontemporal_store(v[u], reinterpret_cast<u32x4*>(out + dst[u]));
+                else *reinterpret_cast<u32x4*>(out + dst[u]) = v[u];
+            }
     } else {
 #pragma unroll
         for (int u = 0; u < kCopyUnroll; ++u) {
@@ -167,18 +174,54 @@ extern "C" int lg_copy2d(const float* in, float* out, int64_t R, int64_t Cn,
     hipStream_t s = static_cast<hipStream_t>(stream);
     auto* i32 = reinterpret_cast<const uint32_t*>(in);
     auto* o32 = reinterpret_cast<uint32_t*>(out);
-    if (vec) hipLaunchKernelGGL(copy2d_kernel<true>, dim3((unsigned)blocks), dim3(kCopyThreads), 0, s, i32, o32, R, Cn, ld_in, ld_out);
-    else     hipLaunchKernelGGL(copy2d_kernel<false>, dim3((unsigned)blocks), dim3(kCopyThreads), 0, s, i32, o32, R, Cn, ld_in, ld_out);
+    // Past what the last-level cache holds nothing of the stream is worth keeping; a small copy is
+    // usually read again by the next kernel, and is faster itself through the caches.
+    const bool stream_hint = 2 * R * Cn * 4 > ((int64_t)200 << 20);      // 256 MB of last-level cache on this part
+    const bool flat = ld_in == Cn && ld_out == Cn;
+    if (vec && stream_hint && flat) hipLaunchKernelGGL((copy2d_kernel<true, true, true>), dim3((unsigned)blocks), dim3(kCopyThreads), 0, s, i32, o32, R, Cn, ld_in, ld_out);
+    else if (vec && stream_hint) hipLaunchKernelGGL((copy2d_kernel<true, true, false>), dim3((unsigned)blocks), dim3(kCopyThreads), 0, s, i32, o32, R, Cn, ld_in, ld_out);
+    else if (vec && flat) hipLaunchKernelGGL((copy2d_kernel<true, false, true>), dim3((unsigned)blocks), dim3(kCopyThreads), 0, s, i32, o32, R, Cn, ld_in, ld_out);
+    else if (vec) hipLaunchKernelGGL((copy2d_kernel<true, false, false>), dim3((unsigned)blocks), dim3(kCopyThreads), 0, s, i32, o32, R, Cn, ld_in, ld_out);
+    else     hipLaunchKernelGGL((copy2d_kernel<false, false>), dim3((unsigned)blocks), dim3(kCopyThreads), 0, s, i32, o32, R, Cn, ld_in, ld_out);
     return launch_status();
 }
 
 namespace lg {
+
+// Transpose of a matrix with very few rows or very few columns (a vector, three interleaved
+// channels): an LDS tile would be almost empty.  One element per lane, walking the side whose rows
+// are the short ones in memory order, so that the other side is a handful of contiguous streams.
+// BY_OUT: lanes enumerate the output (R small: out rows are R long); else the input (Cn small).
+template <bool BY_OUT>
+__global__ __launch_bounds__(256) void transpose_thin_kernel(
+    const uint32_t* __restrict__ in, uint32_t* __restrict__ out,
+    int64_t R, int64_t Cn, int64_t ld_in, int64_t ld_out) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= R * Cn) return;
+    const int64_t minor = BY_OUT ? R : Cn;
+    int64_t major, rem;
+    if (R * Cn < ((int64_t)1 << 32)) {             // 32-bit division when it fits: several times cheaper
+        const uint32_t q = (uint32_t)idx / (uint32_t)minor;
+        major = q; rem = (uint32_t)idx - q * (uint32_t)minor;
+    } else {
+        major = idx / minor; rem = idx - major * minor;
+    }
+    const int64_t i = BY_OUT ? rem : major, j = BY_OUT ? major : rem;
+    out[j * ld_out + i] = in[i * ld_in + j];
+}
 
 static int transpose_dispatch(const float* in, float* out, int64_t R, int64_t Cn, int64_t ld_in, int64_t ld_out,
                               int64_t B0, int64_t B1, BatchStrides bs, bool vec, void* stream) {
     hipStream_t s = static_cast<hipStream_t>(stream);
     auto* i32 = reinterpret_cast<const uint32_t*>(in);
     auto* o32 = reinterpret_cast<uint32_t*>(out);
+    if (B0 == 1 && B1 == 1 && (R < 16 || Cn < 16)) {
+        const int64_t blocks = cdiv(R * Cn, 256);
+        if (blocks > kMaxGrid) return LG_ERR_UNSUPPORTED;
+        if (R <= Cn) hipLaunchKernelGGL(transpose_thin_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, i32, o32, R, Cn, ld_in, ld_out);
+        else         hipLaunchKernelGGL(transpose_thin_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, i32, o32, R, Cn, ld_in, ld_out);
+        return launch_status();
+    }
     // 128x128 tiles once they still give every CU several workgroups, 64x64 below that
     const bool big = cdiv(R, 128) * cdiv(Cn, 128) * B0 * B1 >= 1024 && R >= 128 && Cn >= 128;
     if (vec && big) return launch_transpose<128, 1024, true>(i32, o32, R, Cn, ld_in, ld_out, B0, B1, bs, s);

@@ -543,7 +543,10 @@ def special_bits(shape, seed):
 
 
 @pytest.mark.parametrize("R,Cn", [(64, 64), (1, 1), (1, 19), (19, 1), (37, 53), (128, 256), (100, 260),
-                                  (250, 960), (1000, 1000), (1027, 765), (4, 4096), (4096, 4)])
+                                  (250, 960), (1000, 1000), (1027, 765), (4, 4096), (4096, 4),
+                                  # thin matrices: the one-element-per-lane kernel on both of its sides
+                                  (1, 100003), (100003, 1), (3, 70001), (70001, 3), (15, 257), (257, 15),
+                                  (16, 300), (300, 16)])
 def test_transpose_and_copy_bit_exact(lg, lgo, R, Cn):
     xb = special_bits((R, Cn), 140)
     x = xb.view(np.float32)
@@ -558,8 +561,8 @@ def test_transpose_and_copy_bit_exact(lg, lgo, R, Cn):
     assert np.array_equal(bits(cp.host()), bits(lgo.copy2d(x)))
 
 
-def test_transpose_copy_leading_dims(lg, lgo):
-    R, Cn = 130, 200
+@pytest.mark.parametrize("R,Cn", [(130, 200), (5, 999), (999, 5)])
+def test_transpose_copy_leading_dims(lg, lgo, R, Cn):
     xb = special_bits((R, Cn), 141)
     for pi, po in [(8, 4), (3, 5)]:
         xd = torch.zeros((R, Cn + pi), dtype=torch.int32, device="cuda").view(torch.float32)
