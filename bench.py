@@ -275,35 +275,48 @@ def main():
                                     "(+ one large conv 32x58x58x256->256 3x3), dwconv1d, dwconv2d; one launch of each per step"),
                frac_mfma_peak=value * 1e9 / MFMA_FP32_PEAK, roofline=roofline, ops=per_op)
 
-    # ------------------------------------------------------------------ the paper's small sweep
-    if args.sweep:
-        def per_launch_us(call, batch=20, reps=7):
-            """(eager, graph): microseconds per launch from batches of back-to-back launches, issued one
-            by one through the Python binding and replayed from a HIP graph of the same batch."""
+    # ------------------------------------------------------------------ launch-bound problems
+    def per_launch_us(call, batch=20, reps=7):
+        """(eager, graph): microseconds per launch from batches of back-to-back launches, issued one
+        by one through the Python binding and replayed from a HIP graph of the same batch."""
+        for _ in range(batch):
+            call()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
             for _ in range(batch):
                 call()
-            torch.cuda.synchronize()
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
-                for _ in range(batch):
-                    call()
 
-            def timed(run):
-                ts = []
-                for _ in range(reps):
-                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    a.record(stream)
-                    run()
-                    b.record(stream)
-                    torch.cuda.synchronize()
-                    ts.append(a.elapsed_time(b) * 1e3 / batch)
-                return float(np.median(ts))
+        def timed(run):
+            ts = []
+            for _ in range(reps):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record(stream)
+                run()
+                b.record(stream)
+                torch.cuda.synchronize()
+                ts.append(a.elapsed_time(b) * 1e3 / batch)
+            return float(np.median(ts))
 
-            def eager():
-                for _ in range(batch):
-                    call()
-            return timed(eager), timed(graph.replay)
+        def eager():
+            for _ in range(batch):
+                call()
+        return timed(eager), timed(graph.replay)
 
+    # configuration 0 is 34 MFLOP: inside the step above its figure is the cost of one launch issued
+    # from Python between two events.  Back to back, and replayed from a graph, it is the kernel's own
+    # latency on top of the dispatch floor (an empty-handed copy of one row, timed the same way).
+    sm_call = mm[si.MATMUL_SMALL]["call"]
+    sm_eager, sm_graph = per_launch_us(sm_call)
+    tiny_in, tiny_out = torch.zeros((1, 64), device="cuda"), torch.zeros((1, 64), device="cuda")
+    _, floor_graph = per_launch_us(lambda: lg.lg_copy2d(tiny_in, tiny_out))
+    out["small_matmul"] = dict(shape=list(si.MATMUL_SMALL), kernel=mm[si.MATMUL_SMALL]["kernel"],
+                               us_per_launch_eager=sm_eager, us_per_launch_graph=sm_graph,
+                               us_dispatch_floor_graph=floor_graph,
+                               gflops_graph=mm[si.MATMUL_SMALL]["flops"] / sm_graph / 1e3)
+
+    # ------------------------------------------------------------------ the paper's small sweep
+    if args.sweep:
         sweep = []
         for size in (16, 20, 32, 40, 55, 64, 128):
             for sd in ((1, 1), (2, 1), (1, 2), (2, 2)):
