@@ -111,3 +111,57 @@ def test_conv2d_every_variant(lg, lgo, variant, N, H, W, C, F, KH, KW, st, dl, a
         torch.cuda.synchronize()
         out.check()
         assert_close(out.host(), ref, KH * KW * C, f"variant {variant} splits {k_splits} conv {(N, H, W, C, F, KH, KW)}")
+
+
+def random_cases():
+    import random
+    rng = random.Random(1503)
+    mm, cv = [], []
+    for i in range(14):
+        M = rng.choice([1, 15, 16, 17, 63, 64, 100, 250])
+        N = rng.choice([1, 4, 15, 16, 31, 64, 65, 128, 200])
+        K = rng.choice([1, 4, 15, 16, 17, 48, 64, 100, 513, 700])
+        if i % 2 == 0:                                       # the aligned paths
+            N, K = 4 * ((N + 3) // 4), 4 * ((K + 3) // 4)
+        mm.append((M, N, K, ("nn", "tn", "nt")[i % 3], i % 4 == 1))
+    for i in range(10):
+        KH, KW = rng.choice([1, 2, 3]), rng.choice([1, 3, 5])
+        st = (rng.choice([1, 2]), rng.choice([1, 2, 3]))
+        dl = (rng.choice([1, 2]), rng.choice([1, 2]))
+        H = dl[0] * (KH - 1) + 1 + rng.randint(0, 9)
+        W = dl[1] * (KW - 1) + 1 + rng.randint(0, 12)
+        C = rng.choice([1, 3, 4, 8, 20, 36, 64])             # 64 x 3 x 5 = 960: past the tap table
+        F = rng.choice([1, 4, 6, 16, 40, 64])
+        cv.append((rng.randint(1, 3), H, W, C, F, KH, KW, st, dl, i % 3 == 2))
+    return mm, cv
+
+
+@pytest.mark.parametrize("M,N,K,layout,accumulate", random_cases()[0])
+def test_matmul_random_shapes_every_variant(lg, lgo, M, N, K, layout, accumulate):
+    A, B = si.matmul_inputs(1220 + M, M, N, K, case=K % 7)
+    C0 = si.uniform(1221, N, (M, N), -1, 1) if accumulate else None
+    ref = lgo.matmul(A, B, C0.copy(), accumulate=True) if accumulate else lgo.matmul(A, B)
+    Ad = dev(np.ascontiguousarray(A.T) if layout == "tn" else A)
+    Bd = dev(np.ascontiguousarray(B.T) if layout == "nt" else B)
+    for variant in range(N_VARIANTS):
+        out = Guarded((M, N), init=C0 if accumulate else np.full((M, N), np.nan, np.float32))
+        lg.lg_matmul_variant(Ad, Bd, out.t, variant, trans_a=layout == "tn", trans_b=layout == "nt", accumulate=accumulate)
+        torch.cuda.synchronize()
+        out.check()
+        assert_close(out.host(), ref, K, f"variant {variant} {layout} {(M, N, K)}")
+
+
+@pytest.mark.parametrize("N,H,W,C,F,KH,KW,st,dl,accumulate", random_cases()[1])
+def test_conv2d_random_shapes_every_variant(lg, lgo, N, H, W, C, F, KH, KW, st, dl, accumulate):
+    I, Kf = si.conv2d_inputs(1230 + C, N, H, W, C, F, KH, KW)
+    OH, OW = lg.lg_conv_out_extent(H, KH, st[0], dl[0]), lg.lg_conv_out_extent(W, KW, st[1], dl[1])
+    O0 = si.uniform(1231, F, (N, OH, OW, F), -1, 1) if accumulate else None
+    ref = lgo.conv2d_nhwc_hwcf(I, Kf, O0.copy(), stride=st, dilation=dl, accumulate=True) if accumulate \
+        else lgo.conv2d_nhwc_hwcf(I, Kf, stride=st, dilation=dl)
+    Id, Kd = dev(I), dev(Kf)
+    for variant in range(N_VARIANTS):
+        out = Guarded((N, OH, OW, F), init=O0 if accumulate else np.full((N, OH, OW, F), np.nan, np.float32))
+        lg.lg_conv2d_nhwc_hwcf_variant(Id, Kd, out.t, variant, stride=st, dilation=dl, accumulate=accumulate)
+        torch.cuda.synchronize()
+        out.check()
+        assert_close(out.host(), ref, KH * KW * C, f"variant {variant} conv {(N, H, W, C, F, KH, KW, st, dl)}")
