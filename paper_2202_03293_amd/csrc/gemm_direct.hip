@@ -37,11 +37,28 @@ struct DirectFrag {
 // (0, 0), channel 0 as a table from the host (through the kernel arguments into LDS) instead of
 // walking (kh, kw, c) per lane: the walk starts with integer divisions, which at three channels
 // cost more instructions than the loads and multiplies of the whole block.
+// Division of a row index (< 2^31) by an extent known on the host: q = (m * magic) >> shift, exact
+// for shift = 31 + ceil(log2 d), magic = floor(2^shift / d) + 1 (the error term m / 2^shift stays
+// below 1/d).  Two multiplies instead of the ~40 instructions of a 32-bit integer division.
+struct FastDiv { uint32_t magic, shift; };
+struct ConvDiv { FastDiv ow, oh; };                            // row m -> (n, oh, ow)
+inline FastDiv make_fastdiv(int64_t d) {
+    uint32_t L = 0;
+    while (((int64_t)1 << L) < d) ++L;
+    const uint32_t shift = 31 + L;
+    const uint64_t magic = (uint64_t)(((__uint128_t)1 << shift) / (uint64_t)d) + 1;
+    return FastDiv{(uint32_t)magic, magic <= 0xFFFFFFFFull ? shift : 0u};   // shift 0: no magic fits, divide
+}
+__device__ __forceinline__ uint32_t fastdiv(uint32_t m, const FastDiv& f, uint32_t d) {
+    return f.shift ? (uint32_t)(((uint64_t)m * f.magic) >> f.shift) : m / d;
+}
+
 constexpr int kTapTable = 512;
 struct DirectTaps { uint32_t off[kTapTable + 16]; };          // + one chunk of zeros for lanes past K
 
 template <int LAYOUT, int NBW, bool AVEC, bool BCVEC, bool TABLE>
-__device__ __forceinline__ void gemm_direct_body(const GemmArgs& p, int ks, const uint32_t* taps) {
+__device__ __forceinline__ void gemm_direct_body(const GemmArgs& p, int ks, const uint32_t* taps, const ConvDiv& dv,
+                                                 unsigned bid) {
     constexpr bool CONV = LAYOUT == 1, TA = LAYOUT == 2, TB = LAYOUT == 3;
     static_assert(!TABLE || CONV, "the tap table belongs to the convolution");
     constexpr int PD = (BCVEC || NBW == 1) ? 4 : 2;             // k chunks per register set (one-float loads take an offset register each)
@@ -51,7 +68,7 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& p, int ks, cons
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
     const int r = lane % 16, g = lane / 16;
     const int kpart = wave % ks, rsub = wave / ks;
-    const int64_t rg = blockIdx.x / p.tiles_n, cg = blockIdx.x % p.tiles_n;
+    const int64_t rg = bid / p.tiles_n, cg = bid % p.tiles_n;
     const int64_t m0 = (rg * (4 / ks) + rsub) * 16;
     const int64_t n0 = cg * (16 * NBW);
     const bool active = m0 < p.M;                              // wave-uniform
@@ -89,8 +106,8 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& p, int ks, cons
     uint32_t b_voff[TB ? NBW : 4];
     if constexpr (CONV) {
         const uint32_t mu = (uint32_t)mrow, OWu = (uint32_t)p.g.OW, OHu = (uint32_t)p.g.OH;
-        const uint32_t q = mu / OWu;
-        const int64_t ow = mu - q * OWu, n = q / OHu, oh = q - (uint32_t)n * OHu;
+        const uint32_t q = fastdiv(mu, dv.ow, OWu);
+        const int64_t ow = mu - q * OWu, n = fastdiv(q, dv.oh, OHu), oh = q - (uint32_t)n * OHu;
         a_voff[0] = (uint32_t)((((n * p.g.H + oh * p.g.SH) * p.g.W + ow * p.g.SW) * p.g.C) * 4);   // tap (0, 0), channel 0
         a_step = 0;
     } else if constexpr (TA) {
@@ -338,18 +355,37 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& p, int ks, cons
     }
 }
 
-template <int LAYOUT, int NBW, bool AVEC, bool BCVEC>
-__global__ __launch_bounds__(256, NBW == 1 ? 4 : NBW == 2 ? 3 : 2) void gemm_direct_kernel(GemmArgs p, int ks) {
-    gemm_direct_body<LAYOUT, NBW, AVEC, BCVEC, false>(p, ks, nullptr);
+// LOOP: the grid is a fixed number of workgroups that stride over the blocks (many rounds of
+// blocks: the start-up -- and the convolution's table -- are paid once per workgroup instead of
+// once per block); otherwise one workgroup per group of blocks.
+template <int LAYOUT, int NBW, bool AVEC, bool BCVEC, bool LOOP = false>
+__global__ __launch_bounds__(256, NBW == 1 ? 4 : NBW == 2 ? 3 : 2) void gemm_direct_kernel(GemmArgs p, int ks, ConvDiv dv) {
+    if constexpr (LOOP) {
+        const unsigned nblocks = p.tiles_m * p.tiles_n;
+        for (unsigned bid = blockIdx.x; bid < nblocks; bid += gridDim.x) {
+            gemm_direct_body<LAYOUT, NBW, AVEC, BCVEC, false>(p, ks, nullptr, dv, bid);
+            if (ks > 1) __syncthreads();           // the next block reuses the LDS of the k-part sums
+        }
+    } else {
+        gemm_direct_body<LAYOUT, NBW, AVEC, BCVEC, false>(p, ks, nullptr, dv, blockIdx.x);
+    }
 }
 
-template <int NBW, bool AVEC, bool BCVEC>
+template <int NBW, bool AVEC, bool BCVEC, bool LOOP>
 __global__ __launch_bounds__(256, NBW == 1 ? 4 : NBW == 2 ? 3 : 2) void gemm_direct_conv_table_kernel(
-    GemmArgs p, int ks, DirectTaps host_taps) {
+    GemmArgs p, int ks, ConvDiv dv, DirectTaps host_taps) {
     __shared__ uint32_t taps[kTapTable + 16];
     for (int i = threadIdx.x; i < kTapTable + 16; i += 256) taps[i] = host_taps.off[i];
     __syncthreads();
-    gemm_direct_body<1, NBW, AVEC, BCVEC, true>(p, ks, taps);
+    if constexpr (LOOP) {
+        const unsigned nblocks = p.tiles_m * p.tiles_n;
+        for (unsigned bid = blockIdx.x; bid < nblocks; bid += gridDim.x) {
+            gemm_direct_body<1, NBW, AVEC, BCVEC, true>(p, ks, taps, dv, bid);
+            if (ks > 1) __syncthreads();           // the next block reuses the LDS of the k-part sums
+        }
+    } else {
+        gemm_direct_body<1, NBW, AVEC, BCVEC, true>(p, ks, taps, dv, blockIdx.x);
+    }
 }
 
 // a_vec / bc_vec: see the kernel.  The mixed case exists for the convolution only (three input
@@ -362,7 +398,10 @@ static int launch_direct_layout(GemmArgs a, int nbw, int ks, bool a_vec, bool bc
     if (row_groups * col_groups > kMaxGrid) return LG_ERR_UNSUPPORTED;
     a.tiles_m = (unsigned)row_groups;
     a.tiles_n = (unsigned)col_groups;
-    const dim3 grid((unsigned)(row_groups * col_groups)), block(256);
+    const int64_t nblocks = row_groups * col_groups;
+    const dim3 grid((unsigned)nblocks), block(256);
+    ConvDiv dv{};
+    if constexpr (LAYOUT == 1) dv = ConvDiv{make_fastdiv(a.g.OW), make_fastdiv(a.g.OH)};
     if constexpr (LAYOUT == 1) {
         if (a.K <= kTapTable) {
             DirectTaps taps{};
@@ -370,11 +409,19 @@ static int launch_direct_layout(GemmArgs a, int nbw, int ks, bool a_vec, bool bc
                 const int64_t c = k % a.g.C, tap = k / a.g.C, kw = tap % a.g.KW, kh = tap / a.g.KW;
                 taps.off[k] = (uint32_t)(((kh * a.g.DH * a.g.W + kw * a.g.DW) * a.g.C + c) * 4);
             }
+            // many rounds of blocks (and aligned filter/output, the case this is for): as many
+            // workgroups as the chip holds at once -- 4 / 3 / 2 per SIMD by the register budget --
+            // each striding over the blocks
+            const int64_t resident = (int64_t)kCUs * (nbw == 1 ? 4 : nbw == 2 ? 3 : 2);
+            const bool loop = bc_vec && nblocks > 4 * resident;
+            const dim3 lgrid((unsigned)resident);
 #define LG_DIRECT_TABLE(NBW)                                                                                                 \
     do {                                                                                                                     \
-        if (a_vec && bc_vec) hipLaunchKernelGGL((gemm_direct_conv_table_kernel<NBW, true, true>), grid, block, 0, s, a, ks, taps);   \
-        else if (bc_vec)     hipLaunchKernelGGL((gemm_direct_conv_table_kernel<NBW, false, true>), grid, block, 0, s, a, ks, taps);  \
-        else                 hipLaunchKernelGGL((gemm_direct_conv_table_kernel<NBW, false, false>), grid, block, 0, s, a, ks, taps); \
+        if (loop && a_vec)   hipLaunchKernelGGL((gemm_direct_conv_table_kernel<NBW, true, true, true>), lgrid, block, 0, s, a, ks, dv, taps);   \
+        else if (loop)       hipLaunchKernelGGL((gemm_direct_conv_table_kernel<NBW, false, true, true>), lgrid, block, 0, s, a, ks, dv, taps);  \
+        else if (a_vec && bc_vec) hipLaunchKernelGGL((gemm_direct_conv_table_kernel<NBW, true, true, false>), grid, block, 0, s, a, ks, dv, taps);   \
+        else if (bc_vec)     hipLaunchKernelGGL((gemm_direct_conv_table_kernel<NBW, false, true, false>), grid, block, 0, s, a, ks, dv, taps);  \
+        else                 hipLaunchKernelGGL((gemm_direct_conv_table_kernel<NBW, false, false, false>), grid, block, 0, s, a, ks, dv, taps); \
     } while (0)
             switch (nbw) {
                 case 1: LG_DIRECT_TABLE(1); break;
@@ -386,10 +433,30 @@ static int launch_direct_layout(GemmArgs a, int nbw, int ks, bool a_vec, bool bc
         }
     }
     const bool all_vec = a_vec && bc_vec;
+    if constexpr (LAYOUT == 0) {
+        // AB with aligned B and C over many rounds of blocks (a tall matrix times a small one): the
+        // striding grid, and the mixed case of an A whose rows are not 16-byte aligned
+        const int64_t resident = (int64_t)kCUs * (nbw == 1 ? 4 : nbw == 2 ? 3 : 2);
+        if (bc_vec && nblocks > 4 * resident) {
+            const dim3 lgrid((unsigned)resident);
+#define LG_DIRECT_LOOP(NBW)                                                                                                  \
+    do {                                                                                                                     \
+        if (a_vec) hipLaunchKernelGGL((gemm_direct_kernel<0, NBW, true, true, true>), lgrid, block, 0, s, a, ks, dv);        \
+        else       hipLaunchKernelGGL((gemm_direct_kernel<0, NBW, false, true, true>), lgrid, block, 0, s, a, ks, dv);       \
+    } while (0)
+            switch (nbw) {
+                case 1: LG_DIRECT_LOOP(1); break;
+                case 2: LG_DIRECT_LOOP(2); break;
+                default: LG_DIRECT_LOOP(4); break;
+            }
+#undef LG_DIRECT_LOOP
+            return launch_status();
+        }
+    }
 #define LG_DIRECT(NBW)                                                                                              \
     do {                                                                                                            \
-        if (all_vec) hipLaunchKernelGGL((gemm_direct_kernel<LAYOUT, NBW, true, true>), grid, block, 0, s, a, ks);   \
-        else         hipLaunchKernelGGL((gemm_direct_kernel<LAYOUT, NBW, false, false>), grid, block, 0, s, a, ks); \
+        if (all_vec) hipLaunchKernelGGL((gemm_direct_kernel<LAYOUT, NBW, true, true>), grid, block, 0, s, a, ks, dv);   \
+        else         hipLaunchKernelGGL((gemm_direct_kernel<LAYOUT, NBW, false, false>), grid, block, 0, s, a, ks, dv); \
     } while (0)
     switch (nbw) {
         case 1: LG_DIRECT(1); break;

@@ -116,6 +116,11 @@ inline Plan make_plan(int64_t M, int64_t N, int64_t K) {
             double cost = chain > pipe ? chain : pipe;
             const double cache_rate = waves <= 4 * kCUs ? 15e12 : 9e12;
             if (bytes / cache_rate > cost) cost = bytes / cache_rate;
+            // A contraction of one or two chunks over many rounds of blocks (a first-layer convolution):
+            // what a block costs is its own latency chain -- row set-up, one round trip for its
+            // operands, the stores -- spread over the wavefronts a SIMD holds: measured 0.5 / 0.9 us
+            // per wavefront and SIMD for nbw = 1 / 2.
+            if (K <= 32 && waves > 16 * kCUs) cost = waves / (4.0 * kCUs) * (0.25e-6 + 0.33e-6 * nbw);
             cost += 6.9e-6 + (ks > 1 ? 0.3e-6 : 0.0);
             if (cost < best_cost) {
                 best_cost = cost;
