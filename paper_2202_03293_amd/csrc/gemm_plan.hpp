@@ -97,9 +97,9 @@ inline Plan make_plan(int64_t M, int64_t N, int64_t K) {
     // another and contend for them) and the output costs the same; against
     // the tiled kernel's launch constant above it starts 1.1 us ahead (no staging ring to fill, no
     // barriers, a short epilogue).  Extents that rule out 16-byte accesses (K or N not a multiple
-    // of 4) leave only the one-float path, which is worth it for a single round of small blocks,
-    // or when the contraction is one or two chunks deep (a 3x3 filter over three channels), where
-    // the tiled kernel spends its time filling and draining its ring.
+    // of 4) leave only the one-float path for A, which is worth it for a single round of small
+    // blocks, or when the contraction is a few chunks deep (a filter over three channels), where the
+    // tiled kernel spends its time filling and draining its ring.
     const bool one_float = (K % 4 != 0) || (N % 4 != 0);
     for (int nbw = 1; nbw <= ((N % 4 != 0) ? 2 : 4); nbw *= 2) {
         const int occ = nbw == 1 ? 4 : nbw == 2 ? 3 : 2;
@@ -107,7 +107,9 @@ inline Plan make_plan(int64_t M, int64_t N, int64_t K) {
             const int64_t groups = cdiv(cdiv(M, 16), 4 / ks) * cdiv(N, 16 * nbw);
             if (groups > kMaxGrid) continue;
             const double waves = (double)cdiv(M, 16) * (double)cdiv(N, 16 * nbw) * ks;
-            if (one_float && waves > 4 * kCUs && K > 32) continue;
+            if (one_float && waves > 4 * kCUs && (K > 128 || (K > 32 && waves <= 16 * kCUs))) continue;
+            if (one_float && nbw == 4 && waves <= 16 * kCUs) continue;   // measured only over many rounds
+            if (one_float && ks > 1 && waves > 4 * kCUs) continue;       // k parts are for filling an idle chip
             const double chunks = (double)cdiv(cdiv(K, 16), ks);
             const double per_simd = (double)cdiv((int64_t)waves, 4 * kCUs);
             const double chain = chunks * (0.05e-6 + 0.07e-6 * nbw) * (one_float ? 1.7 : 1.0) * (double)cdiv((int64_t)per_simd, occ);
@@ -116,11 +118,13 @@ inline Plan make_plan(int64_t M, int64_t N, int64_t K) {
             double cost = chain > pipe ? chain : pipe;
             const double cache_rate = waves <= 4 * kCUs ? 15e12 : 9e12;
             if (bytes / cache_rate > cost) cost = bytes / cache_rate;
-            // A contraction of one or two chunks over many rounds of blocks (a first-layer convolution):
-            // what a block costs is its own latency chain -- row set-up, one round trip for its
-            // operands, the stores -- spread over the wavefronts a SIMD holds: measured 0.5 / 0.9 us
-            // per wavefront and SIMD for nbw = 1 / 2.
-            if (K <= 32 && waves > 16 * kCUs) cost = waves / (4.0 * kCUs) * (0.25e-6 + 0.33e-6 * nbw);
+            // A shallow contraction with an unaligned A over many rounds of blocks (a convolution over
+            // three channels): what a block costs is its own latency chain -- row set-up, a round trip
+            // for its operands, one-float loads, the stores -- spread over the wavefronts a SIMD
+            // holds: measured 0.26 / 0.36 / 0.56 us per wavefront, SIMD and k chunk for nbw = 1 / 2 / 4
+            // (K = 27 ... 147, 12 000 ... 100 000 blocks).
+            if (one_float && waves > 16 * kCUs)
+                cost = waves / (4.0 * kCUs) * (double)cdiv(K, 16) * (0.16e-6 + 0.10e-6 * nbw);
             cost += 6.9e-6 + (ks > 1 ? 0.3e-6 : 0.0);
             if (cost < best_cost) {
                 best_cost = cost;
