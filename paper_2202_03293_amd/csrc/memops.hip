@@ -195,9 +195,11 @@ namespace lg {
 template <bool BY_OUT>
 __global__ __launch_bounds__(256) void transpose_thin_kernel(
     const uint32_t* __restrict__ in, uint32_t* __restrict__ out,
-    int64_t R, int64_t Cn, int64_t ld_in, int64_t ld_out) {
+    int64_t R, int64_t Cn, int64_t ld_in, int64_t ld_out, BatchStrides bs) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= R * Cn) return;
+    in += (int64_t)blockIdx.z * bs.in0 + (int64_t)blockIdx.y * bs.in1;      // batch (b0, b1) = (z, y)
+    out += (int64_t)blockIdx.z * bs.out0 + (int64_t)blockIdx.y * bs.out1;
     const int64_t minor = BY_OUT ? R : Cn;
     int64_t major, rem;
     if (R * Cn < ((int64_t)1 << 32)) {             // 32-bit division when it fits: several times cheaper
@@ -215,11 +217,12 @@ static int transpose_dispatch(const float* in, float* out, int64_t R, int64_t Cn
     hipStream_t s = static_cast<hipStream_t>(stream);
     auto* i32 = reinterpret_cast<const uint32_t*>(in);
     auto* o32 = reinterpret_cast<uint32_t*>(out);
-    if (B0 == 1 && B1 == 1 && (R < 16 || Cn < 16)) {
+    if (R < 16 || Cn < 16) {                       // e.g. NHWC <-> NCHW with three channels, as a batch over N
         const int64_t blocks = cdiv(R * Cn, 256);
-        if (blocks > kMaxGrid) return LG_ERR_UNSUPPORTED;
-        if (R <= Cn) hipLaunchKernelGGL(transpose_thin_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, i32, o32, R, Cn, ld_in, ld_out);
-        else         hipLaunchKernelGGL(transpose_thin_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, i32, o32, R, Cn, ld_in, ld_out);
+        if (blocks > kMaxGrid || B0 > 65535 || B1 > 65535) return LG_ERR_UNSUPPORTED;
+        const dim3 grid((unsigned)blocks, (unsigned)B1, (unsigned)B0);
+        if (R <= Cn) hipLaunchKernelGGL(transpose_thin_kernel<true>, grid, dim3(256), 0, s, i32, o32, R, Cn, ld_in, ld_out, bs);
+        else         hipLaunchKernelGGL(transpose_thin_kernel<false>, grid, dim3(256), 0, s, i32, o32, R, Cn, ld_in, ld_out, bs);
         return launch_status();
     }
     // 128x128 tiles once they still give every CU several workgroups, 64x64 below that

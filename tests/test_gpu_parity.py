@@ -602,6 +602,18 @@ def test_transpose_batched_4d_paper_permutation(lg, lgo, dims):
     assert np.array_equal(got, np.transpose(xb, (2, 1, 3, 0)))
 
 
+@pytest.mark.parametrize("N,H,W,C", [(5, 17, 19, 3), (2, 40, 33, 1), (3, 9, 8, 15)])
+def test_transpose_batched_few_channels(lg, lgo, N, H, W, C):
+    # NHWC -> NCHW and back with a handful of channels: per image a (H*W) x C matrix, too thin for LDS tiles
+    xb = special_bits((N, H, W, C), 144)
+    nchw = run_transpose_batched(lg, lgo, xb, (N, C, H, W), H * W, C, C, H * W, N, 1,
+                                 (H * W * C, 0), (C * H * W, 0))
+    assert np.array_equal(nchw, np.transpose(xb, (0, 3, 1, 2)))
+    back = run_transpose_batched(lg, lgo, nchw, (N, H, W, C), C, H * W, H * W, C, N, 1,
+                                 (C * H * W, 0), (H * W * C, 0))
+    assert np.array_equal(back, xb)
+
+
 def test_transpose_batched_3d_padded_and_empty(lg, lgo):
     # [b,i,j] -> [b,j,i] with padded rows on both sides: the padding keeps its fill pattern
     B, R, Cn, pi, po = 7, 50, 36, 3, 5
