@@ -4,8 +4,9 @@
 // Register-window kernels (filter widths 3, 5, 7 in 1-D, 3x3 in 2-D; strides and dilations 1 and 2,
 // the values the paper sweeps): a lane owns 4 adjacent channels (one 128-bit access) and a few output
 // positions, keeps the input window in registers so each input element is loaded once per lane, and
-// neighbouring lanes/workgroups share the halo through L2.  General kernels cover any other
-// stride, dilation, filter size and channel count, one output position per lane.
+// neighbouring lanes/workgroups share the halo through L2.  A row-streaming kernel covers the other
+// filter widths up to 9 at horizontal stride and dilation 1 (5x5, 7x7); general kernels cover any
+// other stride, dilation, filter size and channel count, one output position per lane.
 #include "lg_common.hpp"
 
 namespace lg {
@@ -157,6 +158,62 @@ __global__ __launch_bounds__(kDThreads) void dwconv2d_win_kernel(
         }
 }
 
+// Row-streaming kernel for the filters the window kernels do not cover (5x5, 7x7, 1-D widths
+// 2 ... 9): horizontal stride and dilation 1, C % 4 == 0, any filter height, vertical stride and
+// dilation.  A lane owns a run of TW outputs of one output row for 4 channels and walks the filter
+// rows: per filter row it loads the TW + KW - 1 input positions its run touches and the KW taps,
+// then does TW * KW multiply-adds -- (TW + 2*KW - 1) / TW loads per output and filter row instead of
+// the 2*KW of one output per lane.  Vertical reuse (neighbouring output rows read the same input
+// rows) is left to the caches.
+template <int KW, int TW>
+__global__ __launch_bounds__(kDThreads) void dwconv_rows_kernel(
+    const float* __restrict__ I, const float* __restrict__ Kf, float* __restrict__ O,
+    int64_t N, int64_t H, int64_t W, int64_t C, int64_t KH, int64_t SH, int64_t DH,
+    int64_t OH, int64_t OW, int accumulate) {
+    const int64_t C4 = C / 4, runs = (OW + TW - 1) / TW;
+    const int64_t total = N * OH * runs * C4;
+    const int64_t idx = (int64_t)blockIdx.x * kDThreads + threadIdx.x;
+    if (idx >= total) return;
+    const int64_t c4 = idx % C4;
+    const int64_t run = (idx / C4) % runs;
+    const int64_t oh = (idx / (C4 * runs)) % OH;
+    const int64_t n = idx / (C4 * runs * OH);
+    const int64_t w0 = run * TW;
+    const int nw = OW - w0 < TW ? (int)(OW - w0) : TW;
+    const float* ip = I + ((n * H + oh * SH) * W + w0) * C + 4 * c4;
+    float4 acc[TW];
+#pragma unroll
+    for (int o = 0; o < TW; ++o) acc[o] = make_float4(0, 0, 0, 0);
+    for (int64_t a = 0; a < KH; ++a) {
+        const float* row = ip + a * DH * W * C;
+        float4 x[TW + KW - 1], k[KW];
+#pragma unroll
+        for (int c = 0; c < TW + KW - 1; ++c) {
+            x[c] = make_float4(0, 0, 0, 0);
+            if (c < nw + KW - 1) x[c] = *reinterpret_cast<const float4*>(row + (int64_t)c * C);
+        }
+#pragma unroll
+        for (int b = 0; b < KW; ++b) k[b] = *reinterpret_cast<const float4*>(Kf + (a * KW + b) * C + 4 * c4);
+#pragma unroll
+        for (int o = 0; o < TW; ++o)
+#pragma unroll
+            for (int b = 0; b < KW; ++b) acc[o] = fma4(x[o + b], k[b], acc[o]);
+    }
+    float* op = O + ((n * OH + oh) * OW + w0) * C + 4 * c4;
+#pragma unroll
+    for (int o = 0; o < TW; ++o) {
+        if (o < nw) {
+            float* q = op + (int64_t)o * C;
+            float4 s = acc[o];
+            if (accumulate) {
+                const float4 old = *reinterpret_cast<const float4*>(q);
+                s.x += old.x; s.y += old.y; s.z += old.z; s.w += old.w;
+            }
+            store_stream4(q, s);
+        }
+    }
+}
+
 // General depthwise kernel (1-D is H = KH = 1): one output element per lane, channels fastest.
 __global__ __launch_bounds__(kDThreads) void dwconv_general_kernel(
     const float* __restrict__ I, const float* __restrict__ Kf, float* __restrict__ O,
@@ -255,6 +312,25 @@ static int dwconv_dispatch(const float* I, const float* Kf, float* O,
         // patch sizes: small enough that the problem fills 256 CUs and the patch fits in registers
         LG_DW2(1, 1, 4, 2) LG_DW2(2, 1, 2, 2) LG_DW2(1, 2, 4, 2) LG_DW2(2, 2, 4, 2)
 #undef LG_DW2
+    }
+    // (with few channels a wavefront's lanes would sit a whole run of pixels apart: left to the general
+    // kernel, whose lanes are adjacent outputs)
+    if (vec && SW == 1 && DW == 1 && KW >= 2 && KW <= 9 && C >= 64) {
+        // long runs once they still leave every SIMD a few wavefronts, short ones below that
+        const bool long_runs = N * OH * cdiv(OW, 8) * (C / 4) >= (int64_t)kDThreads * 256 * 4;
+        const int64_t items = N * OH * cdiv(OW, long_runs ? 8 : 4) * (C / 4);
+        const int64_t blocks = cdiv(items, kDThreads);
+        if (blocks > kMaxGrid) return LG_ERR_UNSUPPORTED;
+#define LG_DWR(K_)                                                                                            \
+        if (KW == K_) {                                                                                      \
+            if (long_runs) hipLaunchKernelGGL((dwconv_rows_kernel<K_, 8>), dim3((unsigned)blocks), dim3(kDThreads), 0, s, \
+                                              I, Kf, O, N, H, W, C, KH, SH, DH, OH, OW, accumulate);        \
+            else           hipLaunchKernelGGL((dwconv_rows_kernel<K_, 4>), dim3((unsigned)blocks), dim3(kDThreads), 0, s, \
+                                              I, Kf, O, N, H, W, C, KH, SH, DH, OH, OW, accumulate);        \
+            return launch_status();                                                                          \
+        }
+        LG_DWR(2) LG_DWR(3) LG_DWR(4) LG_DWR(5) LG_DWR(6) LG_DWR(7) LG_DWR(8) LG_DWR(9)
+#undef LG_DWR
     }
     if (vec) {
         const int64_t blocks4 = cdiv(out_elems / 4, kDThreads);

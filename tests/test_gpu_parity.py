@@ -423,6 +423,24 @@ def test_dwconv2d_window_kernels(lg, lgo, s, d):
         assert_close(run_dw2(lg, I, Kf, (s, s), (d, d), O0=O0, accumulate=True), ref2, 9, "dwconv2d window accumulate")
 
 
+# the row-streaming kernel: filter widths 2 ... 9 at horizontal stride and dilation 1, any height,
+# vertical stride and dilation; short runs (small problems) and long runs, ragged last run, accumulate
+@pytest.mark.parametrize("N,H,W,C,KH,KW,sh,dh", [
+    (2, 20, 23, 64, 5, 5, 1, 1), (1, 16, 19, 96, 7, 7, 1, 1), (2, 9, 40, 64, 1, 9, 1, 1), (3, 14, 11, 68, 2, 4, 2, 1),
+    (2, 17, 13, 128, 3, 6, 1, 2), (1, 12, 9, 64, 4, 8, 3, 3), (2, 8, 10, 72, 3, 2, 1, 1), (1, 7, 7, 64, 7, 7, 1, 1),
+    (8, 70, 70, 256, 7, 7, 1, 1), (4, 64, 133, 128, 5, 5, 2, 1),
+    # fewer than 64 channels: the general kernel takes these
+    (2, 20, 23, 8, 5, 5, 1, 1), (1, 12, 9, 60, 4, 8, 3, 3)])
+def test_dwconv_row_streaming_kernel(lg, lgo, N, H, W, C, KH, KW, sh, dh):
+    I, Kf = si.dwconv2d_inputs(139 + KW, N, H, W, C, KH, KW)
+    ref = lgo.dwconv2d_nhwc_hwc(I, Kf, stride=(sh, 1), dilation=(dh, 1))
+    assert_close(run_dw2(lg, I, Kf, (sh, 1), (dh, 1)), ref, KH * KW, f"dwconv rows {(N, H, W, C, KH, KW, sh, dh)}")
+    if N * H * W * C < 400000:
+        O0 = si.uniform(139, KW, ref.shape, -1, 1)
+        ref2 = O0.copy(); lgo.dwconv2d_nhwc_hwc(I, Kf, ref2, stride=(sh, 1), dilation=(dh, 1), accumulate=True)
+        assert_close(run_dw2(lg, I, Kf, (sh, 1), (dh, 1), O0=O0, accumulate=True), ref2, KH * KW, "dwconv rows accumulate")
+
+
 # the 2-D depthwise sizes of Section 4.7: batch-1 MobileNet layers (output extent x channels), each
 # at strides and dilations 1 and 2
 @pytest.mark.parametrize("size,C", [(112, 32), (112, 64), (56, 128), (28, 256), (14, 512), (7, 1024)])
