@@ -200,9 +200,20 @@ int lg_dwconv2d_nhwc_hwc(const float *I, const float *Kf, float *O,
  * vectors from the workspace.  lg_reduce_rows gives every row one workgroup (one
  * wavefront when Cn < 4096) and needs no workspace; it fills the GPU once R is in
  * the hundreds, while a handful of very long rows occupy only as many compute units.
+ * lg_reduce_rows_ws is the same operation with a workspace: when there are fewer
+ * than 512 rows of at least 32768 elements it cuts every row into pieces, one
+ * workgroup each, and adds the piece sums in a second pass (in ascending order of
+ * position: the result does not depend on timing).  lg_reduce_rows_workspace_bytes
+ * says how much it needs for a shape (0: it runs exactly as lg_reduce_rows and
+ * workspace may be NULL); the workspace is device memory, 256-byte aligned, owned
+ * by the caller, free for reuse once the call's work on the stream has finished;
+ * missing, misaligned or too small is LG_ERR_WORKSPACE.
  */
 int lg_reduce_rows(const float *in, float *out, int64_t R, int64_t Cn, int64_t ld,
                    int accumulate, void *stream);
+int lg_reduce_rows_ws(const float *in, float *out, int64_t R, int64_t Cn, int64_t ld,
+                      int accumulate, void *workspace, size_t workspace_bytes, void *stream);
+size_t lg_reduce_rows_workspace_bytes(int64_t R, int64_t Cn);
 int lg_reduce_cols(const float *in, float *out, int64_t R, int64_t Cn, int64_t ld,
                    int accumulate, void *workspace, size_t workspace_bytes, void *stream);
 size_t lg_reduce_cols_workspace_bytes(int64_t R, int64_t Cn);

@@ -21,10 +21,14 @@ __device__ __forceinline__ float4 load_stream4(const float* p) {
 // out[i] = sum_j in[i,j].  One workgroup per row when rows are long (WG_PER_ROW), one wavefront
 // per row otherwise.  Each lane owns 128-bit columns strided by the group width; four loads are
 // in flight per lane before the adds.
+// With P > 1 a "row" is one of P segments of a row of the matrix: R counts segments, segment
+// v = (r, q) starts at in + r*ld + q*Cn and is Cn long except the last of a row, which ends at
+// Ctot (long rows cut into pieces so that a handful of them fills the chip; the piece sums are
+// added by a second pass over the R/P x P matrix of partial sums).
 template <bool VEC, bool WG_PER_ROW>
 __global__ __launch_bounds__(kRThreads) void reduce_rows_kernel(
     const float* __restrict__ in, float* __restrict__ out,
-    int64_t R, int64_t Cn, int64_t ld, int accumulate) {
+    int64_t R, int64_t Cn, int64_t ld, int accumulate, int64_t P, int64_t Ctot) {
     __shared__ float part[kRWaves];
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
     const int64_t row = WG_PER_ROW ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * kRWaves + wave;
@@ -33,6 +37,11 @@ __global__ __launch_bounds__(kRThreads) void reduce_rows_kernel(
     float s = 0.f;
     if (row < R) {
         const float* p = in + row * ld;
+        if (P > 1) {
+            const int64_t r = row / P, q = row - r * P;
+            p = in + r * ld + q * Cn;
+            if (Ctot - q * Cn < Cn) Cn = Ctot - q * Cn;
+        }
         if constexpr (VEC) {
             const int64_t n4 = Cn / 4;
             float4 a0 = make_float4(0, 0, 0, 0), a1 = a0, a2 = a0, a3 = a0;
@@ -322,6 +331,60 @@ static ColPlan plan_cols(int64_t R, int64_t Cn) {
 
 }  // namespace lg
 
+namespace lg {
+
+// How lg_reduce_rows_ws cuts long rows: P pieces per row, each `len` long (a multiple of 1024
+// floats, one pass of a workgroup's 128-bit accesses), once the rows alone cannot fill the chip.
+struct RowPlan { int64_t P, len; };
+static RowPlan plan_rows(int64_t R, int64_t Cn) {
+    RowPlan pl{1, Cn};
+    if (R >= 512 || Cn < 32768) return pl;                     // enough rows, or rows too short to cut
+    int64_t P = 2048 / R;                                      // ~8 workgroups per CU in all
+    if (P > Cn / 8192) P = Cn / 8192;                          // pieces of at least 8192 floats
+    if (P < 2) return pl;
+    pl.len = cdiv(cdiv(Cn, P), 1024) * 1024;
+    pl.P = cdiv(Cn, pl.len);
+    if (pl.P < 2) return RowPlan{1, Cn};
+    return pl;
+}
+
+static int reduce_rows_impl(const float* in, float* out, int64_t R, int64_t Cn, int64_t ld,
+                            int accumulate, hipStream_t s);
+
+}  // namespace lg
+
+extern "C" size_t lg_reduce_rows_workspace_bytes(int64_t R, int64_t Cn) {
+    using namespace lg;
+    if (R <= 0 || Cn <= 0) return 0;
+    const RowPlan pl = plan_rows(R, Cn);
+    return pl.P > 1 ? (size_t)(R * pl.P) * sizeof(float) : 0;
+}
+
+extern "C" int lg_reduce_rows_ws(const float* in, float* out, int64_t R, int64_t Cn, int64_t ld,
+                                 int accumulate, void* workspace, size_t workspace_bytes, void* stream) {
+    using namespace lg;
+    if (R < 0 || Cn < 0 || ld < Cn) return LG_ERR_INVALID_ARG;
+    if (R == 0) return LG_OK;
+    if (!out || (Cn > 0 && !in)) return LG_ERR_INVALID_ARG;
+    if (Cn > 0 && overlaps(in, ((R - 1) * ld + Cn) * 4, out, R * 4)) return LG_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const RowPlan pl = plan_rows(R, Cn);
+    if (pl.P <= 1) return reduce_rows_impl(in, out, R, Cn, ld, accumulate, s);
+    const size_t need = (size_t)(R * pl.P) * sizeof(float);
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return LG_ERR_WORKSPACE;
+    if (overlaps(workspace, (int64_t)need, out, R * 4) ||
+        overlaps(workspace, (int64_t)need, in, ((R - 1) * ld + Cn) * 4))
+        return LG_ERR_INVALID_ARG;
+    float* partial = static_cast<float*>(workspace);
+    const bool vec = (Cn % 4 == 0) && (ld % 4 == 0) && aligned16(in);
+    const dim3 g((unsigned)(R * pl.P)), b(kRThreads);          // R < 512 and P <= 2048 / R
+    if (vec) hipLaunchKernelGGL((reduce_rows_kernel<true, true>), g, b, 0, s, in, partial, R * pl.P, pl.len, ld, 0, pl.P, Cn);
+    else     hipLaunchKernelGGL((reduce_rows_kernel<false, true>), g, b, 0, s, in, partial, R * pl.P, pl.len, ld, 0, pl.P, Cn);
+    if (launch_status() != LG_OK) return LG_ERR_RUNTIME;
+    return reduce_rows_impl(partial, out, R, pl.P, pl.P, accumulate, s);
+}
+
 extern "C" int lg_reduce_rows(const float* in, float* out, int64_t R, int64_t Cn, int64_t ld,
                               int accumulate, void* stream) {
     using namespace lg;
@@ -329,7 +392,13 @@ extern "C" int lg_reduce_rows(const float* in, float* out, int64_t R, int64_t Cn
     if (R == 0) return LG_OK;
     if (!out || (Cn > 0 && !in)) return LG_ERR_INVALID_ARG;
     if (Cn > 0 && overlaps(in, ((R - 1) * ld + Cn) * 4, out, R * 4)) return LG_ERR_INVALID_ARG;
-    hipStream_t s = static_cast<hipStream_t>(stream);
+    return reduce_rows_impl(in, out, R, Cn, ld, accumulate, static_cast<hipStream_t>(stream));
+}
+
+namespace lg {
+
+static int reduce_rows_impl(const float* in, float* out, int64_t R, int64_t Cn, int64_t ld,
+                            int accumulate, hipStream_t s) {
     const bool vec = Cn > 0 && (Cn % 4 == 0) && (ld % 4 == 0) && aligned16(in);
     const int64_t accesses = vec ? Cn / 4 : Cn;     // per row
     if (accesses >= 1 && accesses <= kWave) {
@@ -346,12 +415,14 @@ extern "C" int lg_reduce_rows(const float* in, float* out, int64_t R, int64_t Cn
     const int64_t blocks = wg_per_row ? R : cdiv(R, kRWaves);
     if (blocks > kMaxGrid) return LG_ERR_UNSUPPORTED;
     const dim3 g((unsigned)blocks), b(kRThreads);
-    if (vec && wg_per_row)       hipLaunchKernelGGL((reduce_rows_kernel<true, true>), g, b, 0, s, in, out, R, Cn, ld, accumulate);
-    else if (vec)                hipLaunchKernelGGL((reduce_rows_kernel<true, false>), g, b, 0, s, in, out, R, Cn, ld, accumulate);
-    else if (wg_per_row)         hipLaunchKernelGGL((reduce_rows_kernel<false, true>), g, b, 0, s, in, out, R, Cn, ld, accumulate);
-    else                         hipLaunchKernelGGL((reduce_rows_kernel<false, false>), g, b, 0, s, in, out, R, Cn, ld, accumulate);
+    if (vec && wg_per_row)       hipLaunchKernelGGL((reduce_rows_kernel<true, true>), g, b, 0, s, in, out, R, Cn, ld, accumulate, (int64_t)1, Cn);
+    else if (vec)                hipLaunchKernelGGL((reduce_rows_kernel<true, false>), g, b, 0, s, in, out, R, Cn, ld, accumulate, (int64_t)1, Cn);
+    else if (wg_per_row)         hipLaunchKernelGGL((reduce_rows_kernel<false, true>), g, b, 0, s, in, out, R, Cn, ld, accumulate, (int64_t)1, Cn);
+    else                         hipLaunchKernelGGL((reduce_rows_kernel<false, false>), g, b, 0, s, in, out, R, Cn, ld, accumulate, (int64_t)1, Cn);
     return launch_status();
 }
+
+}  // namespace lg
 
 extern "C" size_t lg_reduce_cols_workspace_bytes(int64_t R, int64_t Cn) {
     using namespace lg;

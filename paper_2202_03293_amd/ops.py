@@ -32,6 +32,8 @@ _SIGNATURES = {
     "lg_dwconv1d_nwc_wc": (_int, [_vp, _vp, _vp] + [_i64] * 6 + [_int, _vp]),
     "lg_dwconv2d_nhwc_hwc": (_int, [_vp, _vp, _vp] + [_i64] * 10 + [_int, _vp]),
     "lg_reduce_rows": (_int, [_vp, _vp] + [_i64] * 3 + [_int, _vp]),
+    "lg_reduce_rows_ws": (_int, [_vp, _vp] + [_i64] * 3 + [_int, _vp, _sz, _vp]),
+    "lg_reduce_rows_workspace_bytes": (_sz, [_i64] * 2),
     "lg_reduce_cols": (_int, [_vp, _vp] + [_i64] * 3 + [_int, _vp, _sz, _vp]),
     "lg_reduce_cols_workspace_bytes": (_sz, [_i64] * 2),
     "lg_transpose": (_int, [_vp, _vp] + [_i64] * 4 + [_vp]),
@@ -294,6 +296,21 @@ def lg_reduce_rows(x, out, accumulate=False, stream=None):
         raise ValueError("out must be a dense vector with one entry per row")
     _check("lg_reduce_rows", lib().lg_reduce_rows(_ptr(x), _ptr(out), R, Cn, _ld(x), int(accumulate),
                                                   _stream(stream)))
+    return out
+
+
+def lg_reduce_rows_workspace_bytes(R, Cn):
+    return lib().lg_reduce_rows_workspace_bytes(R, Cn)
+
+
+def lg_reduce_rows_ws(x, out, accumulate=False, workspace=None, stream=None):
+    """lg_reduce_rows with a workspace, which lets a handful of very long rows use the whole GPU."""
+    R, Cn = x.shape
+    if tuple(out.shape) != (R,) or not out.is_contiguous():
+        raise ValueError("out must be a dense vector with one entry per row")
+    wp, wb = _ws(workspace)
+    _check("lg_reduce_rows_ws", lib().lg_reduce_rows_ws(_ptr(x), _ptr(out), R, Cn, _ld(x), int(accumulate),
+                                                        wp, wb, _stream(stream)))
     return out
 
 

@@ -542,6 +542,35 @@ def test_reductions_all_ones_accumulate_ld_and_empty(lg, lgo):
     assert np.all(e.cpu().numpy() == 0)
 
 
+# a handful of very long rows: lg_reduce_rows_ws cuts them into pieces (one workgroup each) and adds
+# the piece sums in a second pass; ragged last piece, unaligned, padded rows, accumulate
+@pytest.mark.parametrize("R,Cn,pad", [(1, 1000000, 0), (3, 333333, 0), (7, 200004, 4), (2, 32768, 0), (100, 70000, 0),
+                                      (511, 40000, 8), (5, 32767, 0), (512, 40000, 0), (1, 9000, 0)])
+def test_reduce_rows_with_workspace(lg, lgo, R, Cn, pad):
+    x = si.uniform(150 + R, 0, (R, Cn), 0, 1)
+    need = lg.lg_reduce_rows_workspace_bytes(R, Cn)
+    assert (need > 0) == (R < 512 and Cn >= 32768)
+    xd = torch.full((R, Cn + pad), float("nan"), device="cuda")
+    xd[:, :Cn] = dev(x)
+    ref = lgo.reduce_rows(x)
+    out = Guarded((R,))
+    lg.lg_reduce_rows_ws(xd[:, :Cn], out.t, workspace=workspace(need)); sync(); out.check()
+    assert_close(out.host(), ref, Cn, f"reduce_rows_ws {R}x{Cn}")
+    o0 = si.uniform(151, R, (R,), -1, 1)
+    acc = Guarded((R,), init=o0)
+    lg.lg_reduce_rows_ws(xd[:, :Cn], acc.t, accumulate=True, workspace=workspace(need)); sync(); acc.check()
+    assert_close(acc.host(), ref + o0, Cn, f"reduce_rows_ws accumulate {R}x{Cn}")
+    again = Guarded((R,))
+    lg.lg_reduce_rows_ws(xd[:, :Cn], again.t, workspace=workspace(need)); sync()
+    assert np.array_equal(bits(again.host()), bits(out.host()))              # same pieces, same order
+    if need:
+        with pytest.raises(lg.LgError) as e:
+            lg.lg_reduce_rows_ws(xd[:, :Cn], out.t)
+        assert e.value.status == -3
+        with pytest.raises(lg.LgError):
+            lg.lg_reduce_rows_ws(xd[:, :Cn], out.t, workspace=workspace(need - 4))
+
+
 def test_reductions_full_size(lg, lgo):
     x = si.uniform(1, 0, si.REDUCE_SHAPE, 0, 1)
     assert_close(run_rows(lg, x), lgo.reduce_rows(x), x.shape[1], "reduce_rows full")
