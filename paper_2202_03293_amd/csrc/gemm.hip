@@ -100,6 +100,11 @@ static int run_gemm(const GemmArgs& a, Layout layout, bool vec, int user_accumul
                     size_t workspace_bytes, hipStream_t s, int variant = -1, int k_splits = 1) {
     Plan pl{};
     if (variant < 0) {
+        if (gemv_applies(a, layout)) {
+            GemmArgs g = a;
+            g.accumulate = user_accumulate;
+            return launch_gemv(g, layout, s);
+        }
         pl = make_plan(a.M, a.N, a.K);
         // the planner knows extents, not pitches: operands padded past the direct kernel's reach
         // run on the smallest tile, unsplit (which needs no workspace either)

@@ -29,6 +29,10 @@ enum class Layout { NN, CONV, TN, NT };
 int launch_direct(const GemmArgs& a, Layout layout, int nbw, int ks, hipStream_t s);
 bool direct_can_run(const GemmArgs& a, Layout layout);     // operands within its 32-bit offsets?
 
+// Matrix times one to four vectors (gemv.hip): a weighted row reduction, no MFMA.
+bool gemv_applies(const GemmArgs& a, Layout layout);
+int launch_gemv(const GemmArgs& a, Layout layout, hipStream_t s);
+
 // One row per tile of gemm_kernel.hpp's menu.  `occ` = workgroups of that tile a CU can hold (LDS and
 // registers), `mfma` = matrix-pipe clocks one k-slice costs one SIMD, `eff` = the measured fraction
 // of the matrix-pipe rate the tile sustains with a full CU (clock-normalised), `dead` = clocks per

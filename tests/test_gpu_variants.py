@@ -165,3 +165,33 @@ def test_conv2d_random_shapes_every_variant(lg, lgo, N, H, W, C, F, KH, KW, st, 
         torch.cuda.synchronize()
         out.check()
         assert_close(out.host(), ref, KH * KW * C, f"variant {variant} conv {(N, H, W, C, F, KH, KW, st, dl)}")
+
+
+# matrix times one to four vectors: the planner's entry points send these to the weighted
+# row-reduction kernel (AB and A B^T); A^T B and shapes below its thresholds take the MFMA kernels
+@pytest.mark.parametrize("M,N,K,layout,accumulate,padded", [
+    (1024, 1, 1024, "nn", False, False), (2000, 3, 1501, "nn", True, False), (1500, 4, 2048, "nt", False, False),
+    (1031, 2, 4096, "nt", True, True), (4096, 1, 1030, "nn", False, True), (1024, 4, 1024, "tn", False, False),
+    (1023, 1, 5000, "nn", False, False), (3000, 2, 1000, "nn", False, False)])
+def test_matrix_times_few_vectors(lg, lgo, M, N, K, layout, accumulate, padded):
+    A, B = si.matmul_inputs(1240 + N, M, N, K, case=K % 7)
+    C0 = si.uniform(1241, N, (M, N), -1, 1) if accumulate else None
+    ref = lgo.matmul(A, B, C0.copy(), accumulate=True) if accumulate else lgo.matmul(A, B)
+    As = np.ascontiguousarray(A.T) if layout == "tn" else A
+    Bs = np.ascontiguousarray(B.T) if layout == "nt" else B
+    pad = 4 if padded else 0
+
+    def padded_dev(x):
+        if not pad:
+            return dev(x)
+        full = torch.full((x.shape[0], x.shape[1] + pad), float("nan"), device="cuda")
+        full[:, :x.shape[1]] = dev(x)
+        return full[:, :x.shape[1]]
+
+    out = Guarded((M, N), init=C0 if accumulate else np.full((M, N), np.nan, np.float32))
+    ws = workspace(lg.lg_matmul_workspace_bytes(M, N, K))
+    lg.lg_matmul_t(padded_dev(As), padded_dev(Bs), out.t, trans_a=layout == "tn", trans_b=layout == "nt",
+                   accumulate=accumulate, workspace=ws)
+    torch.cuda.synchronize()
+    out.check()
+    assert_close(out.host(), ref, K, f"{layout} {(M, N, K)}")
