@@ -1,6 +1,6 @@
 // Matrix times a few vectors: C[M, N] (+)= A[M, K] B for N <= 4 (AB, and A B^T with B stored N x K).
-// The paper counts the reductions "associated with matrix-vector products" among its
-// bandwidth-bound kernels (Section 4.4); with one to four output columns a matmul is exactly that:
+// The paper names matrix-vector products as where its bandwidth-bound reductions come from
+// (Section 4.4); with one to four output columns a matmul is exactly that:
 // every element of A is used N times, so the op is a weighted row reduction bound by the read of A.
 // MFMA blocks would leave 15 of 16 columns empty and, worse, fetch A in 64-byte pieces.
 //
