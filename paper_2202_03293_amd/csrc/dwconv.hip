@@ -165,51 +165,69 @@ __global__ __launch_bounds__(kDThreads) void dwconv2d_win_kernel(
 // then does TW * KW multiply-adds -- (TW + 2*KW - 1) / TW loads per output and filter row instead of
 // the 2*KW of one output per lane.  Vertical reuse (neighbouring output rows read the same input
 // rows) is left to the caches.
-template <int KW, int TW>
+// V = 4: a lane owns 4 adjacent channels (128-bit accesses; C % 4 == 0, 16-byte aligned tensors);
+// V = 1: one channel per lane, for channel counts and alignments that rule those out.
+template <int V> struct ChanVec;
+template <> struct ChanVec<4> {
+    float4 v;
+    __device__ static __forceinline__ ChanVec zero() { return {make_float4(0, 0, 0, 0)}; }
+    __device__ static __forceinline__ ChanVec load(const float* p) { return {*reinterpret_cast<const float4*>(p)}; }
+    __device__ __forceinline__ void fma(const ChanVec& a, const ChanVec& b) { v = fma4(a.v, b.v, v); }
+    __device__ __forceinline__ void add(const ChanVec& a) { v.x += a.v.x; v.y += a.v.y; v.z += a.v.z; v.w += a.v.w; }
+    __device__ __forceinline__ void store(float* p) const { store_stream4(p, v); }
+};
+template <> struct ChanVec<1> {
+    float v;
+    __device__ static __forceinline__ ChanVec zero() { return {0.f}; }
+    __device__ static __forceinline__ ChanVec load(const float* p) { return {*p}; }
+    __device__ __forceinline__ void fma(const ChanVec& a, const ChanVec& b) { v = fmaf(a.v, b.v, v); }
+    __device__ __forceinline__ void add(const ChanVec& a) { v += a.v; }
+    __device__ __forceinline__ void store(float* p) const { __builtin_nontemporal_store(v, p); }
+};
+
+template <int KW, int TW, int V>
 __global__ __launch_bounds__(kDThreads) void dwconv_rows_kernel(
     const float* __restrict__ I, const float* __restrict__ Kf, float* __restrict__ O,
     int64_t N, int64_t H, int64_t W, int64_t C, int64_t KH, int64_t SH, int64_t DH,
     int64_t OH, int64_t OW, int accumulate) {
-    const int64_t C4 = C / 4, runs = (OW + TW - 1) / TW;
-    const int64_t total = N * OH * runs * C4;
+    using CV = ChanVec<V>;
+    const int64_t CG = C / V, runs = (OW + TW - 1) / TW;       // channel groups of V
+    const int64_t total = N * OH * runs * CG;
     const int64_t idx = (int64_t)blockIdx.x * kDThreads + threadIdx.x;
     if (idx >= total) return;
-    const int64_t c4 = idx % C4;
-    const int64_t run = (idx / C4) % runs;
-    const int64_t oh = (idx / (C4 * runs)) % OH;
-    const int64_t n = idx / (C4 * runs * OH);
+    const int64_t cg = idx % CG;
+    const int64_t run = (idx / CG) % runs;
+    const int64_t oh = (idx / (CG * runs)) % OH;
+    const int64_t n = idx / (CG * runs * OH);
     const int64_t w0 = run * TW;
     const int nw = OW - w0 < TW ? (int)(OW - w0) : TW;
-    const float* ip = I + ((n * H + oh * SH) * W + w0) * C + 4 * c4;
-    float4 acc[TW];
+    const float* ip = I + ((n * H + oh * SH) * W + w0) * C + V * cg;
+    CV acc[TW];
 #pragma unroll
-    for (int o = 0; o < TW; ++o) acc[o] = make_float4(0, 0, 0, 0);
+    for (int o = 0; o < TW; ++o) acc[o] = CV::zero();
     for (int64_t a = 0; a < KH; ++a) {
         const float* row = ip + a * DH * W * C;
-        float4 x[TW + KW - 1], k[KW];
+        CV x[TW + KW - 1], k[KW];
 #pragma unroll
         for (int c = 0; c < TW + KW - 1; ++c) {
-            x[c] = make_float4(0, 0, 0, 0);
-            if (c < nw + KW - 1) x[c] = *reinterpret_cast<const float4*>(row + (int64_t)c * C);
+            x[c] = CV::zero();
+            if (c < nw + KW - 1) x[c] = CV::load(row + (int64_t)c * C);
         }
 #pragma unroll
-        for (int b = 0; b < KW; ++b) k[b] = *reinterpret_cast<const float4*>(Kf + (a * KW + b) * C + 4 * c4);
+        for (int b = 0; b < KW; ++b) k[b] = CV::load(Kf + (a * KW + b) * C + V * cg);
 #pragma unroll
         for (int o = 0; o < TW; ++o)
 #pragma unroll
-            for (int b = 0; b < KW; ++b) acc[o] = fma4(x[o + b], k[b], acc[o]);
+            for (int b = 0; b < KW; ++b) acc[o].fma(x[o + b], k[b]);
     }
-    float* op = O + ((n * OH + oh) * OW + w0) * C + 4 * c4;
+    float* op = O + ((n * OH + oh) * OW + w0) * C + V * cg;
 #pragma unroll
     for (int o = 0; o < TW; ++o) {
         if (o < nw) {
             float* q = op + (int64_t)o * C;
-            float4 s = acc[o];
-            if (accumulate) {
-                const float4 old = *reinterpret_cast<const float4*>(q);
-                s.x += old.x; s.y += old.y; s.z += old.z; s.w += old.w;
-            }
-            store_stream4(q, s);
+            CV s = acc[o];
+            if (accumulate) s.add(CV::load(q));
+            s.store(q);
         }
     }
 }
@@ -314,23 +332,28 @@ static int dwconv_dispatch(const float* I, const float* Kf, float* O,
 #undef LG_DW2
     }
     // (with few channels a wavefront's lanes would sit a whole run of pixels apart: left to the general
-    // kernel, whose lanes are adjacent outputs)
-    if (vec && SW == 1 && DW == 1 && KW >= 2 && KW <= 9 && C >= 64) {
+    // kernels, whose lanes are adjacent outputs)
+    if (SW == 1 && DW == 1 && KW >= 2 && KW <= 9 && C >= 64) {
         // long runs once they still leave every SIMD a few wavefronts, short ones below that
-        const bool long_runs = N * OH * cdiv(OW, 8) * (C / 4) >= (int64_t)kDThreads * 256 * 4;
-        const int64_t items = N * OH * cdiv(OW, long_runs ? 8 : 4) * (C / 4);
+        const int64_t CG = vec ? C / 4 : C;
+        const bool long_runs = N * OH * cdiv(OW, 8) * CG >= (int64_t)kDThreads * 256 * 4;
+        const int64_t items = N * OH * cdiv(OW, long_runs ? 8 : 4) * CG;
         const int64_t blocks = cdiv(items, kDThreads);
         if (blocks > kMaxGrid) return LG_ERR_UNSUPPORTED;
+#define LG_DWR2(K_, T_, V_)                                                                                  \
+        hipLaunchKernelGGL((dwconv_rows_kernel<K_, T_, V_>), dim3((unsigned)blocks), dim3(kDThreads), 0, s,   \
+                           I, Kf, O, N, H, W, C, KH, SH, DH, OH, OW, accumulate)
 #define LG_DWR(K_)                                                                                            \
         if (KW == K_) {                                                                                      \
-            if (long_runs) hipLaunchKernelGGL((dwconv_rows_kernel<K_, 8>), dim3((unsigned)blocks), dim3(kDThreads), 0, s, \
-                                              I, Kf, O, N, H, W, C, KH, SH, DH, OH, OW, accumulate);        \
-            else           hipLaunchKernelGGL((dwconv_rows_kernel<K_, 4>), dim3((unsigned)blocks), dim3(kDThreads), 0, s, \
-                                              I, Kf, O, N, H, W, C, KH, SH, DH, OH, OW, accumulate);        \
+            if (vec && long_runs) LG_DWR2(K_, 8, 4);                                                         \
+            else if (vec)         LG_DWR2(K_, 4, 4);                                                         \
+            else if (long_runs)   LG_DWR2(K_, 8, 1);                                                         \
+            else                  LG_DWR2(K_, 4, 1);                                                         \
             return launch_status();                                                                          \
         }
         LG_DWR(2) LG_DWR(3) LG_DWR(4) LG_DWR(5) LG_DWR(6) LG_DWR(7) LG_DWR(8) LG_DWR(9)
 #undef LG_DWR
+#undef LG_DWR2
     }
     if (vec) {
         const int64_t blocks4 = cdiv(out_elems / 4, kDThreads);

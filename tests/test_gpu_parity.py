@@ -429,6 +429,9 @@ def test_dwconv2d_window_kernels(lg, lgo, s, d):
     (2, 20, 23, 64, 5, 5, 1, 1), (1, 16, 19, 96, 7, 7, 1, 1), (2, 9, 40, 64, 1, 9, 1, 1), (3, 14, 11, 68, 2, 4, 2, 1),
     (2, 17, 13, 128, 3, 6, 1, 2), (1, 12, 9, 64, 4, 8, 3, 3), (2, 8, 10, 72, 3, 2, 1, 1), (1, 7, 7, 64, 7, 7, 1, 1),
     (8, 70, 70, 256, 7, 7, 1, 1), (4, 64, 133, 128, 5, 5, 2, 1),
+    # channel counts that are not a multiple of 4: one channel per lane
+    (2, 20, 23, 65, 3, 3, 1, 1), (1, 16, 19, 97, 7, 7, 1, 1), (3, 1, 300, 130, 1, 5, 1, 1), (2, 9, 33, 67, 3, 3, 2, 2),
+    (4, 70, 140, 255, 3, 3, 1, 1),
     # fewer than 64 channels: the general kernel takes these
     (2, 20, 23, 8, 5, 5, 1, 1), (1, 12, 9, 60, 4, 8, 3, 3)])
 def test_dwconv_row_streaming_kernel(lg, lgo, N, H, W, C, KH, KW, sh, dh):
