@@ -164,14 +164,24 @@ extern "C" int lg_copy2d(const float* in, float* out, int64_t R, int64_t Cn,
     if (R == 0 || Cn == 0) return LG_OK;
     if (!in || !out) return LG_ERR_INVALID_ARG;
     if (overlaps(in, ((R - 1) * ld_in + Cn) * 4, out, ((R - 1) * ld_out + Cn) * 4)) return LG_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
     if (ld_in == Cn && ld_out == Cn) {   // dense: one long row
         Cn *= R; R = 1; ld_in = ld_out = Cn;
+        // a long dense array whose length is not a multiple of 4: the 128-bit body, then the last 1-3 floats
+        if (Cn % 4 != 0 && Cn >= (1 << 20) && aligned16(in) && aligned16(out)) {
+            const int64_t body = Cn - Cn % 4;
+            const int rc = lg_copy2d(in, out, 1, body, body, body, stream);
+            if (rc != LG_OK) return rc;
+            hipLaunchKernelGGL((lg::copy2d_kernel<false, false>), dim3(1), dim3(lg::kCopyThreads), 0, s,
+                               reinterpret_cast<const uint32_t*>(in + body), reinterpret_cast<uint32_t*>(out + body),
+                               (int64_t)1, Cn - body, Cn - body, Cn - body);
+            return lg::launch_status();
+        }
     }
     const bool vec = (Cn % 4 == 0) && (ld_in % 4 == 0) && (ld_out % 4 == 0) && aligned16(in) && aligned16(out);
     const int64_t items = vec ? R * (Cn / 4) : R * Cn;
     const int64_t blocks = cdiv(items, kCopyThreads * kCopyUnroll);
     if (blocks > kMaxGrid) return LG_ERR_UNSUPPORTED;
-    hipStream_t s = static_cast<hipStream_t>(stream);
     auto* i32 = reinterpret_cast<const uint32_t*>(in);
     auto* o32 = reinterpret_cast<uint32_t*>(out);
     // Past what the last-level cache holds nothing of the stream is worth keeping; a small copy is

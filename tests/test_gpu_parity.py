@@ -596,7 +596,9 @@ def special_bits(shape, seed):
                                   (250, 960), (1000, 1000), (1027, 765), (4, 4096), (4096, 4),
                                   # thin matrices: the one-element-per-lane kernel on both of its sides
                                   (1, 100003), (100003, 1), (3, 70001), (70001, 3), (15, 257), (257, 15),
-                                  (16, 300), (300, 16)])
+                                  (16, 300), (300, 16),
+                                  # dense, more than 2^20 elements, not a multiple of 4: 128-bit body + scalar tail copy
+                                  (1025, 1031), (1, 1048579)])
 def test_transpose_and_copy_bit_exact(lg, lgo, R, Cn):
     xb = special_bits((R, Cn), 140)
     x = xb.view(np.float32)
