@@ -55,6 +55,56 @@ def measured_traffic(kernel_name):
                 total_bytes=TRAFFIC["fetch_bytes"] + TRAFFIC["write_bytes"])
 
 
+class ClockSampler:
+    """Samples the GPU's current engine and memory clocks (the starred line of the driver's
+    pp_dpm_sclk / pp_dpm_mclk tables) from a thread while the timed region runs; reports nothing
+    when the files are not there or not readable."""
+
+    def __init__(self, period_s=0.02):
+        import glob
+        self.files = {k: sorted(glob.glob(f"/sys/class/drm/card*/device/pp_dpm_{k}"))[:1] for k in ("sclk", "mclk")}
+        self.samples = {"sclk": [], "mclk": []}
+        self.period_s = period_s
+        self._stop = False
+        self._thread = None
+
+    def _read(self, kind):
+        for path in self.files[kind]:
+            try:
+                with open(path) as f:
+                    for line in f:
+                        if line.rstrip().endswith("*"):
+                            return float(line.split(":")[1].strip().split("M")[0])
+            except (OSError, ValueError, IndexError):
+                return None
+        return None
+
+    def _loop(self):
+        while not self._stop:
+            for kind in ("sclk", "mclk"):
+                v = self._read(kind)
+                if v is not None:
+                    self.samples[kind].append(v)
+            time.sleep(self.period_s)
+
+    def __enter__(self):
+        import threading
+        self._thread = threading.Thread(target=self._loop, daemon=True)
+        self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop = True
+        self._thread.join()
+
+    def summary(self):
+        out = {}
+        for kind, v in self.samples.items():
+            out[kind + "_mhz"] = (dict(min=min(v), median=sorted(v)[len(v) // 2], max=max(v), samples=len(v))
+                                  if v else None)
+        return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -112,7 +162,7 @@ def main():
         mm[(M, N, K)] = dict(name=f"matmul_{M}x{N}x{K}",
                              call=(lambda Ad=Ad, Bd=Bd, Cd=Cd, w=w: lg.lg_matmul(Ad, Bd, Cd, workspace=w)),
                              flops=2.0 * M * N * K, nbytes=4.0 * (M * K + K * N + M * N),
-                             kernel=gemm_kernel_name(M, N, K))
+                             kernel=gemm_kernel_name(M, N, K), operands=(Ad, Bd))
         del A, B
 
     # the row and the column reduction get their own tensor of the configured shape, so the second
@@ -199,6 +249,13 @@ def main():
         2.0 * Mt * Nt * Kt, 12.0 * Mt * Nt, "mfma", gemm_kernel_name(Mt, Nt, Kt) + "_nt")
     add_mm((1024, 1024, 1024))
     add_mm((4096, 4096, 64))
+    # the same shallow product accumulating into C: the output is read as well as written, which
+    # halves the arithmetic intensity and puts the op on the HBM side of the ridge
+    d64 = mm[(4096, 4096, 64)]
+    A64, B64 = d64["operands"]
+    C64acc = torch.zeros((4096, 4096), device="cuda")
+    add("matmul_4096x4096x64_accumulate", lambda: lg.lg_matmul(A64, B64, C64acc, accumulate=True), d64["flops"],
+        4.0 * (2 * 4096 * 64 + 2 * 4096 * 4096), "mfma", d64["kernel"] + "_acc")
     add_mm(si.MATMUL_SMALL)          # configuration 0: 0.2 us of math, a launch-latency figure
 
     # ------------------------------------------------------------------ run
@@ -216,11 +273,13 @@ def main():
     all_events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
                    for _ in ops] for _ in range(args.steps)]
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        step(all_events[k])
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    clocks = ClockSampler()
+    with clocks:
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            step(all_events[k])
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
     per_op = []
@@ -244,6 +303,25 @@ def main():
         if r["bound"] == "hbm":
             r["frac_copy_rate"] = r["gbps"] / copy_gbps
 
+    # the measured ceiling for the contractions: a register-only MFMA issue loop, long enough (~14 ms
+    # per launch) for the engine clock to settle -- a one-millisecond launch from idle reads 10 % low
+    probe_out = torch.empty(lg.lg_mfma_probe_out_elems(), device="cuda")
+    probe_iters = 64000
+    lg.lg_mfma_probe(probe_out, probe_iters)
+    torch.cuda.synchronize()
+    probe_ts = []
+    for _ in range(5):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        lg.lg_mfma_probe(probe_out, probe_iters)
+        b.record(stream)
+        torch.cuda.synchronize()
+        probe_ts.append(a.elapsed_time(b) * 1e-3)
+    mfma_measured = lg.lg_mfma_probe_flops(probe_iters) / float(np.median(probe_ts))
+    for r in per_op:
+        if r["bound"] == "mfma":
+            r["frac_mfma_measured"] = r["gflops"] * 1e9 / mfma_measured
+
     contraction_flops = sum(op["flops"] for op in ops if op["bound"] == "mfma")
     value = contraction_flops / (ms_per_step * 1e-3) / 1e9
 
@@ -257,7 +335,8 @@ def main():
                     launches_per_step=len(dom), ops=[op["name"] for op in dom],
                     flops_per_launch=dom_flops, avg_launch_us=dom_dur * 1e6,
                     achieved=dom_flops / dom_dur / 1e12, peak=MFMA_FP32_PEAK / 1e12, unit="TFLOP/s",
-                    frac=dom_flops / dom_dur / MFMA_FP32_PEAK)
+                    frac=dom_flops / dom_dur / MFMA_FP32_PEAK,
+                    measured_ceiling=mfma_measured / 1e12, frac_of_measured_ceiling=dom_flops / dom_dur / mfma_measured)
     tr = measured_traffic(dom_name)
     # HBM bytes per launch as counted (null once the kernel source differs from the counted one), beside
     # the operand bytes per launch; the excess is A/B panels streamed once per block of output tiles
@@ -273,7 +352,29 @@ def main():
                config=dict(workload="configs[0..4]: matmul 256^3, reduce_rows/cols 4096x16384, transpose (+copy) 8192^2, matmul sweep "
                                     "(1024^3, 4096^3, 8192^3, 16384x512x2048, 4096x4096x64; A^T B and A B^T at 4096^3), conv2d x3 "
                                     "(+ one large conv 32x58x58x256->256 3x3), dwconv1d, dwconv2d; one launch of each per step"),
-               frac_mfma_peak=value * 1e9 / MFMA_FP32_PEAK, roofline=roofline, ops=per_op)
+               frac_mfma_peak=value * 1e9 / MFMA_FP32_PEAK, roofline=roofline, clocks=clocks.summary(), ops=per_op)
+
+    # The memory-bound ops once more, ten launches back to back on the same buffers: "warm" figures
+    # (part of a 256 MiB operand is still in the last-level cache, and no other kernel's write-back
+    # is in the way), to set beside the cold figures of the step above.
+    def back_to_back_us(call, batch=10, reps=5):
+        call()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            for _ in range(batch):
+                call()
+            b.record(stream)
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b) * 1e3 / batch)
+        return float(np.median(ts))
+
+    for op, rec in zip(ops, per_op):
+        if op["bound"] == "hbm":
+            rec["us_warm_back_to_back"] = back_to_back_us(op["call"])
+            rec["gbps_warm"] = op["bytes"] / rec["us_warm_back_to_back"] / 1e3
 
     # ------------------------------------------------------------------ launch-bound problems
     def per_launch_us(call, batch=20, reps=7):

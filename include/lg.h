@@ -236,6 +236,20 @@ int lg_copy2d(const float *in, float *out, int64_t R, int64_t Cn,
               int64_t ld_in, int64_t ld_out, void *stream);
 
 /*
+ * Matrix-pipe yardstick (calibration, the compute counterpart of lg_copy2d): 512 workgroups of
+ * four wavefronts, each wavefront issuing 4 * iters independent 32x32x2 fp32 MFMAs on registers
+ * only, no memory traffic in the loop.  lg_mfma_probe_flops(iters) divided by the launch's
+ * duration is the fp32 matrix rate this part sustains; the GEMM figures are quoted against it
+ * beside the theoretical peak the paper uses for its compute-bound kernels (Section 4.3).
+ * `out` receives lg_mfma_probe_out_elems() floats (one checksum per lane, so the work is
+ * observable); out_elems is the caller's buffer length in elements and must be at least that.
+ * 0 <= iters <= 2^22; anything else, or a short or null buffer, is LG_ERR_INVALID_ARG.
+ */
+int lg_mfma_probe(float *out, int64_t out_elems, int64_t iters, void *stream);
+int64_t lg_mfma_probe_out_elems(void);
+double lg_mfma_probe_flops(int64_t iters);
+
+/*
  * Batched 2-D transpose, Section 4.4: a transpose of more than two dimensions is a set of 2-D
  * transposes at various places in the tensor (the paper's example: [i,j,k,l] -> [k,j,l,i] is
  * j x k transposes of an i x l matrix).  For every b0 < B0, b1 < B1, i < R, j < Cn:

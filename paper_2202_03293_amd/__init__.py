@@ -14,4 +14,5 @@ from .ops import (  # noqa: F401
     lg_dwconv1d_nwc_wc, lg_dwconv2d_nhwc_hwc,
     lg_reduce_rows, lg_reduce_rows_ws, lg_reduce_rows_workspace_bytes, lg_reduce_cols, lg_reduce_cols_workspace_bytes,
     lg_transpose, lg_transpose_batched, lg_copy2d,
+    lg_mfma_probe, lg_mfma_probe_out_elems, lg_mfma_probe_flops,
 )

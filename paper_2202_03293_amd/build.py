@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "liblg.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["status.hip", "memops.hip", "reduce.hip", "dwconv.hip", "gemm.hip", "gemm_t.hip", "gemm_direct.hip", "gemv.hip"]
+SOURCES = ["status.hip", "memops.hip", "reduce.hip", "dwconv.hip", "gemm.hip", "gemm_t.hip", "gemm_direct.hip", "gemv.hip", "calib.hip"]
 
 # Packed-fp32 VALU forms are disabled on purpose (device-side target feature).
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -41,14 +41,15 @@ __global__ __launch_bounds__(256) void gemv_kernel(GemmArgs p) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float* b = p.B + (k + e) * bs;
-                if constexpr (NV == 1) {
-                    bq[e][0] = b[0];
-                } else if constexpr (NV == 2) {            // a row of B is one 8- or 16-byte load (the host checks)
+                if constexpr (NV == 2) {                   // a row of B is one 8- or 16-byte load (the host checks)
                     const float2 v = *reinterpret_cast<const float2*>(b);
                     bq[e][0] = v.x; bq[e][1] = v.y;
-                } else {
+                } else if constexpr (NV == 4) {
                     const float4 v = *reinterpret_cast<const float4*>(b);
                     bq[e][0] = v.x; bq[e][1] = v.y; bq[e][2] = v.z; bq[e][3] = v.w;
+                } else {
+#pragma unroll
+                    for (int n = 0; n < NV; ++n) bq[e][n] = b[n];
                 }
             }
         }

@@ -39,6 +39,9 @@ _SIGNATURES = {
     "lg_transpose": (_int, [_vp, _vp] + [_i64] * 4 + [_vp]),
     "lg_transpose_batched": (_int, [_vp, _vp] + [_i64] * 10 + [_vp]),
     "lg_copy2d": (_int, [_vp, _vp] + [_i64] * 4 + [_vp]),
+    "lg_mfma_probe": (_int, [_vp, _i64, _i64, _vp]),
+    "lg_mfma_probe_out_elems": (_i64, []),
+    "lg_mfma_probe_flops": (ctypes.c_double, [_i64]),
 }
 
 _lib = None
@@ -344,6 +347,20 @@ def lg_copy2d(x, out, stream=None):
     if tuple(out.shape) != (R, Cn):
         raise ValueError("out must have the same shape")
     _check("lg_copy2d", lib().lg_copy2d(_ptr(x), _ptr(out), R, Cn, _ld(x), _ld(out), _stream(stream)))
+    return out
+
+
+def lg_mfma_probe_out_elems():
+    return int(lib().lg_mfma_probe_out_elems())
+
+
+def lg_mfma_probe_flops(iters):
+    return float(lib().lg_mfma_probe_flops(int(iters)))
+
+
+def lg_mfma_probe(out, iters, stream=None):
+    """Enqueue the register-only MFMA issue loop; `out` takes one checksum per lane."""
+    _check("lg_mfma_probe", lib().lg_mfma_probe(_ptr(out), out.numel(), int(iters), _stream(stream)))
     return out
 
 

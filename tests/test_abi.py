@@ -70,6 +70,14 @@ def test_argument_validation_without_device(L):
     assert L.lg_transpose(P, P, 4, 4, 4, 4, None) == -1                        # in place
     assert L.lg_copy2d(P, Q, 4, 8, 7, 8, None) == -1
     assert L.lg_transpose(P, Q, 0, 8, 8, 8, None) == 0
+    n = L.lg_mfma_probe_out_elems()
+    assert n == 512 * 256
+    assert L.lg_mfma_probe(None, n, 10, None) == -1                            # no buffer
+    assert L.lg_mfma_probe(P, n - 1, 10, None) == -1                           # short buffer
+    assert L.lg_mfma_probe(P, n, -1, None) == -1
+    assert L.lg_mfma_probe(P, n, (1 << 22) + 1, None) == -1
+    assert L.lg_mfma_probe_flops(1) == 512 * 4 * 4 * 4096.0                    # groups x waves x chains x flops per MFMA
+    assert L.lg_mfma_probe_flops(-5) == 0.0
     assert L.lg_conv1d_nwc_wcf(P, P, Q, 1, 4, 4, 3, 4, 1, 2, 0, None, 0, None) == -1   # dilated window too big
     assert L.lg_conv1d_nwc_wcf(P, P, Q, 1, 8, 4, 3, 4, 0, 1, 0, None, 0, None) == -1   # stride 0
     assert L.lg_conv1d_nwc_wcf(P, P, Q, 0, 8, 4, 3, 4, 1, 1, 0, None, 0, None) == 0    # empty batch

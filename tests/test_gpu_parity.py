@@ -685,3 +685,29 @@ def test_transpose_full_size(lg, lgo):
     od = torch.empty((x.shape[1], x.shape[0]), device="cuda")
     lg.lg_transpose(dev(x), od); sync()
     assert np.array_equal(bits(od.cpu().numpy()), bits(lgo.transpose(x)))
+
+
+def test_mfma_probe_checksums(lg):
+    """The matrix-pipe yardstick really does the MFMAs it is priced for: its per-lane checksums
+    follow from the instruction's definition (D[i,j] += sum_k A[i,k] B[k,j], lane l holding A[l%32, l//32]
+    and B[l//32, l%32]; a lane's 16 results are rows 8*(v//4) + 4*(l//32) + v%4 of column l%32)."""
+    n = lg.lg_mfma_probe_out_elems()
+    groups, threads, chains = 512, 256, 4
+    assert n == groups * threads
+    out = Guarded((n,))
+    lg.lg_mfma_probe(out.t, 0); sync(); out.check()
+    assert not out.host().any()
+    iters = 48
+    lg.lg_mfma_probe(out.t, iters); sync(); out.check()
+    got = out.host().reshape(groups, threads // 64, 64).astype(np.float64)
+    lane = np.arange(64)
+    rows = np.array([[8 * (v // 4) + 4 * (l // 32) + v % 4 for v in range(16)] for l in lane])   # [lane, v]
+    for g in (0, 1, 77, 511):
+        for w in range(threads // 64):
+            a = (((lane * 37 + g * 11) % 127) - 63) / 65536.0         # A[i = l%32, k = l//32]
+            b = (((lane * 53 + w * 29) % 113) - 56) / 65536.0         # B[k = l//32, j = l%32]
+            A = a.reshape(2, 32).T                                      # [i, k]
+            B = b.reshape(2, 32)                                        # [k, j]
+            D = A @ B                                                   # one MFMA's increment
+            want = np.array([D[rows[l], l % 32].sum() for l in lane]) * iters * chains
+            assert np.allclose(got[g, w], want, rtol=1e-5, atol=1e-9), (g, w)
