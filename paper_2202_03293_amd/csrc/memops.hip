@@ -131,13 +131,22 @@ __global__ __launch_bounds__(THREADS) void transpose_kernel(
     } else {
         constexpr int RP = THREADS / TS;
         const int c = t % TS, rr = t / TS;
-#pragma unroll 4
-        for (int r = rr; r < TS; r += RP)
-            if (i0 + r < R && j0 + c < Cn) tile[r * S + c] = in[(i0 + r) * ld_in + j0 + c];
+        constexpr int NP = TS / RP;                 // elements per lane, all requested before the first lands in LDS
+        uint32_t v[NP];
+#pragma unroll
+        for (int k = 0; k < NP; ++k) {
+            const int r = rr + k * RP;
+            v[k] = 0;
+            if (i0 + r < R && j0 + c < Cn) v[k] = in[(i0 + r) * ld_in + j0 + c];
+        }
+#pragma unroll
+        for (int k = 0; k < NP; ++k) tile[(rr + k * RP) * S + c] = v[k];
         __syncthreads();
-#pragma unroll 4
-        for (int orow = rr; orow < TS; orow += RP)
+#pragma unroll
+        for (int k = 0; k < NP; ++k) {
+            const int orow = rr + k * RP;
             if (j0 + orow < Cn && i0 + c < R) out[(j0 + orow) * ld_out + i0 + c] = tile[c * S + orow];
+        }
     }
 }
 
