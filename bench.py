@@ -480,6 +480,18 @@ def main():
         A256, B256 = host_keep["mm256"]
         t = time.perf_counter(); lgo.matmul(A256, B256); d = time.perf_counter() - t
         others["matmul_256_all_threads_GFLOPs"] = 2.0 * 256 ** 3 / d / 1e9
+        # the paper's own numbers are single-threaded: the same 256^3 product on one host thread, in a
+        # child process that only loads the oracle (the thread count is fixed when OpenMP starts)
+        import subprocess
+        code = ("import sys, time; sys.path.insert(0, %r); import seeded_inputs as si; from oracle import lgo; "
+                "A, B = si.matmul_inputs(0, 256, 256, 256, case=0); lgo.matmul(A, B); t = time.perf_counter(); "
+                "lgo.matmul(A, B); print(2.0 * 256 ** 3 / (time.perf_counter() - t) / 1e9)" % ROOT)
+        try:
+            r = subprocess.run([sys.executable, "-c", code], env=dict(os.environ, OMP_NUM_THREADS="1"),
+                               capture_output=True, text=True, timeout=120)
+            others["matmul_256_one_thread_GFLOPs"] = float(r.stdout.strip().splitlines()[-1])
+        except (subprocess.SubprocessError, ValueError, IndexError):
+            others["matmul_256_one_thread_GFLOPs"] = None
         out["cpu_baseline"] = dict(value=2.0 * 128 * 8192 * 8192 / dt / 1e9, unit="GFLOP/s",
                                    cores=lgo.num_threads(), kind="oracle",
                                    sample="rows 0..127 of the 8192^3 matmul (naive fp64-accumulate loop nest, "
