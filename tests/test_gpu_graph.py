@@ -62,3 +62,45 @@ def test_graph_replay_matches_eager_and_oracle(lgo):
     assert_close(O.cpu().numpy(), lgo.conv2d_nhwc_hwcf(I.cpu().numpy(), Kf.cpu().numpy()), 288, "graph conv")
     assert_close(rows.cpu().numpy(), lgo.reduce_rows(X.cpu().numpy()), 520, "graph reduce_rows")
     assert np.array_equal(Xt.cpu().numpy().view(np.uint32), lgo.transpose(X.cpu().numpy()).view(np.uint32))
+
+
+def test_ops_run_on_the_stream_they_are_given(lgo):
+    """Two side streams, each with several milliseconds of other work queued ahead of the library
+    calls and the operands produced on that stream right before them, no synchronisation until the
+    end.  A call that ran anywhere but on its stream (or that synchronised or kept state shared with
+    the other stream's calls) would read operands that are not there yet."""
+    import paper_2202_03293_amd as lg
+    lg.lib()
+    M, N, K = 784, 512, 4608                   # the planner splits k here: two kernels and a workspace
+    assert lg.lg_matmul_plan(M, N, K)[2] > 1
+    R, Cn = 4100, 1028                         # column reduction in chunks: two kernels and a workspace
+    hA, hB = si.uniform(80, 0, (M, K), -1, 1), si.uniform(80, 1, (K, N), -1, 1)
+    hX = si.uniform(80, 2, (R, Cn), 0, 1)
+    srcA, srcB, srcX = dev(hA), dev(hB), dev(hX)
+    big = torch.rand((6144, 6144), device="cuda")
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    results = []
+    for s in streams:
+        with torch.cuda.stream(s):
+            busy = big @ big                   # keeps the stream busy while the calls below are enqueued
+            A, B, X = torch.zeros_like(srcA), torch.zeros_like(srcB), torch.zeros_like(srcX)
+            A.add_(srcA); B.add_(srcB); X.add_(srcX)
+            C = torch.full((M, N), float("nan"), device="cuda")
+            cols, rows = torch.full((Cn,), float("nan"), device="cuda"), torch.full((R,), float("nan"), device="cuda")
+            Xt = torch.zeros((Cn, R), device="cuda")
+            ws_mm = workspace(lg.lg_matmul_workspace_bytes(M, N, K))
+            ws_rc = workspace(lg.lg_reduce_cols_workspace_bytes(R, Cn))
+            lg.lg_matmul(A, B, C, workspace=ws_mm, stream=s)
+            lg.lg_reduce_cols(X, cols, workspace=ws_rc, stream=s)
+            lg.lg_reduce_rows(X, rows, stream=s)
+            lg.lg_transpose(X, Xt, stream=s)
+            results.append((busy, A, B, X, C, cols, rows, Xt, ws_mm, ws_rc))
+    for s in streams:
+        s.synchronize()
+    refC, refcols, refrows = lgo.matmul(hA, hB), lgo.reduce_cols(hX), lgo.reduce_rows(hX)
+    for _, _, _, _, C, cols, rows, Xt, _, _ in results:
+        assert_close(C.cpu().numpy(), refC, K, "matmul on a side stream")
+        assert_close(cols.cpu().numpy(), refcols, R, "reduce_cols on a side stream")
+        assert_close(rows.cpu().numpy(), refrows, Cn, "reduce_rows on a side stream")
+        assert np.array_equal(Xt.cpu().numpy().view(np.uint32), lgo.transpose(hX).view(np.uint32))
