@@ -711,3 +711,86 @@ def test_mfma_probe_checksums(lg):
             D = A @ B                                                   # one MFMA's increment
             want = np.array([D[rows[l], l % 32].sum() for l in lane]) * iters * chains
             assert np.allclose(got[g, w], want, rtol=1e-5, atol=1e-9), (g, w)
+
+
+# ------------------------------------------------------------------------------- misaligned base pointers
+
+def shifted(a, fill=None):
+    """A device copy of `a` (or a NaN-filled tensor of its shape) that starts 4 bytes into a 16-byte
+    aligned allocation: every extent may be a multiple of 4 and still no access is 16-byte aligned."""
+    n = int(np.prod(a.shape))
+    buf = torch.full((n + 5,), float("nan") if fill is None else fill, device="cuda")
+    view = buf[1:1 + n].view(*a.shape)
+    if fill is None:
+        view.copy_(dev(a))
+    assert view.data_ptr() % 16 == 4
+    return buf, view
+
+
+@pytest.mark.parametrize("which", ["A", "B", "C"])
+@pytest.mark.parametrize("M,N,K", [(256, 256, 256), (200, 192, 1024), (1024, 512, 64), (2048, 4, 2048)])
+def test_matmul_misaligned_operand(lg, lgo, M, N, K, which):
+    A, B = si.matmul_inputs(150, M, N, K)
+    ref = lgo.matmul(A, B)
+    keep = []
+    Ad = shifted(A) if which == "A" else (None, dev(A))
+    Bd = shifted(B) if which == "B" else (None, dev(B))
+    Cd = shifted(np.empty((M, N), np.float32), fill=7.0) if which == "C" else (None, torch.empty((M, N), device="cuda"))
+    keep += [Ad, Bd, Cd]
+    lg.lg_matmul(Ad[1], Bd[1], Cd[1], workspace=workspace(lg.lg_matmul_workspace_bytes(M, N, K))); sync()
+    assert_close(Cd[1].cpu().numpy(), ref, K, f"matmul with {which} 4 bytes off alignment")
+    if which == "C":
+        b = Cd[0].cpu().numpy()
+        assert b[0] == 7.0 and np.all(b[1 + M * N:] == 7.0)       # nothing written outside the view
+    for ta, tb in ((True, False), (False, True)):
+        At = np.ascontiguousarray(A.T) if ta else A
+        Bt = np.ascontiguousarray(B.T) if tb else B
+        Ad2 = shifted(At) if which == "A" else (None, dev(At))
+        Bd2 = shifted(Bt) if which == "B" else (None, dev(Bt))
+        out = shifted(np.empty((M, N), np.float32), fill=7.0) if which == "C" else (None, torch.empty((M, N), device="cuda"))
+        lg.lg_matmul_t(Ad2[1], Bd2[1], out[1], trans_a=ta, trans_b=tb,
+                       workspace=workspace(lg.lg_matmul_workspace_bytes(M, N, K))); sync()
+        assert_close(out[1].cpu().numpy(), ref, K, f"matmul_t {ta, tb} with {which} 4 bytes off alignment")
+
+
+def test_other_ops_misaligned_operands(lg, lgo):
+    I, Kf = si.conv2d_inputs(151, 2, 20, 20, 32, 64, 3, 3)
+    ref = lgo.conv2d_nhwc_hwcf(I, Kf)
+    for which in range(3):
+        ops = [shifted(I) if which == 0 else (None, dev(I)), shifted(Kf) if which == 1 else (None, dev(Kf)),
+               shifted(ref, fill=7.0) if which == 2 else (None, torch.empty(ref.shape, device="cuda"))]
+        lg.lg_conv2d_nhwc_hwcf(ops[0][1], ops[1][1], ops[2][1],
+                               workspace=workspace(lg.lg_conv2d_workspace_bytes(2, 20, 20, 32, 3, 3, 64))); sync()
+        assert_close(ops[2][1].cpu().numpy(), ref, 288, f"conv2d operand {which} misaligned")
+    Id, Kd = si.dwconv2d_inputs(152, 2, 30, 30, 64, 3, 3)
+    refd = lgo.dwconv2d_nhwc_hwc(Id, Kd)
+    I1, K1 = si.dwconv1d_inputs(153, 2, 300, 128, 3)
+    ref1 = lgo.dwconv1d_nwc_wc(I1, K1)
+    for which in range(3):
+        ops = [shifted(Id) if which == 0 else (None, dev(Id)), shifted(Kd) if which == 1 else (None, dev(Kd)),
+               shifted(refd, fill=7.0) if which == 2 else (None, torch.empty(refd.shape, device="cuda"))]
+        lg.lg_dwconv2d_nhwc_hwc(ops[0][1], ops[1][1], ops[2][1]); sync()
+        assert_close(ops[2][1].cpu().numpy(), refd, 9, f"dwconv2d operand {which} misaligned")
+        ops = [shifted(I1) if which == 0 else (None, dev(I1)), shifted(K1) if which == 1 else (None, dev(K1)),
+               shifted(ref1, fill=7.0) if which == 2 else (None, torch.empty(ref1.shape, device="cuda"))]
+        lg.lg_dwconv1d_nwc_wc(ops[0][1], ops[1][1], ops[2][1]); sync()
+        assert_close(ops[2][1].cpu().numpy(), ref1, 3, f"dwconv1d operand {which} misaligned")
+    X = si.uniform(154, 0, (2052, 1024), 0, 1)
+    for mis_in, mis_out in ((True, False), (False, True), (True, True)):
+        xin = shifted(X) if mis_in else (None, dev(X))
+        rows = shifted(np.empty(2052, np.float32), fill=7.0) if mis_out else (None, torch.empty(2052, device="cuda"))
+        cols = shifted(np.empty(1024, np.float32), fill=7.0) if mis_out else (None, torch.empty(1024, device="cuda"))
+        xt = shifted(np.empty((1024, 2052), np.float32), fill=7.0) if mis_out else (None, torch.empty((1024, 2052), device="cuda"))
+        xc = shifted(np.empty((2052, 1024), np.float32), fill=7.0) if mis_out else (None, torch.empty((2052, 1024), device="cuda"))
+        lg.lg_reduce_rows(xin[1], rows[1])
+        lg.lg_reduce_cols(xin[1], cols[1], workspace=workspace(lg.lg_reduce_cols_workspace_bytes(2052, 1024)))
+        lg.lg_transpose(xin[1], xt[1])
+        lg.lg_copy2d(xin[1], xc[1]); sync()
+        assert_close(rows[1].cpu().numpy(), lgo.reduce_rows(X), 1024, "reduce_rows misaligned")
+        assert_close(cols[1].cpu().numpy(), lgo.reduce_cols(X), 2052, "reduce_cols misaligned")
+        assert np.array_equal(bits(xt[1].cpu().numpy()), bits(lgo.transpose(X)))
+        assert np.array_equal(bits(xc[1].cpu().numpy()), bits(X))
+        if mis_out:
+            for b, n in ((rows[0], 2052), (cols[0], 1024), (xt[0], 2052 * 1024), (xc[0], 2052 * 1024)):
+                h = b.cpu().numpy()
+                assert h[0] == 7.0 and np.all(h[1 + n:] == 7.0)
