@@ -794,3 +794,51 @@ def test_other_ops_misaligned_operands(lg, lgo):
             for b, n in ((rows[0], 2052), (cols[0], 1024), (xt[0], 2052 * 1024), (xc[0], 2052 * 1024)):
                 h = b.cpu().numpy()
                 assert h[0] == 7.0 and np.all(h[1 + n:] == 7.0)
+
+
+# ------------------------------------------------------------------------------- non-finite values
+
+def assert_same_nonfinite(got, ref, K, what):
+    """NaNs and infinities land exactly where the definition puts them (zero padding of ragged tiles
+    must never meet an infinity); everything else meets the usual bar."""
+    got, ref = np.asarray(got), np.asarray(ref)
+    assert np.array_equal(np.isnan(got), np.isnan(ref)), f"{what}: NaN positions differ"
+    inf = np.isinf(ref)
+    assert np.array_equal(np.isinf(got), inf) and np.array_equal(got[inf], ref[inf]), f"{what}: infinities differ"
+    fin = np.isfinite(ref)
+    assert_close(np.where(fin, got, 0), np.where(fin, ref, 0), K, what)
+
+
+@pytest.mark.parametrize("M,N,K", [(70, 50, 30), (300, 260, 1001), (130, 129, 64)])
+def test_matmul_propagates_nonfinite_values(lg, lgo, M, N, K):
+    A, B = si.matmul_inputs(160, M, N, K)
+    A[3, K - 1] = np.inf            # last k of a ragged slice
+    A[M - 1, 0] = np.nan            # last row of a ragged tile
+    B[K - 1, N - 1] = -np.inf       # last column
+    A[5, 2] = np.inf; A[5, 7] = -np.inf        # +inf and -inf in one row: NaN wherever both count
+    ref = lgo.matmul(A, B)
+    assert np.isnan(ref).any() and np.isinf(ref).any() and np.isfinite(ref).any()
+    assert_same_nonfinite(run_matmul(lg, A, B), ref, K, "matmul")
+    for v in range(lg.lg_gemm_variants()):
+        out = Guarded((M, N))
+        lg.lg_matmul_variant(dev(A), dev(B), out.t, v); sync(); out.check()
+        assert_same_nonfinite(out.host(), ref, K, f"matmul variant {v}")
+
+
+def test_other_ops_propagate_nonfinite_values(lg, lgo):
+    I, Kf = si.conv2d_inputs(161, 2, 11, 13, 6, 10, 3, 3)
+    I[1, 10, 12, 5] = np.inf; I[0, 0, 0, 0] = np.nan; Kf[2, 2, 5, 9] = -np.inf
+    assert_same_nonfinite(run_conv(lg, I, Kf), lgo.conv2d_nhwc_hwcf(I, Kf), 54, "conv2d")
+    Id, Kd = si.dwconv2d_inputs(162, 2, 9, 21, 68, 3, 3)
+    Id[1, 8, 20, 67] = np.inf; Id[0, 4, 4, 1] = np.nan; Kd[0, 0, 3] = -np.inf
+    out = Guarded((2, 7, 19, 68))
+    lg.lg_dwconv2d_nhwc_hwc(dev(Id), dev(Kd), out.t); sync(); out.check()
+    assert_same_nonfinite(out.host(), lgo.dwconv2d_nhwc_hwc(Id, Kd), 9, "dwconv2d")
+    X = si.uniform(163, 0, (523, 1031), 0, 1)
+    X[0, 1030] = np.inf; X[522, 0] = np.nan; X[7, 5] = -np.inf; X[9, 5] = np.inf
+    rows, cols = Guarded((523,)), Guarded((1031,))
+    lg.lg_reduce_rows(dev(X), rows.t)
+    lg.lg_reduce_cols(dev(X), cols.t, workspace=workspace(lg.lg_reduce_cols_workspace_bytes(523, 1031))); sync()
+    rows.check(); cols.check()
+    assert_same_nonfinite(rows.host(), lgo.reduce_rows(X), 1031, "reduce_rows")
+    assert_same_nonfinite(cols.host(), lgo.reduce_cols(X), 523, "reduce_cols")
