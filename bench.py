@@ -118,7 +118,7 @@ def main():
                          "problems, reported per launch from batches of back-to-back launches under `sweep`")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives are part of it); "
+        print("bench.py: liblg runs on ONE GPU only (it has no collectives); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
