@@ -104,3 +104,46 @@ def test_ops_run_on_the_stream_they_are_given(lgo):
         assert_close(cols.cpu().numpy(), refcols, R, "reduce_cols on a side stream")
         assert_close(rows.cpu().numpy(), refrows, Cn, "reduce_rows on a side stream")
         assert np.array_equal(Xt.cpu().numpy().view(np.uint32), lgo.transpose(hX).view(np.uint32))
+
+
+def test_first_use_of_a_kernel_inside_a_capture():
+    """A caller may record a graph before it has ever launched anything: the one-time set-up a
+    kernel needs on first use (its dynamic LDS limit) must work under stream capture too.  Runs in
+    a fresh process, where no kernel of the library has been launched yet."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = r"""
+import sys
+sys.path.insert(0, %r)
+import torch
+import paper_2202_03293_amd as lg
+A = torch.rand(512, 2048, device="cuda") - 0.5
+B = torch.rand(2048, 1024, device="cuda") - 0.5
+C = torch.zeros(512, 1024, device="cuda")
+X = torch.rand(300, 520, device="cuda")
+Xt = torch.zeros(520, 300, device="cuda")
+cols = torch.zeros(520, device="cuda")
+ws = torch.empty(max(lg.lg_matmul_workspace_bytes(512, 1024, 2048) // 4, 1), device="cuda")
+wc = torch.empty(max(lg.lg_reduce_cols_workspace_bytes(300, 520) // 4, 1), device="cuda")
+torch.cuda.synchronize()
+g = torch.cuda.CUDAGraph()
+with torch.cuda.graph(g):
+    for v in range(lg.lg_gemm_variants()):          # every kernel of the menu, first use
+        lg.lg_matmul_variant(A, B, C, v)
+    lg.lg_matmul(A, B, C, workspace=ws)
+    lg.lg_transpose(X, Xt)
+    lg.lg_reduce_cols(X, cols, workspace=wc)
+C.zero_(); Xt.zero_(); cols.zero_()
+torch.cuda.synchronize()
+g.replay()
+torch.cuda.synchronize()
+ref = (A.double() @ B.double()).float()
+assert (C - ref).abs().max().item() < 1e-4 * 2048 ** 0.5, (C - ref).abs().max().item()
+assert torch.equal(Xt, X.t().contiguous())
+assert (cols - X.double().sum(0).float()).abs().max().item() < 1e-4 * 300 ** 0.5
+print("capture-first ok")
+""" % root
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=110)
+    assert r.returncode == 0 and "capture-first ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
