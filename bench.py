@@ -60,7 +60,7 @@ class ClockSampler:
     pp_dpm_sclk / pp_dpm_mclk tables) from a thread while the timed region runs; reports nothing
     when the files are not there or not readable."""
 
-    def __init__(self, period_s=0.02):
+    def __init__(self, period_s=0.1):
         import glob
         self.files = {k: sorted(glob.glob(f"/sys/class/drm/card*/device/pp_dpm_{k}"))[:1] for k in ("sclk", "mclk")}
         self.samples = {"sclk": [], "mclk": []}
