@@ -311,6 +311,23 @@ static ColPlan plan_cols(int64_t R, int64_t Cn) {
     // least 64 rows each -- 256 once the strips alone give every CU a workgroup (a second launch to
     // combine the chunks then costs more than the extra parallelism returns).
     p.big = R >= 2048 && strips * cdiv(R, 512) >= 128;
+    // A small input is one launch: a 16-wave workgroup keeps 16 x 8 rows in flight (64 / L times that
+    // when L <= 32 lanes cover a row, counting one float per lane as the unaligned case does), and up
+    // to four such round trips cost less than a second launch that adds the chunks (measured back to
+    // back: 100 x 4098 9.5 -> one launch).
+    int64_t in_flight = 16 * 8;
+    if (Cn <= 32) {
+        int64_t L = 1;
+        while (L < Cn) L *= 2;
+        in_flight *= kWave / L;
+    }
+    if (R <= 4 * in_flight && R * Cn <= ((int64_t)1 << 20)) {    // up to 4 MB: beyond that the chunks are worth their launch
+        p.big = R >= 64;
+        p.splits = 1;
+        p.rows_per_wg = R;
+        p.ldp = cdiv(Cn, 64) * 64;
+        return p;
+    }
     int64_t rows;
     if (p.big) {
         rows = 512;
