@@ -8,6 +8,7 @@ namespace lg {
 
 constexpr int kRThreads = 256;
 constexpr int kRWaves = kRThreads / kWave;
+constexpr int64_t kWideRowsBelow = 768;   // fewer rows than this (three per CU), each at least 32768 long: 1024-lane workgroups
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
@@ -25,14 +26,17 @@ __device__ __forceinline__ float4 load_stream4(const float* p) {
 // v = (r, q) starts at in + r*ld + q*Cn and is Cn long except the last of a row, which ends at
 // Ctot (long rows cut into pieces so that a handful of them fills the chip; the piece sums are
 // added by a second pass over the R/P x P matrix of partial sums).
-template <bool VEC, bool WG_PER_ROW>
-__global__ __launch_bounds__(kRThreads) void reduce_rows_kernel(
+// NTH: 256 lanes per workgroup, or 1024 when there are only a few long rows (what one CU draws from
+// memory grows with the loads it has in flight).
+template <bool VEC, bool WG_PER_ROW, int NTH = kRThreads>
+__global__ __launch_bounds__(NTH) void reduce_rows_kernel(
     const float* __restrict__ in, float* __restrict__ out,
     int64_t R, int64_t Cn, int64_t ld, int accumulate, int64_t P, int64_t Ctot) {
-    __shared__ float part[kRWaves];
+    constexpr int NW = NTH / kWave;
+    __shared__ float part[NW];
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-    const int64_t row = WG_PER_ROW ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * kRWaves + wave;
-    const int width = WG_PER_ROW ? kRThreads : kWave;
+    const int64_t row = WG_PER_ROW ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * NW + wave;
+    const int width = WG_PER_ROW ? NTH : kWave;
     const int pos = WG_PER_ROW ? (int)threadIdx.x : lane;
     float s = 0.f;
     if (row < R) {
@@ -77,7 +81,9 @@ __global__ __launch_bounds__(kRThreads) void reduce_rows_kernel(
         if (lane == 0) part[wave] = s;
         __syncthreads();
         if (threadIdx.x == 0) {
-            float tot = (part[0] + part[1]) + (part[2] + part[3]);
+            float tot = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; w += 4) tot += (part[w] + part[w + 1]) + (part[w + 2] + part[w + 3]);
             if (accumulate) tot += out[row];
             out[row] = tot;
         }
@@ -432,6 +438,12 @@ static int reduce_rows_impl(const float* in, float* out, int64_t R, int64_t Cn, 
     const int64_t blocks = wg_per_row ? R : cdiv(R, kRWaves);
     if (blocks > kMaxGrid) return LG_ERR_UNSUPPORTED;
     const dim3 g((unsigned)blocks), b(kRThreads);
+    // a few long rows: 16 wavefronts per row instead of 4 (3 x 1 000 000: 184 -> 32 us; 256 x 131072: 35 -> 20 us)
+    if (wg_per_row && R < kWideRowsBelow && Cn >= 32768) {
+        if (vec) hipLaunchKernelGGL((reduce_rows_kernel<true, true, 1024>), g, dim3(1024), 0, s, in, out, R, Cn, ld, accumulate, (int64_t)1, Cn);
+        else     hipLaunchKernelGGL((reduce_rows_kernel<false, true, 1024>), g, dim3(1024), 0, s, in, out, R, Cn, ld, accumulate, (int64_t)1, Cn);
+        return launch_status();
+    }
     if (vec && wg_per_row)       hipLaunchKernelGGL((reduce_rows_kernel<true, true>), g, b, 0, s, in, out, R, Cn, ld, accumulate, (int64_t)1, Cn);
     else if (vec)                hipLaunchKernelGGL((reduce_rows_kernel<true, false>), g, b, 0, s, in, out, R, Cn, ld, accumulate, (int64_t)1, Cn);
     else if (wg_per_row)         hipLaunchKernelGGL((reduce_rows_kernel<false, true>), g, b, 0, s, in, out, R, Cn, ld, accumulate, (int64_t)1, Cn);

@@ -510,7 +510,10 @@ RED_SHAPES = [(250, 960), (1, 1), (7, 5), (64, 4096), (100, 4100), (33, 8191), (
               (2500, 1000), (2049, 260), (4100, 37), (2048, 4096),
               # short rows / narrow inputs: several rows per wavefront (128-bit and scalar variants)
               (70001, 64), (5000, 128), (3001, 100), (9000, 12), (4097, 4), (20000, 1), (777, 31),
-              (2600, 33), (1500, 256), (999, 63), (100003, 2)]
+              (2600, 33), (1500, 256), (999, 63), (100003, 2),
+              # a few long rows: 16-wavefront workgroups per row (128-bit and scalar); small inputs whose column
+              # sums take one launch
+              (3, 100000), (5, 65537), (700, 32768), (767, 32770), (100, 4098), (5001, 4), (257, 63)]
 
 
 @pytest.mark.parametrize("R,Cn", RED_SHAPES)
