@@ -706,6 +706,41 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
     // accumulator register r of block (mb, nb): row = 32*mb + 8*(r/4) + 4*h + r%4;
     // column = NB*c32 + nb (interleaved, C-kind B) or nb*32 + c32 (R-kind B)
     float* Cz = p.C + (int64_t)blockIdx.y * p.M * p.ldc;
+    if constexpr (!VEC && !TB && NB > 1) {
+        // An output that cannot take 128-bit stores: written straight from the accumulators, the lanes
+        // of a store would sit NB columns apart (1/NB-dense instructions).  Each wavefront instead
+        // turns one 32 x WN block at a time around in its own piece of LDS (the ring is done) and
+        // writes whole rows: 64 adjacent floats per store instruction.
+        constexpr int WN = T::WN;
+        static_assert(T::WAVES * 32 * WN <= T::LDS_FLOATS, "the staging blocks must fit the ring's LDS");
+        __syncthreads();                               // every wave is done reading the ring's stages
+        float* ws = lds + wave * (32 * WN);
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float* q = ws + (8 * (r / 4) + 4 * h + (r % 4)) * WN + NB * c32;
+                if constexpr (NB == 4) *reinterpret_cast<float4*>(q) = make_float4(acc[mb][0][r], acc[mb][1][r], acc[mb][2][r], acc[mb][3][r]);
+                else                   *reinterpret_cast<float2*>(q) = make_float2(acc[mb][0][r], acc[mb][1][r]);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int it = 0; it < 32 * WN / kWave; ++it) {
+                const int idx = it * kWave + lane;
+                const int64_t m = m0 + wm0 + mb * 32 + idx / WN;
+                const int64_t n = n0 + wn0 + idx % WN;
+                const float v = ws[idx];
+                if (m < p.M && n < p.N) {
+                    float* cp = Cz + m * p.ldc + n;
+                    *cp = p.accumulate ? *cp + v : v;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+        return;
+    }
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
