@@ -105,3 +105,13 @@ def test_binding_fails_loudly_without_library(monkeypatch):
     monkeypatch.setattr(ops, "LIB_PATH", "/nonexistent/liblg.so")
     with pytest.raises(ImportError):
         ops.lib()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark is a one-GPU program: asked for more it says so and exits before touching a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
