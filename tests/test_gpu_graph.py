@@ -29,6 +29,21 @@ def test_graph_replay_matches_eager_and_oracle(lgo):
     rows, cols = torch.zeros(2100, device="cuda"), torch.zeros(520, device="cuda")
     ws_rc = workspace(lg.lg_reduce_cols_workspace_bytes(2100, 520))
     Xt = torch.zeros((520, 2100), device="cuda")
+    # the other entry points and the other GEMM kernels: transposed operand, the register-direct kernel
+    # (a small product), matrix times one vector, 1-D convolutions, copy, batched transpose, long rows
+    # cut into pieces
+    Ct = torch.zeros((K, N), device="cuda")                      # A^T (K x M) times C-shaped (M x N)
+    As, Cs = dev(si.uniform(70, 6, (64, 64), -1, 1)), torch.zeros((64, 64), device="cuda")
+    Av, xv = dev(si.uniform(70, 7, (2048, 2048), -1, 1)), dev(si.uniform(70, 8, (2048, 1), -1, 1))
+    yv = torch.zeros((2048, 1), device="cuda")
+    I1, K1 = dev(si.uniform(70, 9, (2, 40, 32), -1, 1)), dev(si.uniform(70, 10, (3, 32, 64), -1, 1))
+    O1 = torch.zeros((2, 38, 64), device="cuda")
+    ws_c1 = workspace(lg.lg_conv1d_workspace_bytes(2, 40, 32, 3, 64))
+    Kd1, Od1 = dev(si.uniform(70, 11, (3, 32), -1, 1)), torch.zeros((2, 38, 32), device="cuda")
+    Xc = torch.zeros((2100, 520), device="cuda")
+    Xb = torch.zeros(2100 * 520, device="cuda")                  # 4 x 5 transposes of 105 x 104 blocks... as a batch
+    Xl, long_rows = dev(si.uniform(70, 12, (3, 40000), 0, 1)), torch.zeros(3, device="cuda")
+    ws_rr = workspace(lg.lg_reduce_rows_workspace_bytes(3, 40000))
 
     def run_all():
         lg.lg_matmul(A, B, C, workspace=ws_mm)
@@ -37,8 +52,16 @@ def test_graph_replay_matches_eager_and_oracle(lgo):
         lg.lg_reduce_rows(X, rows)
         lg.lg_reduce_cols(X, cols, workspace=ws_rc)
         lg.lg_transpose(X, Xt)
+        lg.lg_matmul_t(A, C, Ct, trans_a=True, workspace=workspace(0))
+        lg.lg_matmul(As, As, Cs)
+        lg.lg_matmul(Av, xv, yv)
+        lg.lg_conv1d_nwc_wcf(I1, K1, O1, workspace=ws_c1)
+        lg.lg_dwconv1d_nwc_wc(I1, Kd1, Od1)
+        lg.lg_copy2d(X, Xc)
+        lg.lg_transpose_batched(X.view(-1), Xb, 105, 104, 520, 105, 20, 5, (105 * 520, 104), (5 * 104 * 105, 104 * 105))
+        lg.lg_reduce_rows_ws(Xl, long_rows, workspace=ws_rr)
 
-    outs = (C, O, Od, rows, cols, Xt)
+    outs = (C, O, Od, rows, cols, Xt, Ct, Cs, yv, O1, Od1, Xc, Xb, long_rows)
     run_all()                                  # first use of each kernel happens outside the capture
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
