@@ -167,6 +167,15 @@ __global__ __launch_bounds__(kDThreads) void dwconv2d_win_kernel(
 // rows) is left to the caches.
 // V = 4: a lane owns 4 adjacent channels (128-bit accesses; C % 4 == 0, 16-byte aligned tensors);
 // V = 1: one channel per lane, for channel counts and alignments that rule those out.
+// window position c is read by some (output o < T, tap b < K) of a run of consecutive outputs
+template <int K, int S, int D, int T>
+constexpr bool rows_used(int c) {
+    for (int o = 0; o < T; ++o)
+        for (int b = 0; b < K; ++b)
+            if (o * S + b * D == c) return true;
+    return false;
+}
+
 template <int V> struct ChanVec;
 template <> struct ChanVec<4> {
     float4 v;
@@ -185,7 +194,10 @@ template <> struct ChanVec<1> {
     __device__ __forceinline__ void store(float* p) const { __builtin_nontemporal_store(v, p); }
 };
 
-template <int KW, int TW, int V>
+// SW, DW: horizontal stride and dilation (1 or 2): the run's outputs then read window positions
+// o*SW + b*DW, and only those are loaded (for stride 2 a run of 4 outputs of a 5-wide filter loads
+// 11 positions and 5 taps instead of the 40 loads of four single outputs).
+template <int KW, int TW, int V, int SW = 1, int DW = 1>
 __global__ __launch_bounds__(kDThreads) void dwconv_rows_kernel(
     const float* __restrict__ I, const float* __restrict__ Kf, float* __restrict__ O,
     int64_t N, int64_t H, int64_t W, int64_t C, int64_t KH, int64_t SH, int64_t DH,
@@ -201,24 +213,26 @@ __global__ __launch_bounds__(kDThreads) void dwconv_rows_kernel(
     const int64_t n = idx / (CG * runs * OH);
     const int64_t w0 = run * TW;
     const int nw = OW - w0 < TW ? (int)(OW - w0) : TW;
-    const float* ip = I + ((n * H + oh * SH) * W + w0) * C + V * cg;
+    constexpr int SPAN = (TW - 1) * SW + (KW - 1) * DW + 1;
+    const float* ip = I + ((n * H + oh * SH) * W + w0 * SW) * C + V * cg;
+    const int reach = (nw - 1) * SW + (KW - 1) * DW;   // last window position the run's nw outputs read
     CV acc[TW];
 #pragma unroll
     for (int o = 0; o < TW; ++o) acc[o] = CV::zero();
     for (int64_t a = 0; a < KH; ++a) {
         const float* row = ip + a * DH * W * C;
-        CV x[TW + KW - 1], k[KW];
+        CV x[SPAN], k[KW];
 #pragma unroll
-        for (int c = 0; c < TW + KW - 1; ++c) {
+        for (int c = 0; c < SPAN; ++c) {
             x[c] = CV::zero();
-            if (c < nw + KW - 1) x[c] = CV::load(row + (int64_t)c * C);
+            if (rows_used<KW, SW, DW, TW>(c) && c <= reach) x[c] = CV::load(row + (int64_t)c * C);
         }
 #pragma unroll
         for (int b = 0; b < KW; ++b) k[b] = CV::load(Kf + (a * KW + b) * C + V * cg);
 #pragma unroll
         for (int o = 0; o < TW; ++o)
 #pragma unroll
-            for (int b = 0; b < KW; ++b) acc[o].fma(x[o + b], k[b]);
+            for (int b = 0; b < KW; ++b) acc[o].fma(x[o * SW + b * DW], k[b]);
     }
     float* op = O + ((n * OH + oh) * OW + w0) * C + V * cg;
 #pragma unroll
@@ -333,9 +347,12 @@ static int dwconv_dispatch(const float* I, const float* Kf, float* O,
     }
     // (with few channels a wavefront's lanes would sit a whole run of pixels apart: left to the general
     // kernels, whose lanes are adjacent outputs)
-    if (SW == 1 && DW == 1 && KW >= 2 && KW <= 9 && C >= 64) {
+    // lanes of one position are contiguous in memory: at least 16 x 16 bytes with four channels per lane,
+    // at least 32 x 4 bytes with one (which is also what 32 ... 63 channels get when they are a multiple of 4)
+    const bool v4 = vec && C >= 64;
+    if (SW == 1 && DW == 1 && KW >= 2 && KW <= 9 && C >= 32) {
         // long runs once they still leave every SIMD a few wavefronts, short ones below that
-        const int64_t CG = vec ? C / 4 : C;
+        const int64_t CG = v4 ? C / 4 : C;
         const bool long_runs = N * OH * cdiv(OW, 8) * CG >= (int64_t)kDThreads * 256 * 4;
         const int64_t items = N * OH * cdiv(OW, long_runs ? 8 : 4) * CG;
         const int64_t blocks = cdiv(items, kDThreads);
@@ -345,8 +362,8 @@ static int dwconv_dispatch(const float* I, const float* Kf, float* O,
                            I, Kf, O, N, H, W, C, KH, SH, DH, OH, OW, accumulate)
 #define LG_DWR(K_)                                                                                            \
         if (KW == K_) {                                                                                      \
-            if (vec && long_runs) LG_DWR2(K_, 8, 4);                                                         \
-            else if (vec)         LG_DWR2(K_, 4, 4);                                                         \
+            if (v4 && long_runs)  LG_DWR2(K_, 8, 4);                                                         \
+            else if (v4)          LG_DWR2(K_, 4, 4);                                                         \
             else if (long_runs)   LG_DWR2(K_, 8, 1);                                                         \
             else                  LG_DWR2(K_, 4, 1);                                                         \
             return launch_status();                                                                          \
@@ -354,6 +371,26 @@ static int dwconv_dispatch(const float* I, const float* Kf, float* O,
         LG_DWR(2) LG_DWR(3) LG_DWR(4) LG_DWR(5) LG_DWR(6) LG_DWR(7) LG_DWR(8) LG_DWR(9)
 #undef LG_DWR
 #undef LG_DWR2
+    }
+    // the same kernel at horizontal stride / dilation 2 for widths 3, 5, 7 (the 3 x 3 case with C % 4 == 0
+    // went to the window kernels above): runs of 4 outputs
+    if (SW <= 2 && DW <= 2 && (KW == 3 || KW == 5 || KW == 7) && C >= 32) {
+        const int64_t CG = v4 ? C / 4 : C;
+        const int64_t items = N * OH * cdiv(OW, 4) * CG;
+        const int64_t blocks = cdiv(items, kDThreads);
+        if (blocks > kMaxGrid) return LG_ERR_UNSUPPORTED;
+#define LG_DWS(K_, S_, D_)                                                                                    \
+        if (KW == K_ && SW == S_ && DW == D_) {                                                              \
+            if (v4)  hipLaunchKernelGGL((dwconv_rows_kernel<K_, 4, 4, S_, D_>), dim3((unsigned)blocks), dim3(kDThreads), 0, s, \
+                                        I, Kf, O, N, H, W, C, KH, SH, DH, OH, OW, accumulate);               \
+            else     hipLaunchKernelGGL((dwconv_rows_kernel<K_, 4, 1, S_, D_>), dim3((unsigned)blocks), dim3(kDThreads), 0, s, \
+                                        I, Kf, O, N, H, W, C, KH, SH, DH, OH, OW, accumulate);               \
+            return launch_status();                                                                          \
+        }
+        LG_DWS(3, 2, 1) LG_DWS(3, 1, 2) LG_DWS(3, 2, 2)
+        LG_DWS(5, 2, 1) LG_DWS(5, 1, 2) LG_DWS(5, 2, 2)
+        LG_DWS(7, 2, 1) LG_DWS(7, 1, 2) LG_DWS(7, 2, 2)
+#undef LG_DWS
     }
     if (vec) {
         const int64_t blocks4 = cdiv(out_elems / 4, kDThreads);

@@ -432,8 +432,10 @@ def test_dwconv2d_window_kernels(lg, lgo, s, d):
     # channel counts that are not a multiple of 4: one channel per lane
     (2, 20, 23, 65, 3, 3, 1, 1), (1, 16, 19, 97, 7, 7, 1, 1), (3, 1, 300, 130, 1, 5, 1, 1), (2, 9, 33, 67, 3, 3, 2, 2),
     (4, 70, 140, 255, 3, 3, 1, 1),
-    # fewer than 64 channels: the general kernel takes these
-    (2, 20, 23, 8, 5, 5, 1, 1), (1, 12, 9, 60, 4, 8, 3, 3)])
+    # 32 ... 63 channels: one channel per lane whether or not they are a multiple of 4
+    (1, 12, 9, 60, 4, 8, 3, 3), (2, 20, 23, 33, 5, 5, 1, 1), (2, 20, 23, 48, 5, 5, 1, 1), (2, 1, 200, 32, 1, 4, 1, 1),
+    # fewer than 32 channels: the general kernels take these
+    (2, 20, 23, 8, 5, 5, 1, 1), (2, 20, 23, 31, 5, 5, 1, 1)])
 def test_dwconv_row_streaming_kernel(lg, lgo, N, H, W, C, KH, KW, sh, dh):
     I, Kf = si.dwconv2d_inputs(139 + KW, N, H, W, C, KH, KW)
     ref = lgo.dwconv2d_nhwc_hwc(I, Kf, stride=(sh, 1), dilation=(dh, 1))
@@ -442,6 +444,24 @@ def test_dwconv_row_streaming_kernel(lg, lgo, N, H, W, C, KH, KW, sh, dh):
         O0 = si.uniform(139, KW, ref.shape, -1, 1)
         ref2 = O0.copy(); lgo.dwconv2d_nhwc_hwc(I, Kf, ref2, stride=(sh, 1), dilation=(dh, 1), accumulate=True)
         assert_close(run_dw2(lg, I, Kf, (sh, 1), (dh, 1), O0=O0, accumulate=True), ref2, KH * KW, "dwconv rows accumulate")
+
+
+# the row-streaming kernel at horizontal stride / dilation 2 (widths 3, 5, 7): 128-bit and one-channel
+# lanes, ragged last runs, unequal vertical and horizontal strides, 1-D signals, accumulate
+@pytest.mark.parametrize("N,H,W,C,KH,KW,st,dl", [
+    (2, 23, 25, 64, 5, 5, (2, 2), (1, 1)), (1, 30, 31, 96, 5, 5, (1, 1), (2, 2)), (2, 21, 22, 72, 7, 7, (2, 2), (2, 2)),
+    (2, 17, 19, 65, 3, 3, (2, 2), (1, 1)), (1, 19, 27, 67, 3, 3, (1, 1), (2, 2)), (2, 19, 21, 130, 5, 5, (2, 2), (2, 2)),
+    (3, 12, 40, 64, 3, 5, (1, 2), (1, 1)), (2, 15, 33, 100, 2, 7, (3, 1), (1, 2)), (2, 11, 16, 64, 3, 3, (1, 2), (2, 1)),
+    (4, 1, 301, 63, 1, 5, (1, 2), (1, 2)), (2, 1, 64, 129, 1, 7, (1, 2), (1, 1)), (8, 61, 61, 144, 5, 5, (2, 2), (1, 1)),
+    (2, 23, 25, 50, 5, 5, (2, 2), (1, 1)), (2, 23, 25, 36, 7, 7, (1, 1), (2, 2)), (2, 23, 25, 31, 5, 5, (2, 2), (1, 1))])
+def test_dwconv_row_streaming_kernel_strided(lg, lgo, N, H, W, C, KH, KW, st, dl):
+    I, Kf = si.dwconv2d_inputs(170 + KW, N, H, W, C, KH, KW)
+    ref = lgo.dwconv2d_nhwc_hwc(I, Kf, stride=st, dilation=dl)
+    assert_close(run_dw2(lg, I, Kf, st, dl), ref, KH * KW, f"dwconv rows strided {(N, H, W, C, KH, KW, st, dl)}")
+    if N * H * W * C < 400000:
+        O0 = si.uniform(170, KW, ref.shape, -1, 1)
+        ref2 = O0.copy(); lgo.dwconv2d_nhwc_hwc(I, Kf, ref2, stride=st, dilation=dl, accumulate=True)
+        assert_close(run_dw2(lg, I, Kf, st, dl, O0=O0, accumulate=True), ref2, KH * KW, "dwconv rows strided accumulate")
 
 
 # the 2-D depthwise sizes of Section 4.7: batch-1 MobileNet layers (output extent x channels), each
