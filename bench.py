@@ -222,9 +222,9 @@ def main():
         add(d["name"], d["call"], d["flops"], d["nbytes"], "mfma", d["kernel"])
 
     # Order.  Writes of one kernel linger dirty in the Infinity Cache and are paid for by the next
-    # kernel, so (a) the write-heavy memory-bound ops run as one chain, each preceded by another
-    # write-heavy op as in a steady state (copy2d, the bandwidth yardstick, heads the chain and is the
-    # only one that starts from clean caches), (b) a compute-bound GEMM follows the chain and absorbs
+    # kernel, so (a) the large write-heavy memory-bound ops run as one chain, each preceded by another
+    # write-heavy op of its own size as in a steady state (copy2d, the bandwidth yardstick, heads the
+    # chain and starts from clean caches), (b) a compute-bound GEMM follows the chain and absorbs
     # its write-back, (c) the read-only reductions follow GEMMs with small outputs.  Every operand was
     # last touched > 1 GiB of traffic ago, i.e. it is cold in L2 and in the Infinity Cache.
     add("copy2d_8192x8192", lambda: lg.lg_copy2d(x_cp, y_cp), 0, 8.0 * x_cp.numel(), "hbm", "copy2d")
@@ -232,8 +232,6 @@ def main():
     # depthwise bytes follow the paper's accounting: output written, filter read, input read once
     add("dwconv1d_n32w4098c512k3", lambda: lg.lg_dwconv1d_nwc_wc(I1, K1, O1), 2.0 * O1.numel() * k1,
         4.0 * (O1.numel() + K1.numel() + I1.numel()), "hbm", "dwconv1d")
-    add("dwconv2d_n8h114c96k3", lambda: lg.lg_dwconv2d_nhwc_hwc(I2, K2, O2), 2.0 * O2.numel() * kh2 * kw2,
-        4.0 * (O2.numel() + K2.numel() + I2.numel()), "hbm", "dwconv2d")
     add_mm((4096, 4096, 4096))
     add_mm((16384, 512, 2048))
     for c in convs[:-1]:
@@ -242,6 +240,10 @@ def main():
         "reduce_rows")
     add("reduce_cols_4096x16384", lambda: lg.lg_reduce_cols(x_cols, out_cols, workspace=ws_cols), R * Cn,
         4.0 * (R * Cn + Cn), "hbm", "reduce_cols")
+    # the 2-D depthwise op is small (77 MB): right after the 1-D one it would spend its time behind the
+    # write-back of that kernel's 268 MB; here its operands are just as cold and the caches are clean
+    add("dwconv2d_n8h114c96k3", lambda: lg.lg_dwconv2d_nhwc_hwc(I2, K2, O2), 2.0 * O2.numel() * kh2 * kw2,
+        4.0 * (O2.numel() + K2.numel() + I2.numel()), "hbm", "dwconv2d")
     add_mm((8192, 8192, 8192))
     c = convs[-1]            # the large conv: what the implicit GEMM does once the machine is full
     add(c["name"], c["call"], c["flops"], c["nbytes"], "mfma", c["kernel"])
