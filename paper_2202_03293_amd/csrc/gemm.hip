@@ -168,8 +168,13 @@ static int matmul_impl(const float* A, const float* B, float* C, int64_t M, int6
         overlaps(B, ((b_rows - 1) * ldb + b_cols) * 4, C, c_bytes))
         return LG_ERR_INVALID_ARG;
     if (M >= (int64_t)1 << 31 || N >= (int64_t)1 << 31 || K >= (int64_t)1 << 31) return LG_ERR_UNSUPPORTED;
-    const bool vec = (K % 4 == 0) && (N % 4 == 0) && (M % 4 == 0 || !transA) && (lda % 4 == 0) && (ldb % 4 == 0) &&
-                     (ldc % 4 == 0) && aligned16(A) && aligned16(B) && aligned16(C);
+    // 128-bit transfers need every operand row to start on a 16-byte boundary and hold whole quads.
+    // A B^T fetches both operands along k and writes C one float per lane in dense rows, so there
+    // the output (N, ldc, C's base) does not enter into it: a product against a [vocabulary x hidden]
+    // matrix with an odd vocabulary keeps its 128-bit loads.
+    const bool vec = transB ? (K % 4 == 0) && (lda % 4 == 0) && (ldb % 4 == 0) && aligned16(A) && aligned16(B)
+                            : (K % 4 == 0) && (N % 4 == 0) && (M % 4 == 0 || !transA) && (lda % 4 == 0) &&
+                              (ldb % 4 == 0) && (ldc % 4 == 0) && aligned16(A) && aligned16(B) && aligned16(C);
     GemmArgs a{};
     a.A = A; a.B = B; a.C = C;
     a.M = M; a.N = N; a.K = K;
