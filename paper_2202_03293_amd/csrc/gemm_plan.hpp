@@ -39,10 +39,11 @@ int launch_gemv(const GemmArgs& a, Layout layout, hipStream_t s);
 // slice of barrier skew and LDS latency that only other resident workgroups hide (less with the
 // four-stage ring, which fetches across the barrier).
 struct TileInfo { int bm, bn, bk, occ, mfma; double eff, dead; };
-constexpr int kNumTiles = 6;
+constexpr int kNumTiles = 7;
 static const TileInfo kTiles[kNumTiles] = {
     {128, 256, 16, 2, 4096, 0.935, 350}, {128, 128, 16, 2, 2048, 0.96, 300}, {128, 64, 16, 3, 1024, 0.91, 250},
-    {64, 64, 16, 5, 512, 0.88, 220},     {64, 128, 32, 2, 2048, 0.89, 478},  {64, 64, 32, 2, 1024, 0.88, 330}};
+    {64, 64, 16, 5, 512, 0.88, 220},     {64, 128, 32, 2, 2048, 0.89, 478},  {64, 64, 32, 2, 1024, 0.88, 330},
+    {128, 32, 32, 2, 1024, 0.85, 300}};
 
 struct Plan {
     int tile;          // index into kTiles
@@ -68,10 +69,15 @@ inline Plan make_plan(int64_t M, int64_t N, int64_t K) {
     for (int ti = 0; ti < kNumTiles; ++ti) {
         const TileInfo& tl = kTiles[ti];
         const int64_t tm = cdiv(M, tl.bm), tn = cdiv(N, tl.bn);
+        // the 128 x 32 tile is for tall products with few columns (a 1 x 1 convolution to a handful of
+        // channels): one or two tile columns, so that A still streams through once or twice
+        if (tl.bn == 32 && tn > 2) continue;
         const double dead = tl.dead;
         // tile 0 has no k-tail handling: a k that is not a multiple of its slice depth sends every
         // tile down the register-staged path
-        const double slow = (ti == 0 && K % tl.bk != 0) ? 1.25 : 1.0;
+        // ... and the 128 x 32 tile, whose few slices are all transfer issue when A comes one float at
+        // a time (a convolution over 3 channels: 41 us measured against 22 us by this model)
+        const double slow = (ti == 0 && K % tl.bk != 0) ? 1.25 : (tl.bn == 32 && K % 4 != 0) ? 1.9 : 1.0;
         const double fill = 3000.0 + tl.occ * tl.bm * tl.bn * 4.0 / 9.0;
         for (int sp : split_menu) {
             if (sp > 1 && kslabs < 2 * sp) break;                // keep at least 128 k per slab
@@ -127,8 +133,10 @@ inline Plan make_plan(int64_t M, int64_t N, int64_t K) {
             // for its operands, one-float loads, the stores -- spread over the wavefronts a SIMD
             // holds: measured 0.26 / 0.36 / 0.56 us per wavefront, SIMD and k chunk for nbw = 1 / 2 / 4
             // (K = 27 ... 147, 12 000 ... 100 000 blocks).
+            // (measured with an aligned B and C; one float per access there too -- N not a multiple of
+            // 4 -- costs 1.6 times that: 401408 x 3 x 64 50 us)
             if (one_float && waves > 16 * kCUs)
-                cost = waves / (4.0 * kCUs) * (double)cdiv(K, 16) * (0.16e-6 + 0.10e-6 * nbw);
+                cost = waves / (4.0 * kCUs) * (double)cdiv(K, 16) * (0.16e-6 + 0.10e-6 * nbw) * (N % 4 != 0 ? 1.6 : 1.0);
             cost += 6.9e-6 + (ks > 1 ? 0.3e-6 : 0.0);
             if (cost < best_cost) {
                 best_cost = cost;
