@@ -95,6 +95,14 @@ int lg_matmul_t(const float *A, const float *B, float *C,
 int lg_matmul_plan(int64_t M, int64_t N, int64_t K, int *block_m, int *block_n, int *k_splits);
 
 /*
+ * The same for lg_matmul_t: the plan may depend on the operand layout (a few dozen rows times a
+ * large B stored N x K take k-slabs where AB does not).  lg_matmul_workspace_bytes(M, N, K) covers
+ * the plan of every layout.  transA and transB both set is LG_ERR_INVALID_ARG.
+ */
+int lg_matmul_t_plan(int64_t M, int64_t N, int64_t K, int transA, int transB,
+                     int *block_m, int *block_n, int *k_splits);
+
+/*
  * The decomposition as a parameter (the paper's transformations take their tile sizes as
  * parameters and leave the choice to a search, Sections 3.2 and 4.1; here the menu of compiled
  * decompositions is numbered and the default entry points above pick from it with a cost

@@ -105,7 +105,7 @@ static int run_gemm(const GemmArgs& a, Layout layout, bool vec, int user_accumul
             g.accumulate = user_accumulate;
             return launch_gemv(g, layout, s);
         }
-        pl = make_plan(a.M, a.N, a.K);
+        pl = make_plan(a.M, a.N, a.K, layout == Layout::NT);
         // the planner knows extents, not pitches: operands padded past the direct kernel's reach
         // run on the smallest tile, unsplit (which needs no workspace either)
         if (pl.direct_nbw > 0 && !direct_can_run(a, layout)) forced_plan(a.M, a.N, a.K, 3, 1, &pl);
@@ -145,7 +145,19 @@ extern "C" int lg_matmul_plan(int64_t M, int64_t N, int64_t K, int* block_m, int
 extern "C" size_t lg_matmul_workspace_bytes(int64_t M, int64_t N, int64_t K) {
     using namespace lg;
     if (M <= 0 || N <= 0 || K <= 0) return 0;
-    return plan_workspace(make_plan(M, N, K), M, N);
+    return matmul_workspace(M, N, K);
+}
+
+extern "C" int lg_matmul_t_plan(int64_t M, int64_t N, int64_t K, int transA, int transB,
+                                int* block_m, int* block_n, int* k_splits) {
+    using namespace lg;
+    if (M <= 0 || N <= 0 || K <= 0 || (transA && transB)) return LG_ERR_INVALID_ARG;
+    const Plan pl = make_plan(M, N, K, transB != 0);
+    const bool direct = pl.direct_nbw > 0;
+    if (block_m) *block_m = direct ? 16 : kTiles[pl.tile].bm;
+    if (block_n) *block_n = direct ? 16 * pl.direct_nbw : kTiles[pl.tile].bn;
+    if (k_splits) *k_splits = direct ? 1 : (int)pl.splits;
+    return LG_OK;
 }
 
 namespace lg {

@@ -60,7 +60,7 @@ constexpr int kKGran = 64;   // split-k slabs are multiples of this (a multiple 
 // workgroups on a CU also pays `fill`: start-up, and the output write, which is HBM-bound because
 // the workgroups of a round reach their epilogues together (~9 bytes per clock per CU).  The busiest CU decides; a launch costs ~4 us of fill and drain;
 // split-k adds the partial-sum traffic and a second launch.
-inline Plan make_plan(int64_t M, int64_t N, int64_t K) {
+inline Plan make_plan(int64_t M, int64_t N, int64_t K, bool b_along_k = false) {
     const double clk = 2.4e9;
     const int64_t kslabs = cdiv(K, kKGran);
     static const int split_menu[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
@@ -111,6 +111,10 @@ inline Plan make_plan(int64_t M, int64_t N, int64_t K) {
     // blocks, or when the contraction is a few chunks deep (a filter over three channels), where the
     // tiled kernel spends its time filling and draining its ring.
     const bool one_float = (K % 4 != 0) || (N % 4 != 0);
+    // A B^T (B stored N x K) with a few dozen rows against a large B: the direct blocks fetch B along k
+    // in 64-byte pieces, 16 rows per access, and fall behind the tiles with k-slabs (measured:
+    // 64 x 4096 x 4096 40 vs 27 us, 32 x 4096 x 11008 61 vs 56; up to 16 rows the direct blocks win)
+    if (b_along_k && M >= 32 && M <= 128 && K * N >= ((int64_t)1 << 22)) return best;
     for (int nbw = 1; nbw <= ((N % 4 != 0) ? 2 : 4); nbw *= 2) {
         const int occ = nbw == 1 ? 4 : nbw == 2 ? 3 : 2;
         for (int ks = 1; ks <= 4; ks *= 2) {
@@ -152,6 +156,13 @@ inline Plan make_plan(int64_t M, int64_t N, int64_t K) {
 
 inline size_t plan_workspace(const Plan& pl, int64_t M, int64_t N) {
     return pl.splits > 1 ? (size_t)(pl.splits * M * N) * sizeof(float) : 0;
+}
+
+// What a caller is told to bring for (M, N, K): enough for the plan of any operand layout.
+inline size_t matmul_workspace(int64_t M, int64_t N, int64_t K) {
+    const size_t a = plan_workspace(make_plan(M, N, K, false), M, N);
+    const size_t b = plan_workspace(make_plan(M, N, K, true), M, N);
+    return a > b ? a : b;
 }
 
 }  // namespace lg

@@ -20,6 +20,7 @@ _SIGNATURES = {
     "lg_matmul_t": (_int, [_vp, _vp, _vp] + [_i64] * 6 + [_int, _int, _int, _vp, _sz, _vp]),
     "lg_matmul_workspace_bytes": (_sz, [_i64] * 3),
     "lg_matmul_plan": (_int, [_i64] * 3 + [ctypes.POINTER(_int)] * 3),
+    "lg_matmul_t_plan": (_int, [_i64] * 3 + [_int, _int] + [ctypes.POINTER(_int)] * 3),
     "lg_gemm_variants": (_int, []),
     "lg_gemm_variant_info": (_int, [_int] + [ctypes.POINTER(_int)] * 4),
     "lg_gemm_variant_workspace_bytes": (_sz, [_i64] * 3 + [_int, _int]),
@@ -138,6 +139,14 @@ def lg_matmul_plan(M, N, K):
     """(block_m, block_n, k_splits) the library picks for an M x N x K contraction."""
     bm, bn, sp = _int(), _int(), _int()
     _check("lg_matmul_plan", lib().lg_matmul_plan(M, N, K, ctypes.byref(bm), ctypes.byref(bn), ctypes.byref(sp)))
+    return bm.value, bn.value, sp.value
+
+
+def lg_matmul_t_plan(M, N, K, trans_a=False, trans_b=False):
+    """(block_m, block_n, k_splits) for lg_matmul_t in the given operand layout."""
+    bm, bn, sp = _int(), _int(), _int()
+    _check("lg_matmul_t_plan", lib().lg_matmul_t_plan(M, N, K, int(trans_a), int(trans_b),
+                                                      ctypes.byref(bm), ctypes.byref(bn), ctypes.byref(sp)))
     return bm.value, bn.value, sp.value
 
 

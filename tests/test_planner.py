@@ -38,8 +38,11 @@ def test_plans_name_menu_entries_and_size_their_workspace(lg):
         bm, bn, splits = lg.lg_matmul_plan(M, N, K)
         assert (bm, bn) in blocks, (M, N, K)
         assert 1 <= splits <= max(1, cdiv(K, 128))
+        # the workspace a caller is told to bring covers the plan of every operand layout
         need = lg.lg_matmul_workspace_bytes(M, N, K)
-        assert need == (splits * M * N * 4 if splits > 1 else 0), (M, N, K)
+        plans = [(bm, bn, splits), lg.lg_matmul_t_plan(M, N, K, trans_a=True), lg.lg_matmul_t_plan(M, N, K, trans_b=True)]
+        assert plans[1] == plans[0], (M, N, K)
+        assert need == max(sp * M * N * 4 if sp > 1 else 0 for _, _, sp in plans), (M, N, K)
         if bm == 16:
             assert splits == 1
     assert lg.lg_matmul_workspace_bytes(0, 4, 4) == 0
@@ -53,6 +56,13 @@ def test_regimes(lg):
         assert lg.lg_matmul_plan(*shape)[0] == 16
     # few tiles and a deep contraction: split along k
     assert lg.lg_matmul_plan(784, 512, 4608)[2] > 1
+    # a few dozen rows against a large B stored N x K: tiles with k-slabs, where AB takes the direct blocks
+    assert lg.lg_matmul_plan(64, 4096, 4096)[0] == 16
+    bm, _, sp = lg.lg_matmul_t_plan(64, 4096, 4096, trans_b=True)
+    assert bm > 16 and sp > 1
+    assert lg.lg_matmul_workspace_bytes(64, 4096, 4096) == sp * 64 * 4096 * 4
+    with pytest.raises(lg.LgError):
+        lg.lg_matmul_t_plan(64, 64, 64, trans_a=True, trans_b=True)
 
 
 def test_variant_workspace_follows_the_slab_rule(lg):
