@@ -27,7 +27,7 @@ __global__ __launch_bounds__(256) void fill_zero_2d_kernel(float* C, int64_t M, 
     C[m * ldc + (idx - m * N)] = 0.f;
 }
 
-// The menu a caller may pick from by number: the seven tiles, then the register-direct kernel with
+// The menu a caller may pick from by number: the eight tiles, then the register-direct kernel with
 // blocks 16 x {16, 32, 64} and {1, 2, 4} k parts per workgroup.
 constexpr int kNumVariants = kNumTiles + 9;
 

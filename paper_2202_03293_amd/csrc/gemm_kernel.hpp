@@ -800,6 +800,7 @@ using Tile3 = Tile<64, 64, 16, 32, 32, 4, 4>;      // waves of 32x32 (small prob
 using Tile4 = Tile<64, 128, 32, 32, 64, 2>;        // waves of 32x64, deeper slices (mid-size problems)
 using Tile5 = Tile<64, 64, 32, 32, 32, 2, 4>;      // waves of 32x32, deeper slices
 using Tile6 = Tile<128, 32, 32, 32, 32, 2, 3>;     // four waves of 32x32 stacked along m: tall products with few columns
+using Tile7 = Tile<32, 128, 32, 32, 32, 2, 3>;     // four waves of 32x32 side by side: a few rows times a large matrix
 
 template <class T, bool VEC, bool CONV, bool TA, bool TB>
 static void launch_gemm(const GemmArgs& a, unsigned splits, hipStream_t s) {
@@ -826,7 +827,8 @@ static void launch_planned(const GemmArgs& a, const Plan& pl, bool vec, hipStrea
         case 3: LG_LAUNCH(Tile3); break;
         case 4: LG_LAUNCH(Tile4); break;
         case 5: LG_LAUNCH(Tile5); break;
-        default: LG_LAUNCH(Tile6); break;
+        case 6: LG_LAUNCH(Tile6); break;
+        default: LG_LAUNCH(Tile7); break;
     }
 #undef LG_LAUNCH
 }

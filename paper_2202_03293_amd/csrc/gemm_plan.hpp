@@ -39,11 +39,11 @@ int launch_gemv(const GemmArgs& a, Layout layout, hipStream_t s);
 // slice of barrier skew and LDS latency that only other resident workgroups hide (less with the
 // four-stage ring, which fetches across the barrier).
 struct TileInfo { int bm, bn, bk, occ, mfma; double eff, dead; };
-constexpr int kNumTiles = 7;
+constexpr int kNumTiles = 8;
 static const TileInfo kTiles[kNumTiles] = {
     {128, 256, 16, 2, 4096, 0.935, 350}, {128, 128, 16, 2, 2048, 0.96, 300}, {128, 64, 16, 3, 1024, 0.91, 250},
     {64, 64, 16, 5, 512, 0.88, 220},     {64, 128, 32, 2, 2048, 0.89, 478},  {64, 64, 32, 2, 1024, 0.88, 330},
-    {128, 32, 32, 2, 1024, 0.85, 300}};
+    {128, 32, 32, 2, 1024, 0.85, 300},      {32, 128, 32, 2, 1024, 0.85, 300}};
 
 struct Plan {
     int tile;          // index into kTiles
@@ -72,6 +72,8 @@ inline Plan make_plan(int64_t M, int64_t N, int64_t K, bool b_along_k = false) {
         // the 128 x 32 tile is for tall products with few columns (a 1 x 1 convolution to a handful of
         // channels): one or two tile columns, so that A still streams through once or twice
         if (tl.bn == 32 && tn > 2) continue;
+        // ... and the 32 x 128 tile for its transpose, up to 32 rows times a large matrix: B streams through once
+        if (tl.bm == 32 && tm > 1) continue;
         const double dead = tl.dead;
         // tile 0 has no k-tail handling: a k that is not a multiple of its slice depth sends every
         // tile down the register-staged path
@@ -113,8 +115,8 @@ inline Plan make_plan(int64_t M, int64_t N, int64_t K, bool b_along_k = false) {
     const bool one_float = (K % 4 != 0) || (N % 4 != 0);
     // A B^T (B stored N x K) with a few dozen rows against a large B: the direct blocks fetch B along k
     // in 64-byte pieces, 16 rows per access, and fall behind the tiles with k-slabs (measured:
-    // 64 x 4096 x 4096 40 vs 27 us, 32 x 4096 x 11008 61 vs 56; up to 16 rows the direct blocks win)
-    if (b_along_k && M >= 32 && M <= 128 && K * N >= ((int64_t)1 << 22)) return best;
+    // 64 x 4096 x 4096 40 vs 27 us, 24 x 8192 x 8192 76 vs 49; up to 16 rows the direct blocks win)
+    if (b_along_k && M > 16 && M <= 128 && K * N >= ((int64_t)1 << 22)) return best;
     for (int nbw = 1; nbw <= ((N % 4 != 0) ? 2 : 4); nbw *= 2) {
         const int occ = nbw == 1 ? 4 : nbw == 2 ? 3 : 2;
         for (int ks = 1; ks <= 4; ks *= 2) {

@@ -1,5 +1,5 @@
 """GPU parity of every GEMM kernel variant on shapes the planner would never give it: each of the
-seven LDS tiles (with and without a k-split) and each register-direct variant runs ragged, tiny and
+eight LDS tiles (with and without a k-split) and each register-direct variant runs ragged, tiny and
 unaligned matmuls in the three layouts and convolutions with aligned and odd channel counts,
 against the CPU oracle on the same seeded inputs, between canary guard bands."""
 import numpy as np
@@ -11,7 +11,7 @@ from gpu_util import Guarded, assert_close, dev, workspace
 
 pytestmark = pytest.mark.gpu
 
-N_VARIANTS = 16            # checked against the library in test_variant_menu
+N_VARIANTS = 17            # checked against the library in test_variant_menu
 
 
 @pytest.fixture(scope="module")

@@ -22,7 +22,7 @@ def test_variant_menu_is_consistent(lg):
     infos = [lg.lg_gemm_variant_info(v) for v in range(n)]
     assert len(set(infos)) == n
     for bm, bn, bk, parts in infos:
-        assert bm in (16, 64, 128) and bn % 16 == 0 and bk in (16, 32) and parts in (1, 2, 4)
+        assert bm in (16, 32, 64, 128) and bn % 16 == 0 and bk in (16, 32) and parts in (1, 2, 4)
         assert parts == 1 or bm == 16                 # only the register-direct kernel cuts k inside a workgroup
     for bad in (-1, n, n + 7):
         with pytest.raises(lg.LgError):
