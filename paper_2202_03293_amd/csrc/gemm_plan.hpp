@@ -144,6 +144,18 @@ inline Plan make_plan(int64_t M, int64_t N, int64_t K, bool b_along_k = false) {
             // 4 -- costs 1.6 times that: 401408 x 3 x 64 50 us)
             if (one_float && waves > 16 * kCUs)
                 cost = waves / (4.0 * kCUs) * (double)cdiv(K, 16) * (0.16e-6 + 0.10e-6 * nbw) * (N % 4 != 0 ? 1.6 : 1.0);
+            // A B stored K x N well past the last-level cache streams from HBM in pieces as wide as the
+            // block, every block of 16 rows in a pass of its own: 64-byte pieces (nbw = 1) reach about
+            // 3 TB/s, wider ones 5.6-5.8 (measured: 1 x 4096 x 25088 on 16-wide blocks 133 us,
+            // 16 x 8192 x 8192 on 32-wide 45 us, 1 x 16384 x 16384 on 64-wide 193 us).
+            if (!b_along_k) {
+                const double b_once = (double)K * (double)N * 4.0;
+                if (b_once > 300e6) {
+                    static const double rate[5] = {0.0, 3.0e12, 5.8e12, 0.0, 5.6e12};
+                    const double hbm = b_once * (double)cdiv(M, 16) / rate[nbw];
+                    if (hbm > cost) cost = hbm;
+                }
+            }
             cost += 6.9e-6 + (ks > 1 ? 0.3e-6 : 0.0);
             if (cost < best_cost) {
                 best_cost = cost;
