@@ -105,7 +105,7 @@ static int run_gemm(const GemmArgs& a, Layout layout, bool vec, int user_accumul
             g.accumulate = user_accumulate;
             return launch_gemv(g, layout, s);
         }
-        pl = make_plan(a.M, a.N, a.K, layout == Layout::NT);
+        pl = make_plan(a.M, a.N, a.K, layout == Layout::NT, layout == Layout::CONV ? a.g.C : 0);
         // the planner knows extents, not pitches: operands padded past the direct kernel's reach
         // run on the smallest tile, unsplit (which needs no workspace either)
         if (pl.direct_nbw > 0 && !direct_can_run(a, layout)) forced_plan(a.M, a.N, a.K, 3, 1, &pl);
@@ -252,7 +252,9 @@ extern "C" size_t lg_conv2d_workspace_bytes(int64_t N, int64_t H, int64_t W, int
     const int64_t OH = lg_conv_out_extent(H, KH, SH, DH), OW = lg_conv_out_extent(W, KW, SW, DW);
     if (N <= 0 || C <= 0 || F <= 0 || OH <= 0 || OW <= 0) return 0;
     const int64_t M = N * OH * OW;
-    return plan_workspace(make_plan(M, F, KH * KW * C), M, F);
+    // the plan lg_conv2d_nhwc_hwcf will make: a 1 x 1 filter at stride 1 runs as the matmul it is
+    const bool as_matmul = KH == 1 && KW == 1 && SH == 1 && SW == 1;
+    return plan_workspace(make_plan(M, F, KH * KW * C, false, as_matmul ? 0 : C), M, F);
 }
 
 namespace lg {

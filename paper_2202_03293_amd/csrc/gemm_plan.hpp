@@ -60,7 +60,7 @@ constexpr int kKGran = 64;   // split-k slabs are multiples of this (a multiple 
 // workgroups on a CU also pays `fill`: start-up, and the output write, which is HBM-bound because
 // the workgroups of a round reach their epilogues together (~9 bytes per clock per CU).  The busiest CU decides; a launch costs ~4 us of fill and drain;
 // split-k adds the partial-sum traffic and a second launch.
-inline Plan make_plan(int64_t M, int64_t N, int64_t K, bool b_along_k = false) {
+inline Plan make_plan(int64_t M, int64_t N, int64_t K, bool b_along_k = false, int64_t conv_c = 0) {
     const double clk = 2.4e9;
     const int64_t kslabs = cdiv(K, kKGran);
     static const int split_menu[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
@@ -80,7 +80,11 @@ inline Plan make_plan(int64_t M, int64_t N, int64_t K, bool b_along_k = false) {
         // tile down the register-staged path
         // ... and the 128 x 32 tile, whose few slices are all transfer issue when A comes one float at
         // a time (a convolution over 3 channels: 41 us measured against 22 us by this model)
-        const double slow = (ti == 0 && K % tl.bk != 0) ? 1.25 : (tl.bn == 32 && K % 4 != 0) ? 1.9 : 1.0;
+        double slow = (ti == 0 && K % tl.bk != 0) ? 1.25 : (tl.bn == 32 && K % 4 != 0) ? 1.9 : 1.0;
+        // a convolution (conv_c = its channel count) whose channels do not fill whole slices walks the
+        // filter taps per lane instead of in scalar registers (8 x 224 x 224 x 16 -> 16, 3 x 3 on a
+        // 32-deep tile: 68 us against 52 us by this model)
+        if (conv_c > 0 && conv_c % tl.bk != 0) slow *= 1.4;
         const double fill = 3000.0 + tl.occ * tl.bm * tl.bn * 4.0 / 9.0;
         for (int sp : split_menu) {
             if (sp > 1 && kslabs < 2 * sp) break;                // keep at least 128 k per slab
