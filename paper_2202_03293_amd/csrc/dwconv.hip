@@ -118,10 +118,12 @@ __global__ __launch_bounds__(kDThreads) void dwconv2d_win_kernel(
     const int64_t idx = (int64_t)blockIdx.x * kDThreads + threadIdx.x;
     if (idx >= total) return;
     const int64_t c4 = idx % C4;
-    const int64_t rb = (idx / C4) % RB;
-    const int64_t bw = (idx / (C4 * RB)) % pw;
-    const int64_t bh = ((idx / (C4 * RB * pw)) % phb) * RB + rb;
-    const int64_t n = idx / (C4 * RB * pw * phb);
+    const int64_t q = idx / C4;                       // RB is 1 or a power of two: no division for it
+    const int sh = RB > 1 ? 31 - __builtin_clz((unsigned)RB) : 0;
+    const int64_t rb = q & (RB - 1), q2 = q >> sh;
+    const int64_t bw = q2 % pw, q3 = q2 / pw;
+    const int64_t bh = (q3 % phb) * RB + rb;
+    const int64_t n = q3 / phb;
     if (bh >= ph) return;
     const int64_t h0 = (bh / G) * (G * TH) + bh % G, w0 = (bw / G) * (G * TW) + bw % G;
     if (h0 >= OH || w0 >= OW) return;
@@ -219,10 +221,12 @@ __global__ __launch_bounds__(kDThreads) void dwconv_rows_kernel(
     const int64_t idx = (int64_t)blockIdx.x * kDThreads + threadIdx.x;
     if (idx >= total) return;
     const int64_t cg = idx % CG;
-    const int64_t r = (idx / CG) % RB;
-    const int64_t run = (idx / (CG * RB)) % runs;
-    const int64_t ohb = (idx / (CG * RB * runs)) % OHB;
-    const int64_t n = idx / (CG * RB * runs * OHB);
+    const int64_t q = idx / CG;                       // RB is 1 or a power of two: no division for it
+    const int sh = RB > 1 ? 31 - __builtin_clz((unsigned)RB) : 0;
+    const int64_t r = q & (RB - 1), q2 = q >> sh;
+    const int64_t run = q2 % runs, q3 = q2 / runs;
+    const int64_t ohb = q3 % OHB;
+    const int64_t n = q3 / OHB;
     const int64_t oh = ohb * RB + r;
     if (oh >= OH) return;
     const int64_t w0 = run * TW;
