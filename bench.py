@@ -34,8 +34,8 @@ HBM_PEAK = 8.0e12              # bytes/s
 TRAFFIC = {
     "kernel": "gemm_128x128",
     "source_sha256": "cf36c538c364fffe9ff1b0f5559f684526a3bbe23488427f2e4eefbec77672fb",
-    "fetch_bytes": 2499489382,       # 1220453.8 KiB read by FETCH_SIZE x 2.0 (copy-kernel calibration)
-    "write_bytes": 123032986,        # 120149.4 KiB read by WRITE_SIZE x 1.0
+    "fetch_bytes": 2501152154,       # 1221265.7 KiB read by FETCH_SIZE x 2.0 (copy-kernel calibration)
+    "write_bytes": 123033088,        # 120149.5 KiB read by WRITE_SIZE x 1.0
 }
 KERNEL_SOURCE = os.path.join(ROOT, "paper_2202_03293_amd", "csrc", "gemm_kernel.hpp")
 
