@@ -5,8 +5,9 @@
  * Conventions shared by every entry point
  * ---------------------------------------
  *  - Every data pointer is a DEVICE pointer to fp32 elements owned by the
- *    caller.  The library never allocates, frees or retains device memory and
- *    keeps no state between calls.
+ *    caller.  The library never allocates, frees or retains device memory.
+ *    Between calls it keeps no state that results depend on (per process it
+ *    remembers which kernels it has configured on which device).
  *  - Extents, strides and leading dimensions are in ELEMENTS (int64_t).  A
  *    tensor is row-major: the last index is contiguous.  Operands follow the
  *    memref convention of Section 2.3 (pointer + sizes + strides); only the
@@ -17,8 +18,18 @@
  *    `accumulate` == 0 the output is overwritten and never read; with
  *    `accumulate` != 0 the computed value is added to what it holds.
  *  - Inputs must not overlap outputs.
- *  - Return value: LG_OK or a negative LG_ERR_* code.  Nothing is enqueued
- *    when an error is returned.  The library never aborts, throws or prints.
+ *  - Return value: LG_OK or a negative LG_ERR_* code.  Arguments, workspace
+ *    and launch limits of every kernel of a call are checked before the first
+ *    kernel is enqueued: with LG_ERR_INVALID_ARG, LG_ERR_UNSUPPORTED or
+ *    LG_ERR_WORKSPACE nothing has been enqueued.  LG_ERR_RUNTIME means the HIP
+ *    runtime refused a launch; an op made of two kernels (a split reduction or
+ *    contraction and the pass that combines its partial results) may then have
+ *    its first kernel on the stream and the output must be taken as undefined.
+ *    The library never aborts, throws or prints.
+ *  - The HIP runtime keeps one "last error" per host thread, shared by all its
+ *    users in the process.  An entry point that launches clears it on entry
+ *    (an error another library left pending on the calling thread is dropped,
+ *    not reported as this library's) and reads it after its own launches.
  *  - An output with a zero extent is a successful no-op.  A zero REDUCTION
  *    extent yields the neutral element 0 (or leaves an accumulated output
  *    unchanged), cf. the neutral padding value of Section 3.2.
@@ -26,6 +37,7 @@
  *    least the byte count the matching *_workspace_bytes() call returns (which
  *    may be 0, in which case NULL is accepted).  Its contents on entry are
  *    irrelevant and it may be reused once the stream has passed the call.
+ *    It must not overlap any operand of the call (LG_ERR_INVALID_ARG).
  *  - Fast paths need 16-byte aligned base pointers and row lengths / leading
  *    dimensions that are multiples of 4 elements; anything else is handled by
  *    slower element-wise kernels with identical results, not rejected.
@@ -91,6 +103,11 @@ int lg_matmul_t(const float *A, const float *B, float *C,
  * M = N*OH*OW, N = F, K = KH*KW*C) picks for a shape: the workgroup tile block_m x block_n
  * and the number of k-slabs (1 = no split, no workspace).  Host-only query for tools that
  * attribute kernel time to shapes; any of the three output pointers may be NULL.
+ * The answer is the planner's choice from the three extents.  What only the call itself can
+ * see is not reflected: operands whose pitches or base addresses rule out 128-bit access or
+ * exceed a kernel's 32-bit offsets fall back to the 64 x 64 tile, unsplit, and a product with
+ * N <= 4 and M, K >= 1024 (a matrix times a few vectors) runs on a row-reduction kernel that
+ * has no tile at all.
  */
 int lg_matmul_plan(int64_t M, int64_t N, int64_t K, int *block_m, int *block_n, int *k_splits);
 

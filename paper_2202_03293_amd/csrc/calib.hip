@@ -53,6 +53,6 @@ extern "C" int lg_mfma_probe(float* out, int64_t out_elems, int64_t iters, void*
     if (iters < 0 || iters > kProbeMaxIters || out_elems < 0) return LG_ERR_INVALID_ARG;
     if (!out || out_elems < lg_mfma_probe_out_elems()) return LG_ERR_INVALID_ARG;
     hipLaunchKernelGGL(mfma_probe_kernel, dim3(kProbeGroups), dim3(kProbeThreads), 0,
-                       static_cast<hipStream_t>(stream), out, (int)iters);
+                       begin_call(stream), out, (int)iters);
     return launch_status();
 }

@@ -326,7 +326,7 @@ static int dwconv_dispatch(const float* I, const float* Kf, float* O,
     const int64_t in_elems = N * H * W * C, out_elems = N * OH * OW * C;
     if (overlaps(I, in_elems * 4, O, out_elems * 4) || overlaps(Kf, KH * KW * C * 4, O, out_elems * 4))
         return LG_ERR_INVALID_ARG;
-    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipStream_t s = begin_call(stream);
     const bool vec = (C % 4 == 0) && aligned16(I) && aligned16(Kf) && aligned16(O);
     const bool sd12 = SW >= 1 && SW <= 2 && DW >= 1 && DW <= 2;
     if (vec && KH == 1 && SH == 1 && DH == 1 && sd12 && (KW == 3 || KW == 5 || KW == 7)) {

@@ -53,6 +53,20 @@ static bool forced_plan(int64_t M, int64_t N, int64_t K, int variant, int k_spli
     return true;
 }
 
+// bytes from an operand's base to the end of its last element, as stored
+static int64_t operand_bytes_a(const GemmArgs& a, Layout layout) {
+    if (layout == Layout::CONV) {                  // dense NHWC input: batch = M / (OH * OW)
+        const int64_t n = a.M / (a.g.OH * a.g.OW);
+        return n * a.g.H * a.g.W * a.g.C * 4;
+    }
+    const int64_t rows = layout == Layout::TN ? a.K : a.M, cols = layout == Layout::TN ? a.M : a.K;
+    return ((rows - 1) * a.lda + cols) * 4;
+}
+static int64_t operand_bytes_b(const GemmArgs& a, Layout layout) {
+    const int64_t rows = layout == Layout::NT ? a.N : a.K, cols = layout == Layout::NT ? a.K : a.N;
+    return ((rows - 1) * a.ldb + cols) * 4;
+}
+
 static int run_plan(GemmArgs a, Layout layout, bool vec, const Plan& pl, int user_accumulate, void* workspace,
                     size_t workspace_bytes, hipStream_t s) {
     if (pl.direct_nbw > 0) {
@@ -63,8 +77,15 @@ static int run_plan(GemmArgs a, Layout layout, bool vec, const Plan& pl, int use
     if (need > 0) {
         if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
             return LG_ERR_WORKSPACE;
+        // partial sums written over an operand or the output would give wrong numbers, not an error
+        if (overlaps(workspace, (int64_t)need, a.C, ((a.M - 1) * a.ldc + a.N) * 4) ||
+            overlaps(workspace, (int64_t)need, a.A, operand_bytes_a(a, layout)) ||
+            overlaps(workspace, (int64_t)need, a.B, operand_bytes_b(a, layout)))
+            return LG_ERR_INVALID_ARG;
     }
+    // every launch of the call is checked against the grid limits before the first one is enqueued
     if (pl.tiles_m * pl.tiles_n > kMaxGrid || pl.splits > 65535) return LG_ERR_UNSUPPORTED;
+    if (pl.splits > 1 && cdiv(a.M * a.N, 256) > kMaxGrid) return LG_ERR_UNSUPPORTED;
     float* Cfinal = a.C;
     const int64_t ldc_final = a.ldc;
     a.tiles_m = (unsigned)pl.tiles_m;
@@ -86,7 +107,6 @@ static int run_plan(GemmArgs a, Layout layout, bool vec, const Plan& pl, int use
     if (launch_status() != LG_OK) return LG_ERR_RUNTIME;
     if (pl.splits > 1) {
         const int64_t blocks = cdiv(a.M * a.N, 256);
-        if (blocks > kMaxGrid) return LG_ERR_UNSUPPORTED;
         hipLaunchKernelGGL(splitk_combine_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
                            static_cast<const float*>(workspace), Cfinal, a.M, a.N, ldc_final, (int)pl.splits,
                            user_accumulate);
@@ -173,7 +193,7 @@ static int matmul_impl(const float* A, const float* B, float* C, int64_t M, int6
     if (transA && transB) return LG_ERR_UNSUPPORTED;
     if (M == 0 || N == 0) return LG_OK;
     if (!C || (K > 0 && (!A || !B))) return LG_ERR_INVALID_ARG;
-    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipStream_t s = begin_call(stream);
     const int64_t c_bytes = ((M - 1) * ldc + N) * 4;
     if (K == 0) return accumulate ? LG_OK : zero_output(C, M, N, ldc, s);
     if (overlaps(A, ((a_rows - 1) * lda + a_cols) * 4, C, c_bytes) ||
@@ -271,7 +291,7 @@ static int conv2d_impl(const float* I, const float* Kf, float* O,
     const int64_t OH = lg_conv_out_extent(H, KH, SH, DH), OW = lg_conv_out_extent(W, KW, SW, DW);
     if (OH == 0 || OW == 0) return LG_ERR_INVALID_ARG;
     if (!O || (C > 0 && (!I || !Kf))) return LG_ERR_INVALID_ARG;
-    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipStream_t s = begin_call(stream);
     const int64_t M = N * OH * OW, Kg = KH * KW * C;
     if (Kg == 0) return accumulate ? LG_OK : zero_output(O, M, F, F, s);
     if (overlaps(I, N * H * W * C * 4, O, M * F * 4) || overlaps(Kf, Kg * F * 4, O, M * F * 4))

@@ -45,14 +45,14 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
 // dma_wait<N>() followed by a workgroup barrier before the data is read.
 __device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t lds) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds), "v"(voff), "s"(base) : "memory");
+                 :: "s"(lds), "v"(voff), "s"(base) : "memory", "m0");
 }
 
 // The same with 4 bytes per lane (lane l's word lands at lds + 4*l): for operands whose rows are not
 // 16-byte aligned.  Four times the instructions for the same bytes.
 __device__ __forceinline__ void dma4(const void* base, uint32_t voff, uint32_t lds) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
-                 :: "s"(lds), "v"(voff), "s"(base) : "memory");
+                 :: "s"(lds), "v"(voff), "s"(base) : "memory", "m0");
 }
 
 // Wait until at most N of this wave's global->LDS transfers are still in flight.

@@ -32,6 +32,15 @@ inline void allow_dynamic_lds(const void* kernel, size_t bytes, bool* done) {
     if (dev >= 0) done[dev] = true;
 }
 
+// The runtime keeps one "last error" per host thread, shared with every other user of HIP in the
+// process.  An entry point that launches takes its stream through begin_call(), which clears
+// whatever an earlier caller left there, so that launch_status() after a launch reports this
+// library's launches only.
+inline hipStream_t begin_call(void* stream) {
+    (void)hipGetLastError();
+    return static_cast<hipStream_t>(stream);
+}
+
 inline int launch_status() { return hipGetLastError() == hipSuccess ? LG_OK : LG_ERR_RUNTIME; }
 
 // Workgroups are handed to the 8 XCDs round-robin (hardware id i runs on XCD i % 8) and each XCD

@@ -173,7 +173,7 @@ extern "C" int lg_copy2d(const float* in, float* out, int64_t R, int64_t Cn,
     if (R == 0 || Cn == 0) return LG_OK;
     if (!in || !out) return LG_ERR_INVALID_ARG;
     if (overlaps(in, ((R - 1) * ld_in + Cn) * 4, out, ((R - 1) * ld_out + Cn) * 4)) return LG_ERR_INVALID_ARG;
-    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipStream_t s = begin_call(stream);
     if (ld_in == Cn && ld_out == Cn) {   // dense: one long row
         Cn *= R; R = 1; ld_in = ld_out = Cn;
         // a long dense array whose length is not a multiple of 4: the 128-bit body, then the last 1-3 floats
@@ -233,7 +233,7 @@ __global__ __launch_bounds__(256) void transpose_thin_kernel(
 
 static int transpose_dispatch(const float* in, float* out, int64_t R, int64_t Cn, int64_t ld_in, int64_t ld_out,
                               int64_t B0, int64_t B1, BatchStrides bs, bool vec, void* stream) {
-    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipStream_t s = begin_call(stream);
     auto* i32 = reinterpret_cast<const uint32_t*>(in);
     auto* o32 = reinterpret_cast<uint32_t*>(out);
     if (R < 16 || Cn < 16) {                       // e.g. NHWC <-> NCHW with three channels, as a batch over N

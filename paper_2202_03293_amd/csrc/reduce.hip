@@ -390,7 +390,7 @@ extern "C" int lg_reduce_rows_ws(const float* in, float* out, int64_t R, int64_t
     if (R == 0) return LG_OK;
     if (!out || (Cn > 0 && !in)) return LG_ERR_INVALID_ARG;
     if (Cn > 0 && overlaps(in, ((R - 1) * ld + Cn) * 4, out, R * 4)) return LG_ERR_INVALID_ARG;
-    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipStream_t s = begin_call(stream);
     const RowPlan pl = plan_rows(R, Cn);
     if (pl.P <= 1) return reduce_rows_impl(in, out, R, Cn, ld, accumulate, s);
     const size_t need = (size_t)(R * pl.P) * sizeof(float);
@@ -415,7 +415,7 @@ extern "C" int lg_reduce_rows(const float* in, float* out, int64_t R, int64_t Cn
     if (R == 0) return LG_OK;
     if (!out || (Cn > 0 && !in)) return LG_ERR_INVALID_ARG;
     if (Cn > 0 && overlaps(in, ((R - 1) * ld + Cn) * 4, out, R * 4)) return LG_ERR_INVALID_ARG;
-    return reduce_rows_impl(in, out, R, Cn, ld, accumulate, static_cast<hipStream_t>(stream));
+    return reduce_rows_impl(in, out, R, Cn, ld, accumulate, begin_call(stream));
 }
 
 namespace lg {
@@ -460,37 +460,18 @@ extern "C" size_t lg_reduce_cols_workspace_bytes(int64_t R, int64_t Cn) {
     return p.splits > 1 ? (size_t)(p.splits * p.ldp) * sizeof(float) : 0;
 }
 
-extern "C" int lg_reduce_cols(const float* in, float* out, int64_t R, int64_t Cn, int64_t ld,
-                              int accumulate, void* workspace, size_t workspace_bytes, void* stream) {
-    using namespace lg;
-    if (R < 0 || Cn < 0 || ld < Cn) return LG_ERR_INVALID_ARG;
-    if (Cn == 0) return LG_OK;
-    if (!out || (R > 0 && !in)) return LG_ERR_INVALID_ARG;
-    if (R > 0 && overlaps(in, ((R - 1) * ld + Cn) * 4, out, Cn * 4)) return LG_ERR_INVALID_ARG;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (R == 0) {
-        if (!accumulate) {
-            const int64_t blocks = cdiv(Cn, 256);
-            if (blocks > kMaxGrid) return LG_ERR_UNSUPPORTED;
-            hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s, out, Cn);
-            return launch_status();
-        }
-        return LG_OK;
-    }
-    const ColPlan p = plan_cols(R, Cn);
-    const size_t need = p.splits > 1 ? (size_t)(p.splits * p.ldp) * sizeof(float) : 0;
-    if (need > 0) {
-        if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
-            return LG_ERR_WORKSPACE;
-        if (overlaps(workspace, (int64_t)need, out, Cn * 4) ||
-            overlaps(workspace, (int64_t)need, in, ((R - 1) * ld + Cn) * 4))
-            return LG_ERR_INVALID_ARG;
-    }
+namespace lg {
+
+// Both column-reduction entry points: argument checks, plan, stage 1 and (when the rows are split)
+// stage 2.  `partial` is the scratch for the chunk sums; the caller has checked that it is there,
+// large enough and clear of the operands whenever the plan splits the rows.
+static int reduce_cols_impl(const float* in, float* out, int64_t R, int64_t Cn, int64_t ld,
+                            int accumulate, float* partial, const ColPlan& p, hipStream_t s) {
     const bool vec = (Cn % 4 == 0) && (ld % 4 == 0) && aligned16(in);
     const int64_t bx = cdiv(Cn, vec ? 256 : 64);
     if (bx > kMaxGrid || cdiv(Cn, 64) > kMaxGrid || p.splits > 65535) return LG_ERR_UNSUPPORTED;
     const dim3 g((unsigned)bx, (unsigned)p.splits), b(kRThreads), b16(1024);
-    float* dst = p.splits > 1 ? static_cast<float*>(workspace) : out;
+    float* dst = p.splits > 1 ? partial : out;
     const int64_t ldp = p.splits > 1 ? p.ldp : 0;
     const int facc = p.splits > 1 ? 0 : accumulate;
     const int64_t accesses = vec ? Cn / 4 : Cn;     // per row
@@ -512,11 +493,54 @@ extern "C" int lg_reduce_cols(const float* in, float* out, int64_t R, int64_t Cn
         const dim3 gc((unsigned)cdiv(Cn, 64));
         if (p.splits > 16)
             hipLaunchKernelGGL(reduce_cols_combine_kernel<16>, gc, dim3(1024), 0, s,
-                               static_cast<const float*>(workspace), out, Cn, p.ldp, (int)p.splits, accumulate);
+                               partial, out, Cn, p.ldp, (int)p.splits, accumulate);
         else
             hipLaunchKernelGGL(reduce_cols_combine_kernel<4>, gc, dim3(256), 0, s,
-                               static_cast<const float*>(workspace), out, Cn, p.ldp, (int)p.splits, accumulate);
+                               partial, out, Cn, p.ldp, (int)p.splits, accumulate);
         return launch_status();
     }
     return LG_OK;
+}
+
+// Argument checks shared by the column-reduction entry points; *done is set when the call is
+// finished (an error, nothing to do, or the zero-row case, which is handled here).
+static int reduce_cols_check(const float* in, float* out, int64_t R, int64_t Cn, int64_t ld,
+                             int accumulate, hipStream_t s, bool* done) {
+    *done = true;
+    if (R < 0 || Cn < 0 || ld < Cn) return LG_ERR_INVALID_ARG;
+    if (Cn == 0) return LG_OK;
+    if (!out || (R > 0 && !in)) return LG_ERR_INVALID_ARG;
+    if (R > 0 && overlaps(in, ((R - 1) * ld + Cn) * 4, out, Cn * 4)) return LG_ERR_INVALID_ARG;
+    if (R == 0) {
+        if (!accumulate) {
+            const int64_t blocks = cdiv(Cn, 256);
+            if (blocks > kMaxGrid) return LG_ERR_UNSUPPORTED;
+            hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s, out, Cn);
+            return launch_status();
+        }
+        return LG_OK;
+    }
+    *done = false;
+    return LG_OK;
+}
+
+}  // namespace lg
+
+extern "C" int lg_reduce_cols(const float* in, float* out, int64_t R, int64_t Cn, int64_t ld,
+                              int accumulate, void* workspace, size_t workspace_bytes, void* stream) {
+    using namespace lg;
+    hipStream_t s = begin_call(stream);
+    bool done;
+    const int rc = reduce_cols_check(in, out, R, Cn, ld, accumulate, s, &done);
+    if (done) return rc;
+    const ColPlan p = plan_cols(R, Cn);
+    const size_t need = p.splits > 1 ? (size_t)(p.splits * p.ldp) * sizeof(float) : 0;
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+            return LG_ERR_WORKSPACE;
+        if (overlaps(workspace, (int64_t)need, out, Cn * 4) ||
+            overlaps(workspace, (int64_t)need, in, ((R - 1) * ld + Cn) * 4))
+            return LG_ERR_INVALID_ARG;
+    }
+    return reduce_cols_impl(in, out, R, Cn, ld, accumulate, static_cast<float*>(workspace), p, s);
 }

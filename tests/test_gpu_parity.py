@@ -143,6 +143,16 @@ def test_matmul_workspace_errors(lg):
     assert e.value.status == -3
     with pytest.raises(lg.LgError):
         lg.lg_matmul_variant(A, B, C, 3, 4, workspace=workspace(need - 4))
+    # a workspace that overlaps an operand or the output would silently corrupt the product: rejected
+    big = torch.zeros(need // 4 + 256 * 256, device="cuda")
+    for victim in ("A", "B", "C"):
+        n = 256 * 1024 if victim != "C" else 256 * 256
+        t = big[:n].view((256, 1024) if victim == "A" else (1024, 256) if victim == "B" else (256, 256))
+        ops = dict(A=A, B=B, C=C)
+        ops[victim] = t
+        with pytest.raises(lg.LgError) as e:
+            lg.lg_matmul_variant(ops["A"], ops["B"], ops["C"], 3, 4, workspace=big[64:64 + need // 4])
+        assert e.value.status == -1, victim
     lg.lg_matmul_variant(A, B, C, 3, 4, workspace=workspace(need))
     sync()
     assert bool((C == 0).all())
