@@ -7,7 +7,8 @@
  *  - Every data pointer is a DEVICE pointer to fp32 elements owned by the
  *    caller.  The library never allocates, frees or retains device memory.
  *    Between calls it keeps no state that results depend on (per process it
- *    remembers which kernels it has configured on which device).
+ *    remembers which kernels it has configured on which device, and
+ *    lg_reduce_cols_static the address of its device array).
  *  - Extents, strides and leading dimensions are in ELEMENTS (int64_t).  A
  *    tensor is row-major: the last index is contiguous.  Operands follow the
  *    memref convention of Section 2.3 (pointer + sizes + strides); only the
@@ -242,6 +243,22 @@ size_t lg_reduce_rows_workspace_bytes(int64_t R, int64_t Cn);
 int lg_reduce_cols(const float *in, float *out, int64_t R, int64_t Cn, int64_t ld,
                    int accumulate, void *workspace, size_t workspace_bytes, void *stream);
 size_t lg_reduce_cols_workspace_bytes(int64_t R, int64_t Cn);
+
+/*
+ * lg_reduce_cols for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation,
+ * arguments, results (bit for bit) and errors as lg_reduce_cols, minus the workspace: the partial
+ * column sums go to a fixed 4 MiB array in device memory that belongs to the library (each GPU the
+ * library runs on holds its own copy from the first call there until the process ends).  The call
+ * allocates and frees nothing.  A shape whose partial sums need more than 4 MiB -- more than
+ * lg_reduce_cols_workspace_bytes(R, Cn) = 4194304 -- is LG_ERR_UNSUPPORTED; nothing is enqueued
+ * then.  All calls on one GPU share that array: calls that may overlap in time on one GPU (two
+ * streams, two host threads) race on it and must be serialised by the caller; calls on one stream
+ * are ordered by the stream.  Nothing in the array has to be cleared between calls: every partial
+ * sum a call reads it has written itself.
+ */
+int lg_reduce_cols_static(const float *in, float *out, int64_t R, int64_t Cn, int64_t ld,
+                          int accumulate, void *stream);
 
 /*
  * 2-D transpose, Section 4.4 (Transpose2D):   out[j,i] = in[i,j]

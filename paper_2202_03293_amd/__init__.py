@@ -13,6 +13,7 @@ from .ops import (  # noqa: F401
     lg_conv2d_nhwc_hwcf, lg_conv2d_workspace_bytes, lg_conv1d_nwc_wcf, lg_conv1d_workspace_bytes,
     lg_dwconv1d_nwc_wc, lg_dwconv2d_nhwc_hwc,
     lg_reduce_rows, lg_reduce_rows_ws, lg_reduce_rows_workspace_bytes, lg_reduce_cols, lg_reduce_cols_workspace_bytes,
+    lg_reduce_cols_static,
     lg_transpose, lg_transpose_batched, lg_copy2d,
     lg_mfma_probe, lg_mfma_probe_out_elems, lg_mfma_probe_flops,
 )

@@ -3,6 +3,7 @@
 // Both keep every fp32 running sum short: a lane adds at most a few dozen values before its
 // partial enters a tree (cross-lane for rows, cross-wave / cross-workgroup for columns).
 #include "lg_common.hpp"
+#include <mutex>
 
 namespace lg {
 
@@ -543,4 +544,51 @@ extern "C" int lg_reduce_cols(const float* in, float* out, int64_t R, int64_t Cn
             return LG_ERR_INVALID_ARG;
     }
     return reduce_cols_impl(in, out, R, Cn, ld, accumulate, static_cast<float*>(workspace), p, s);
+}
+
+// ---- lg_reduce_cols for callers that cannot allocate ---------------------------------------------
+// The chunk sums go to a fixed array in device memory that belongs to the library instead of a
+// workspace the caller brings.  Every GPU the library runs on holds its own copy of the array (at
+// its own address) until the process ends; the array's name below is only the host-side handle of
+// the symbol, so host code asks the runtime once per device for the device address and passes that
+// to the kernels.
+namespace lg {
+
+constexpr size_t kStaticScratchBytes = (size_t)4 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// device address of `scratch` on the current device, looked up on the first call there
+static int static_scratch(float** ptr) {
+    static std::mutex mu;
+    static void* addr[kMaxDevices] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LG_ERR_RUNTIME;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!addr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return LG_ERR_RUNTIME;
+        addr[dev] = p;
+    }
+    *ptr = static_cast<float*>(addr[dev]);
+    return LG_OK;
+}
+
+}  // namespace lg
+
+extern "C" int lg_reduce_cols_static(const float* in, float* out, int64_t R, int64_t Cn, int64_t ld,
+                                     int accumulate, void* stream) {
+    using namespace lg;
+    hipStream_t s = begin_call(stream);
+    bool done;
+    const int rc = reduce_cols_check(in, out, R, Cn, ld, accumulate, s, &done);
+    if (done) return rc;
+    const ColPlan p = plan_cols(R, Cn);
+    const size_t need = p.splits > 1 ? (size_t)(p.splits * p.ldp) * sizeof(float) : 0;
+    if (need > kStaticScratchBytes) return LG_ERR_UNSUPPORTED;
+    float* partial = nullptr;
+    if (need > 0) {
+        const int sc = static_scratch(&partial);
+        if (sc != LG_OK) return sc;
+    }
+    return reduce_cols_impl(in, out, R, Cn, ld, accumulate, partial, p, s);
 }

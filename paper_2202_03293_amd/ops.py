@@ -37,6 +37,7 @@ _SIGNATURES = {
     "lg_reduce_rows_workspace_bytes": (_sz, [_i64] * 2),
     "lg_reduce_cols": (_int, [_vp, _vp] + [_i64] * 3 + [_int, _vp, _sz, _vp]),
     "lg_reduce_cols_workspace_bytes": (_sz, [_i64] * 2),
+    "lg_reduce_cols_static": (_int, [_vp, _vp] + [_i64] * 3 + [_int, _vp]),
     "lg_transpose": (_int, [_vp, _vp] + [_i64] * 4 + [_vp]),
     "lg_transpose_batched": (_int, [_vp, _vp] + [_i64] * 10 + [_vp]),
     "lg_copy2d": (_int, [_vp, _vp] + [_i64] * 4 + [_vp]),
@@ -345,6 +346,16 @@ def lg_reduce_cols(x, out, accumulate=False, workspace=None, stream=None):
     wp, wb = _ws(workspace)
     _check("lg_reduce_cols", lib().lg_reduce_cols(_ptr(x), _ptr(out), R, Cn, _ld(x), int(accumulate),
                                                   wp, wb, _stream(stream)))
+    return out
+
+
+def lg_reduce_cols_static(x, out, accumulate=False, stream=None):
+    """lg_reduce_cols without a workspace: partial sums go to the library's own fixed device array."""
+    R, Cn = x.shape
+    if tuple(out.shape) != (Cn,) or not out.is_contiguous():
+        raise ValueError("out must be a dense vector with one entry per column")
+    _check("lg_reduce_cols_static", lib().lg_reduce_cols_static(_ptr(x), _ptr(out), R, Cn, _ld(x), int(accumulate),
+                                                                _stream(stream)))
     return out
 
 

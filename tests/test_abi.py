@@ -66,6 +66,8 @@ def test_argument_validation_without_device(L):
     assert L.lg_reduce_rows(P, Q, 4, 8, 7, 0, None) == -1
     assert L.lg_reduce_cols(P, Q, 4, 8, 7, 0, None, 0, None) == -1
     assert L.lg_reduce_cols(P, Q, 4096, 64, 64, 0, None, 0, None) == -3        # needs a workspace
+    assert L.lg_reduce_cols_static(P, Q, 4, 8, 7, 0, None) == -1
+    assert L.lg_reduce_cols_static(ctypes.c_void_p(1 << 40), Q, 1 << 20, 1280, 1280, 0, None) == -2   # 5 MiB of partial sums
     assert L.lg_transpose(P, Q, 4, 8, 8, 3, None) == -1                        # ld_out < R
     assert L.lg_transpose(P, P, 4, 4, 4, 4, None) == -1                        # in place
     assert L.lg_copy2d(P, Q, 4, 8, 7, 8, None) == -1
