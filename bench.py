@@ -1,16 +1,23 @@
-#!/usr/bin/env python3
 """Benchmark of liblg on one MI355X.
 
-One "step" is one pass of the whole hot path: every op of the library at every shape of the
-benchmark configurations 0..4 (small matmul, memory-bound ops, matmul sweep, conv2d, depthwise conv) on
-seeded synthetic inputs already resident in HBM.  Ops are ordered so that each memory-bound
-launch finds its operands cold (several hundred MiB of other traffic since they were last
-touched, more than the 256 MiB Infinity Cache).
+One "step" is one pass of the whole hot path: one launch of every op at every shape of the
+benchmark configurations 0..4 (small matmul, reductions and transpose, matmul sweep, conv2d,
+depthwise conv) on seeded synthetic inputs already resident in HBM, each op between two HIP
+events on the launch stream.  Ops are ordered so that every operand was last touched more than
+1 GiB of traffic earlier (cold in L2 and in the 256 MiB Infinity Cache) and so that every
+memory-bound op follows a compute-bound contraction (no other kernel's write-back in its way).
 
 Prints ONE JSON line.  `value` is the contraction throughput of the whole step (matmul + conv
 FLOPs divided by the full step time, memory-bound ops included in the time); per-op figures
 against their own rooflines are under `ops`; `roofline` describes the dominant kernel (the MFMA
 GEMM tile the 8192^3 matmul runs on) and `cpu_baseline` the CPU oracle timed on a bounded sample.
+
+Beside the in-step figure every memory-bound op carries `us_cold_rotating`: a batch of
+back-to-back launches that rotates over distinct buffer sets adding up to at least 1 GiB, so no
+launch finds its operands in a cache and no event or launch gap is charged to a 20-90 us kernel.
+`ceilings` holds the measured HBM stream rates (read, write, copy probes of the library) taken
+the same two ways, `extras` the ops outside the configurations (copy2d, transposed-operand
+products, a large convolution, the accumulating shallow product).
 """
 import argparse
 import math
@@ -29,28 +36,35 @@ HBM_PEAK = 8.0e12              # bytes/s
 
 # HBM traffic of the dominant kernel per launch (average over its launches in one step), from two
 # counter runs of this file (FETCH_SIZE, then WRITE_SIZE; commands, raw figures and the calibration
-# against the copy kernel in profiles/bench_step_hbm_traffic.md).  Valid only for the kernel source
-# the counters were taken with: a changed source makes `traffic` null.
+# against the copy kernel in profiles/bench_step_hbm_traffic.md).  Valid only for the kernel and
+# planner sources and the launch plans the counters were taken with: anything else makes `traffic` null.
 TRAFFIC = {
     "kernel": "gemm_128x128",
-    "source_sha256": "cf36c538c364fffe9ff1b0f5559f684526a3bbe23488427f2e4eefbec77672fb",
-    "fetch_bytes": 2501152154,       # 1221265.7 KiB read by FETCH_SIZE x 2.0 (copy-kernel calibration)
-    "write_bytes": 123033088,        # 120149.5 KiB read by WRITE_SIZE x 1.0
+    "source_sha256": None,
+    "plans": None,                   # {"MxNxK": [block_m, block_n, k_splits]} of the launches counted
+    "fetch_bytes": None,
+    "write_bytes": None,
 }
-KERNEL_SOURCE = os.path.join(ROOT, "paper_2202_03293_amd", "csrc", "gemm_kernel.hpp")
+KERNEL_SOURCES = [os.path.join(ROOT, "paper_2202_03293_amd", "csrc", f)
+                  for f in ("gemm_kernel.hpp", "gemm_plan.hpp", "gemm.hip")]
 
 
 def kernel_source_sha256():
     import hashlib
-    with open(KERNEL_SOURCE, "rb") as f:
-        return hashlib.sha256(f.read()).hexdigest()
+    h = hashlib.sha256()
+    for path in KERNEL_SOURCES:
+        with open(path, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
 
 
-def measured_traffic(kernel_name):
+def measured_traffic(kernel_name, plans):
+    """The counted bytes, or None when the kernel, its sources or the plan of any of its launches
+    differ from what the counters were taken with."""
     if TRAFFIC["source_sha256"] is None or TRAFFIC["kernel"] != kernel_name:
         return None
-    if kernel_source_sha256() != TRAFFIC["source_sha256"]:
-        return None              # the kernel changed since the counters were read
+    if kernel_source_sha256() != TRAFFIC["source_sha256"] or TRAFFIC["plans"] != plans:
+        return None
     return dict(fetch_bytes=TRAFFIC["fetch_bytes"], write_bytes=TRAFFIC["write_bytes"],
                 total_bytes=TRAFFIC["fetch_bytes"] + TRAFFIC["write_bytes"])
 
@@ -109,13 +123,16 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     # defaults follow the paper's protocol (Section 4.3): 100 measurements per op after the warm-up,
-    # reported as mean, median and quartiles; a step is ~12 ms, so this is ~1.3 s of GPU time
+    # reported as mean, median and quartiles; a step is ~9 ms, so this is ~1 s of GPU time
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--sweep", action="store_true",
                     help="also time the paper's batch-1 stride/dilation sweep (Sections 4.6.2, 4.7): launch-bound "
                          "problems, reported per launch from batches of back-to-back launches under `sweep`")
+    ap.add_argument("--ceilings-sweep", action="store_true",
+                    help="also sweep the HBM stream probes over workgroup size, words per lane and cache hints "
+                         "(the table behind the quoted ceilings), reported under `ceilings.sweep`")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: liblg runs on ONE GPU only (it has no collectives); "
@@ -139,14 +156,18 @@ def main():
         return torch.empty(nbytes // 4, device="cuda") if nbytes else None
 
     # ------------------------------------------------------------------ build the op list
-    ops = []      # dicts: name, call, flops, bytes, bound, kernel
+    ops = []      # the step: dicts name, call, flops, bytes, bound, kernel
+    extras = []   # ops outside the benchmark configurations, timed after the step
 
-    def add(name, call, flops, nbytes, bound, kernel):
-        ops.append(dict(name=name, call=call, flops=float(flops), bytes=float(nbytes), bound=bound,
-                        kernel=kernel))
+    def add(name, call, flops, nbytes, bound, kernel, to=None, rotate=None):
+        (ops if to is None else to).append(dict(name=name, call=call, flops=float(flops), bytes=float(nbytes),
+                                                bound=bound, kernel=kernel, rotate=rotate))
+
+    def gemm_plan(M, N, K):
+        return list(lg.lg_matmul_plan(M, N, K))
 
     def gemm_kernel_name(M, N, K):
-        bm, bn, sp = lg.lg_matmul_plan(M, N, K)
+        bm, bn, sp = gemm_plan(M, N, K)
         return f"gemm_{bm}x{bn}" + (f"_splitk{sp}" if sp > 1 else "")
 
     host_keep = {}
@@ -217,95 +238,146 @@ def main():
     wt = ws(lg.lg_matmul_workspace_bytes(Mt, Nt, Kt))
     del At_h, Bt_h
 
-    def add_mm(shape):
+    def add_mm(shape, to=None):
         d = mm[shape]
-        add(d["name"], d["call"], d["flops"], d["nbytes"], "mfma", d["kernel"])
+        add(d["name"], d["call"], d["flops"], d["nbytes"], "mfma", d["kernel"], to=to)
 
-    # Order.  Writes of one kernel linger dirty in the Infinity Cache and are paid for by the next
-    # kernel, so (a) the large write-heavy memory-bound ops run as one chain, each preceded by another
-    # write-heavy op of its own size as in a steady state (copy2d, the bandwidth yardstick, heads the
-    # chain and starts from clean caches), (b) a compute-bound GEMM follows the chain and absorbs
-    # its write-back, (c) the read-only reductions follow GEMMs with small outputs.  Every operand was
-    # last touched > 1 GiB of traffic ago, i.e. it is cold in L2 and in the Infinity Cache.
-    add("copy2d_8192x8192", lambda: lg.lg_copy2d(x_cp, y_cp), 0, 8.0 * x_cp.numel(), "hbm", "copy2d")
-    add("transpose_8192x8192", lambda: lg.lg_transpose(x_tr, y_tr), 0, 8.0 * x_tr.numel(), "hbm", "transpose")
+    def add_conv(c, to=None):
+        add(c["name"], c["call"], c["flops"], c["nbytes"], "mfma", c["kernel"], to=to)
+
+    # Buffer sets for the rotating cold measurement of a memory-bound op: `make()` clones the op's
+    # operands (same values, other addresses) and returns the call on the clone; at least four sets
+    # and at least 2 GiB in all (eight times the Infinity Cache, so that nothing read by one launch
+    # survives until its set comes round again, whichever hints keep the outputs out of the caches).
+    def rotation(nbytes, make):
+        return dict(sets=max(4, math.ceil((2 << 30) / nbytes)), make=make)
+
+    tr_bytes, red_bytes = 8.0 * x_tr.numel(), 4.0 * (R * Cn)
+    dw1_bytes = 4.0 * (O1.numel() + K1.numel() + I1.numel())
+    dw2_bytes = 4.0 * (O2.numel() + K2.numel() + I2.numel())
+
+    def mk_transpose():
+        x, y = x_tr.clone(), torch.empty_like(y_tr)
+        return lambda: lg.lg_transpose(x, y)
+
+    def mk_copy():
+        x, y = x_cp.clone(), torch.empty_like(y_cp)
+        return lambda: lg.lg_copy2d(x, y)
+
+    def mk_rows():
+        x, y = x_rows.clone(), torch.empty_like(out_rows)
+        return lambda: lg.lg_reduce_rows(x, y)
+
+    def mk_cols():
+        x, y, w = x_cols.clone(), torch.empty_like(out_cols), ws(lg.lg_reduce_cols_workspace_bytes(R, Cn))
+        return lambda: lg.lg_reduce_cols(x, y, workspace=w)
+
+    def mk_dw1():
+        x, y = I1.clone(), torch.empty_like(O1)
+        return lambda: lg.lg_dwconv1d_nwc_wc(x, K1, y)
+
+    def mk_dw2():
+        x, y = I2.clone(), torch.empty_like(O2)
+        return lambda: lg.lg_dwconv2d_nhwc_hwc(x, K2, y)
+
+    # Order.  Writes of one kernel linger dirty in L2 and the Infinity Cache and are paid for by the
+    # kernels after it, so every memory-bound op directly follows a contraction (compute-bound, its
+    # output streamed past the caches): it starts with clean caches and with operands that are cold
+    # (last touched a whole step, > 1 GiB of traffic, ago), and the two ops that leave hundreds of MB
+    # of output behind (transpose, 1-D depthwise) are each followed by the largest products, which flush most of it.
+    add_mm((4096, 4096, 4096))
+    add("transpose_8192x8192", lambda: lg.lg_transpose(x_tr, y_tr), 0, tr_bytes, "hbm", "transpose",
+        rotate=rotation(tr_bytes, mk_transpose))
+    add_mm((8192, 8192, 8192))
     # depthwise bytes follow the paper's accounting: output written, filter read, input read once
     add("dwconv1d_n32w4098c512k3", lambda: lg.lg_dwconv1d_nwc_wc(I1, K1, O1), 2.0 * O1.numel() * k1,
-        4.0 * (O1.numel() + K1.numel() + I1.numel()), "hbm", "dwconv1d")
-    add_mm((4096, 4096, 4096))
+        dw1_bytes, "hbm", "dwconv1d", rotate=rotation(dw1_bytes, mk_dw1))
     add_mm((16384, 512, 2048))
-    for c in convs[:-1]:
-        add(c["name"], c["call"], c["flops"], c["nbytes"], "mfma", c["kernel"])
     add("reduce_rows_4096x16384", lambda: lg.lg_reduce_rows(x_rows, out_rows), R * Cn, 4.0 * (R * Cn + R), "hbm",
-        "reduce_rows")
+        "reduce_rows", rotate=rotation(red_bytes, mk_rows))
+    add_conv(convs[0])
     add("reduce_cols_4096x16384", lambda: lg.lg_reduce_cols(x_cols, out_cols, workspace=ws_cols), R * Cn,
-        4.0 * (R * Cn + Cn), "hbm", "reduce_cols")
-    # the 2-D depthwise op is small (77 MB): right after the 1-D one it would spend its time behind the
-    # write-back of that kernel's 268 MB; here its operands are just as cold and the caches are clean
-    add("dwconv2d_n8h114c96k3", lambda: lg.lg_dwconv2d_nhwc_hwc(I2, K2, O2), 2.0 * O2.numel() * kh2 * kw2,
-        4.0 * (O2.numel() + K2.numel() + I2.numel()), "hbm", "dwconv2d")
-    add_mm((8192, 8192, 8192))
-    c = convs[-1]            # the large conv: what the implicit GEMM does once the machine is full
-    add(c["name"], c["call"], c["flops"], c["nbytes"], "mfma", c["kernel"])
-    add("matmul_AtB_4096x4096x4096", lambda: lg.lg_matmul_t(At_d, Bn_d, Ct_d, trans_a=True, workspace=wt),
-        2.0 * Mt * Nt * Kt, 12.0 * Mt * Nt, "mfma", gemm_kernel_name(Mt, Nt, Kt) + "_tn")
-    add("matmul_ABt_4096x4096x4096", lambda: lg.lg_matmul_t(An_d, Bt_d, Ct_d, trans_b=True, workspace=wt),
-        2.0 * Mt * Nt * Kt, 12.0 * Mt * Nt, "mfma", gemm_kernel_name(Mt, Nt, Kt) + "_nt")
+        4.0 * (R * Cn + Cn), "hbm", "reduce_cols", rotate=rotation(red_bytes, mk_cols))
+    add_conv(convs[1])
+    add_conv(convs[2])
     add_mm((1024, 1024, 1024))
     add_mm((4096, 4096, 64))
-    # the same shallow product accumulating into C: the output is read as well as written, which
-    # halves the arithmetic intensity and puts the op on the HBM side of the ridge
+    add("dwconv2d_n8h114c96k3", lambda: lg.lg_dwconv2d_nhwc_hwc(I2, K2, O2), 2.0 * O2.numel() * kh2 * kw2,
+        dw2_bytes, "hbm", "dwconv2d", rotate=rotation(dw2_bytes, mk_dw2))
+    add_mm(si.MATMUL_SMALL)          # configuration 0: 0.2 us of math, a launch-latency figure
+
+    # Outside the configurations: the copy yardstick, the transposed-operand products, a convolution
+    # large enough to fill the machine, and the shallow product accumulating into C (the output is
+    # read as well as written, which halves the arithmetic intensity: the HBM side of the ridge).
+    add_mm((4096, 4096, 4096), to=extras)      # predecessor of the copy, as in the step; not reported twice
+    add("copy2d_8192x8192", lambda: lg.lg_copy2d(x_cp, y_cp), 0, 8.0 * x_cp.numel(), "hbm", "copy2d", to=extras,
+        rotate=rotation(8.0 * x_cp.numel(), mk_copy))
+    add_conv(convs[3], to=extras)
+    add("matmul_AtB_4096x4096x4096", lambda: lg.lg_matmul_t(At_d, Bn_d, Ct_d, trans_a=True, workspace=wt),
+        2.0 * Mt * Nt * Kt, 12.0 * Mt * Nt, "mfma", gemm_kernel_name(Mt, Nt, Kt) + "_tn", to=extras)
+    add("matmul_ABt_4096x4096x4096", lambda: lg.lg_matmul_t(An_d, Bt_d, Ct_d, trans_b=True, workspace=wt),
+        2.0 * Mt * Nt * Kt, 12.0 * Mt * Nt, "mfma", gemm_kernel_name(Mt, Nt, Kt) + "_nt", to=extras)
     d64 = mm[(4096, 4096, 64)]
     A64, B64 = d64["operands"]
     C64acc = torch.zeros((4096, 4096), device="cuda")
     add("matmul_4096x4096x64_accumulate", lambda: lg.lg_matmul(A64, B64, C64acc, accumulate=True), d64["flops"],
-        4.0 * (2 * 4096 * 64 + 2 * 4096 * 4096), "mfma", d64["kernel"] + "_acc")
-    add_mm(si.MATMUL_SMALL)          # configuration 0: 0.2 us of math, a launch-latency figure
+        4.0 * (2 * 4096 * 64 + 2 * 4096 * 4096), "mfma", d64["kernel"] + "_acc", to=extras)
 
     # ------------------------------------------------------------------ run
-    def step(events=None):
-        for i, op in enumerate(ops):
+    def run_list(lst, events=None):
+        for i, op in enumerate(lst):
             if events is not None:
                 events[i][0].record(stream)
             op["call"]()
             if events is not None:
                 events[i][1].record(stream)
 
+    def event_grid(lst, n):
+        return [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in lst]
+                for _ in range(n)]
+
     for _ in range(args.warmup):
-        step()
+        run_list(ops)
     torch.cuda.synchronize()
-    all_events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                   for _ in ops] for _ in range(args.steps)]
+    all_events = event_grid(ops, args.steps)
     torch.cuda.synchronize()
     clocks = ClockSampler()
     with clocks:
         t0 = time.perf_counter()
         for k in range(args.steps):
-            step(all_events[k])
+            run_list(ops, all_events[k])
         torch.cuda.synchronize()
         t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
-    per_op = []
-    for i, op in enumerate(ops):
-        ts = np.array([a.elapsed_time(b) for a, b in (ev[i] for ev in all_events)]) * 1e-3
-        mean, med = float(ts.mean()), float(np.median(ts))
-        rec = dict(op=op["name"], kernel=op["kernel"], bound=op["bound"], us_mean=mean * 1e6, us_median=med * 1e6,
-                   us_p25=float(np.percentile(ts, 25)) * 1e6, us_p75=float(np.percentile(ts, 75)) * 1e6)
-        if op["bound"] == "mfma":
-            rec.update(gflops=op["flops"] / mean / 1e9, frac_mfma_peak=op["flops"] / mean / MFMA_FP32_PEAK,
-                       gbps=op["bytes"] / mean / 1e9, frac_hbm_peak=op["bytes"] / mean / HBM_PEAK)
-        else:
-            rec.update(gbps=op["bytes"] / mean / 1e9, frac_hbm_peak=op["bytes"] / mean / HBM_PEAK,
-                       gflops=op["flops"] / mean / 1e9)
-        op["mean_s"] = mean
-        per_op.append(rec)
-    # the measured ceiling for the memory-bound ops: the copy kernel of the same step (the paper,
-    # too, quotes its bandwidth-bound kernels against a measured copy, Section 4.3)
-    copy_gbps = next(r["gbps"] for r in per_op if r["kernel"] == "copy2d")
-    for r in per_op:
-        if r["bound"] == "hbm":
-            r["frac_copy_rate"] = r["gbps"] / copy_gbps
+    def op_records(lst, grid):
+        recs = []
+        for i, op in enumerate(lst):
+            ts = np.array([a.elapsed_time(b) for a, b in (ev[i] for ev in grid)]) * 1e-3
+            mean, med = float(ts.mean()), float(np.median(ts))
+            rec = dict(op=op["name"], kernel=op["kernel"], bound=op["bound"], us_mean=mean * 1e6, us_median=med * 1e6,
+                       us_p25=float(np.percentile(ts, 25)) * 1e6, us_p75=float(np.percentile(ts, 75)) * 1e6)
+            if op["bound"] == "mfma":
+                rec.update(gflops=op["flops"] / mean / 1e9, frac_mfma_peak=op["flops"] / mean / MFMA_FP32_PEAK,
+                           gbps=op["bytes"] / mean / 1e9, frac_hbm_peak=op["bytes"] / mean / HBM_PEAK)
+            else:
+                rec.update(gbps=op["bytes"] / mean / 1e9, frac_hbm_peak=op["bytes"] / mean / HBM_PEAK,
+                           gflops=op["flops"] / mean / 1e9)
+            op["mean_s"] = mean
+            recs.append(rec)
+        return recs
+
+    per_op = op_records(ops, all_events)
+
+    # the ops outside the configurations, the same way (20 passes)
+    for _ in range(3):
+        run_list(extras)
+    extra_events = event_grid(extras, 20)
+    for k in range(20):
+        run_list(extras, extra_events[k])
+    torch.cuda.synchronize()
+    per_extra = op_records(extras, extra_events)[1:]
+    extras = extras[1:]
 
     # the measured ceiling for the contractions: a register-only MFMA issue loop, long enough (~14 ms
     # per launch) for the engine clock to settle -- a one-millisecond launch from idle reads 10 % low
@@ -322,7 +394,7 @@ def main():
         torch.cuda.synchronize()
         probe_ts.append(a.elapsed_time(b) * 1e-3)
     mfma_measured = lg.lg_mfma_probe_flops(probe_iters) / float(np.median(probe_ts))
-    for r in per_op:
+    for r in per_op + per_extra:
         if r["bound"] == "mfma":
             r["frac_mfma_measured"] = r["gflops"] * 1e9 / mfma_measured
 
@@ -341,22 +413,106 @@ def main():
                     achieved=dom_flops / dom_dur / 1e12, peak=MFMA_FP32_PEAK / 1e12, unit="TFLOP/s",
                     frac=dom_flops / dom_dur / MFMA_FP32_PEAK,
                     measured_ceiling=mfma_measured / 1e12, frac_of_measured_ceiling=dom_flops / dom_dur / mfma_measured)
-    tr = measured_traffic(dom_name)
-    # HBM bytes per launch as counted (null once the kernel source differs from the counted one), beside
-    # the operand bytes per launch; the excess is A/B panels streamed once per block of output tiles
+    dom_plans = {op["name"].split("_", 1)[1]: gemm_plan(*[int(v) for v in op["name"].split("_", 1)[1].split("x")])
+                 for op in dom}
+    tr = measured_traffic(dom_name, dom_plans)
+    # HBM bytes per launch as counted (null once the kernel or planner sources or the plan of one of the
+    # launches differ from the counted ones), beside the operand bytes per launch; the excess is A/B
+    # panels streamed once per block of output tiles
     roofline.update(traffic=tr["total_bytes"] if tr else None, traffic_unit="bytes per launch",
                     traffic_fetch_bytes=tr["fetch_bytes"] if tr else None,
                     traffic_write_bytes=tr["write_bytes"] if tr else None,
-                    algorithmic_bytes=sum(op["bytes"] for op in dom) / len(dom))
+                    algorithmic_bytes=sum(op["bytes"] for op in dom) / len(dom), plans=dom_plans,
+                    source_sha256=kernel_source_sha256())
 
     out = dict(metric="matmul/conv GFLOP/s (% fp32 MFMA peak); reduce/transpose GB/s (% HBM peak)",
                value=value, unit="GFLOP/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
                ms_per_step=ms_per_step, higher_is_better=True, scaling="weak", vs_baseline=None,
                dtype="f32", data="synthetic",
-               config=dict(workload="configs[0..4]: matmul 256^3, reduce_rows/cols 4096x16384, transpose (+copy) 8192^2, matmul sweep "
-                                    "(1024^3, 4096^3, 8192^3, 16384x512x2048, 4096x4096x64; A^T B and A B^T at 4096^3), conv2d x3 "
-                                    "(+ one large conv 32x58x58x256->256 3x3), dwconv1d, dwconv2d; one launch of each per step"),
-               frac_mfma_peak=value * 1e9 / MFMA_FP32_PEAK, roofline=roofline, clocks=clocks.summary(), ops=per_op)
+               config=dict(workload="configs[0..4]: matmul 256^3; reduce_rows, reduce_cols 4096x16384; transpose 8192^2; matmul "
+                                    "sweep 1024^3, 4096^3, 8192^3, 16384x512x2048, 4096x4096x64; conv2d x3; dwconv1d; dwconv2d; "
+                                    "one launch of each per step"),
+               frac_mfma_peak=value * 1e9 / MFMA_FP32_PEAK, roofline=roofline, clocks=clocks.summary(), ops=per_op,
+               extras=per_extra)
+
+    # ------------------------------------------------------------------ cold, rotating buffer sets
+    # A batch of back-to-back launches that walks over `sets` distinct copies of the operands (>= 1 GiB
+    # in all, several times the 256 MiB Infinity Cache): every launch finds its operands cold, and no
+    # event or launch gap is charged to it.  Beside it, the same launches one by one between events.
+    def cold_rotating(calls, rounds=3, reps=5):
+        for c in calls:
+            c()
+        torch.cuda.synchronize()
+        batch, single = [], []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            for _ in range(rounds):
+                for c in calls:
+                    c()
+            b.record(stream)
+            torch.cuda.synchronize()
+            batch.append(a.elapsed_time(b) * 1e3 / (rounds * len(calls)))
+        for r in range(max(15, len(calls))):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            calls[r % len(calls)]()
+            b.record(stream)
+            torch.cuda.synchronize()
+            single.append(a.elapsed_time(b) * 1e3)
+        return float(np.median(batch)), float(np.median(single))
+
+    # HBM stream ceilings from the library's probes (lg_stream_probe), at 256 MiB per stream and at
+    # the footprint of the small depthwise op, measured like the ops: rotating batch and one by one.
+    def stream_ceiling(mode, nfloats, threads=256, unroll=1, hint=3):
+        nbytes = 4.0 * nfloats * (2 if mode == "copy" else 1)
+        sets = max(4, math.ceil((2 << 30) / nbytes))
+        sink = torch.zeros(1024, device="cuda")
+        calls = []
+        for _ in range(sets):
+            x = torch.ones(nfloats, device="cuda") if mode != "write" else None
+            y = torch.empty(nfloats, device="cuda") if mode != "read" else sink
+            calls.append(lambda x=x, y=y: lg.lg_stream_probe(mode, x, y, threads=threads, unroll=unroll, hint=hint))
+        b, s1 = cold_rotating(calls)
+        del calls
+        torch.cuda.empty_cache()
+        return dict(mode=mode, bytes=nbytes, threads=threads, words_per_lane=unroll, hint=hint,
+                    us_cold_rotating=b, gbps_cold_rotating=nbytes / b / 1e3, frac_hbm_peak_cold_rotating=nbytes / b / 1e3 / (HBM_PEAK / 1e9),
+                    us_single=s1, gbps_single=nbytes / s1 / 1e3, frac_hbm_peak_single=nbytes / s1 / 1e3 / (HBM_PEAK / 1e9))
+
+    big = (256 << 20) // 4
+    ceilings = dict(read=stream_ceiling("read", big), write=stream_ceiling("write", big), copy=stream_ceiling("copy", big),
+                    copy_at_dwconv2d_size=stream_ceiling("copy", O2.numel()),
+                    note="lg_stream_probe, 256 lanes x one 128-bit word per lane, non-temporal hints on both sides "
+                         "(the best point of the sweep in profiles/hbm_ceilings.md); 256 MiB per stream, and a copy of "
+                         "the 2-D depthwise output's size (its input is 3.6 % larger)")
+    if args.ceilings_sweep:
+        sw = []
+        for mode in ("read", "write", "copy"):
+            for threads in (256, 512, 1024):
+                for unroll in (1, 2, 4, 8):
+                    for hint in ((3, 0) if mode != "copy" else (3, 0, 1, 2)):
+                        if mode == "copy" and unroll == 8:
+                            continue     # 8 words per lane in flight both ways: an order of magnitude slower, says nothing
+                        sw.append(stream_ceiling(mode, big, threads, unroll, hint))
+        ceilings["sweep"] = sw
+    out["ceilings"] = ceilings
+
+    for op, rec in list(zip(ops, per_op)) + list(zip(extras, per_extra)):
+        if op["rotate"] is None:
+            continue
+        calls = [op["rotate"]["make"]() for _ in range(op["rotate"]["sets"])]
+        b, s1 = cold_rotating(calls)
+        del calls
+        torch.cuda.empty_cache()
+        ceil = ceilings["read"] if op["kernel"].startswith("reduce") else \
+            ceilings["copy_at_dwconv2d_size"] if op["kernel"] == "dwconv2d" else ceilings["copy"]
+        rec.update(us_cold_rotating=b, gbps_cold_rotating=op["bytes"] / b / 1e3,
+                   frac_hbm_peak_cold_rotating=op["bytes"] / b / 1e3 / (HBM_PEAK / 1e9),
+                   us_cold_single=s1, buffer_sets=op["rotate"]["sets"],
+                   stream_ceiling=ceil["mode"] + ("" if ceil is not ceilings["copy_at_dwconv2d_size"] else " (same size)"),
+                   frac_of_stream_ceiling_cold_rotating=(op["bytes"] / b) / (ceil["bytes"] / ceil["us_cold_rotating"]),
+                   frac_of_stream_ceiling_in_step=(op["bytes"] / rec["us_mean"]) / (ceil["bytes"] / ceil["us_single"]))
 
     # The memory-bound ops and every op under 50 us once more, 10 / 20 launches back to back on the same buffers: "warm" figures
     # (part of a 256 MiB operand is still in the last-level cache, and no other kernel's write-back
@@ -375,7 +531,7 @@ def main():
             ts.append(a.elapsed_time(b) * 1e3 / batch)
         return float(np.median(ts))
 
-    for op, rec in zip(ops, per_op):
+    for op, rec in list(zip(ops, per_op)) + list(zip(extras, per_extra)):
         if op["bound"] == "hbm" or rec["us_mean"] < 50.0:      # short launches too: event resolution, launch gaps
             rec["us_warm_back_to_back"] = back_to_back_us(op["call"], batch=10 if op["bound"] == "hbm" else 20)
             if op["bound"] == "hbm":

@@ -292,6 +292,23 @@ int64_t lg_mfma_probe_out_elems(void);
 double lg_mfma_probe_flops(int64_t iters);
 
 /*
+ * HBM stream yardsticks (calibration, beside lg_copy2d): the paper quotes its bandwidth-bound
+ * kernels against measured copy bandwidths and their read/write mixes (Section 4.3); these are
+ * the three mixes on this part, with the launch shape and cache hints as parameters so that the
+ * sweep behind a quoted ceiling can be repeated.
+ *   mode 0  read   n floats of `in` are loaded and summed per lane; `out` is a sink of at least
+ *                  1024 floats that is written only if a sum is NaN (never, for finite inputs)
+ *   mode 1  write  n floats of `out` are overwritten with a constant pattern; `in` is ignored
+ *   mode 2  copy   out[i] = in[i] for n floats
+ * n is a multiple of 4 and both pointers are 16-byte aligned device pointers.  Every lane moves
+ * `unroll` (1, 2, 4, 8) 128-bit words, `threads` (256, 512, 1024) apart, of its workgroup's
+ * contiguous chunk.  hint bit 0: loads carry the non-temporal hint; bit 1: stores do.
+ * Anything else is LG_ERR_INVALID_ARG; `in` overlapping what is written likewise.
+ */
+int lg_stream_probe(int mode, const float *in, float *out, int64_t n, int threads, int unroll, int hint,
+                    void *stream);
+
+/*
  * Batched 2-D transpose, Section 4.4: a transpose of more than two dimensions is a set of 2-D
  * transposes at various places in the tensor (the paper's example: [i,j,k,l] -> [k,j,l,i] is
  * j x k transposes of an i x l matrix).  For every b0 < B0, b1 < B1, i < R, j < Cn:

@@ -15,5 +15,5 @@ from .ops import (  # noqa: F401
     lg_reduce_rows, lg_reduce_rows_ws, lg_reduce_rows_workspace_bytes, lg_reduce_cols, lg_reduce_cols_workspace_bytes,
     lg_reduce_cols_static,
     lg_transpose, lg_transpose_batched, lg_copy2d,
-    lg_mfma_probe, lg_mfma_probe_out_elems, lg_mfma_probe_flops,
+    lg_mfma_probe, lg_mfma_probe_out_elems, lg_mfma_probe_flops, lg_stream_probe,
 )

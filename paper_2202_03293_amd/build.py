@@ -29,9 +29,9 @@ def _hipcc():
     return "hipcc"
 
 
-def _compile(src):
-    obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
-    cmd = [_hipcc()] + HIPCC_FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+def _compile(src, obj_dir=OBJ_DIR, extra_flags=()):
+    obj = os.path.join(obj_dir, os.path.splitext(src)[0] + ".o")
+    cmd = [_hipcc()] + HIPCC_FLAGS + list(extra_flags) + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     # the host pass does not know the device-only feature flag; that notice is noise
     log = "\n".join(l for l in r.stdout.splitlines() if "not a recognized feature" not in l)
@@ -40,17 +40,18 @@ def _compile(src):
     return obj, log
 
 
-def build(verbose=False):
-    """Compile every source and link liblg.so; always recompiles."""
-    os.makedirs(OBJ_DIR, exist_ok=True)
+def build(verbose=False, out=OUT, obj_dir=OBJ_DIR, extra_flags=()):
+    """Compile every source and link liblg.so; always recompiles.  `out`, `obj_dir` and `extra_flags`
+    (more hipcc options, e.g. -D overrides of tuning constants) build a second copy elsewhere."""
+    os.makedirs(obj_dir, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        results = list(ex.map(_compile, SOURCES))
+        results = list(ex.map(lambda src: _compile(src, obj_dir, extra_flags), SOURCES))
     for _, log in results:
         if verbose and log.strip():
             print(log)
-    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", OUT] + [o for o, _ in results]
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out] + [o for o, _ in results]
     subprocess.run(cmd, check=True)
-    return OUT
+    return out
 
 
 if __name__ == "__main__":

@@ -167,6 +167,128 @@ __global__ __launch_bounds__(kDThreads) void dwconv2d_win_kernel(
         }
 }
 
+// 2-D, 3 x 3, stride 1, dilation 1, overwriting output, channels in slabs of CS4 quads: tiles through LDS.
+//
+// A workgroup owns TH x TW output pixels of one image for one slab of 4*CS4 channels.  The
+// (TH+2) x (TW+2) input patch it needs -- and the nine filter taps of its channels -- are moved
+// global -> LDS by the lanes' direct transfers (16 bytes each, no registers), all requested up front,
+// so every input element crosses from L2 to the compute unit once per tile instead of once per tap row,
+// and the halo between neighbouring tiles is re-read from the L2 they share (tiles are numbered so
+// that an accelerator die works on one image at a time).  Lane -> (channel quad, column of the tile);
+// it walks down the tile's rows with a 3-row window in registers and streams one output per row.
+//
+// The rows are consumed while the rest of the patch is still in flight.  A wave's memory operations
+// complete in issue order, so "input rows <= r have landed" is "at most (transfers of later rows +
+// stores issued since) are outstanding": an s_waitcnt with a compile-time count per row, then a
+// workgroup barrier (each wave has waited for its own transfers, the barrier publishes everybody's).
+// That count is exact only if every lane issues every store, so all tiles are full: tiles at the
+// bottom and right edge are moved inwards and recompute a few outputs of their neighbours (the same
+// values, bit for bit).  The host sends shapes smaller than a tile, and accumulating calls, elsewhere.
+constexpr int ceil_div_i(int a, int b) { return (a + b - 1) / b; }
+constexpr int min_i(int a, int b) { return a < b ? a : b; }
+
+template <int CS4, int TH, int TW>
+struct Dw2Tile {
+    static constexpr int T = CS4 * TW;                        // lanes: one per (channel quad, column)
+    static constexpr int THp = TH + 2, TWp = TW + 2;
+    static constexpr int ROW = TWp * CS4;                     // 128-bit words per patch row
+    static constexpr int ITEMS = THp * ROW;
+    static constexpr int NL = ceil_div_i(ITEMS, T);           // transfers per lane for the patch
+    static constexpr int KNL = ceil_div_i(9 * CS4, T);        // ... and for the filter
+    static constexpr int LDS_BYTES = (KNL + NL) * T * 16;
+    static_assert(T % kWave == 0 && T <= 1024, "whole wavefronts");
+    static_assert(NL + TH <= 63, "the wait counts must fit s_waitcnt's 6 bits");
+};
+
+template <int CS4, int TH, int TW>
+__global__ __launch_bounds__(CS4 * TW) void dwconv2d_tile_kernel(
+    const float* __restrict__ I, const float* __restrict__ Kf, float* __restrict__ O,
+    int64_t H, int64_t W, int64_t C, int64_t OH, int64_t OW,
+    unsigned ntiles, unsigned tiles_h, unsigned tiles_w, unsigned slabs) {
+    using D = Dw2Tile<CS4, TH, TW>;
+    constexpr int T = D::T, TWp = D::TWp, ROW = D::ROW, ITEMS = D::ITEMS, NL = D::NL, KNL = D::KNL;
+    extern __shared__ __align__(16) float4 dw_lds[];          // [KNL*T] filter taps, then [NL*T] patch
+    float4* kf = dw_lds;
+    float4* patch = dw_lds + KNL * T;
+    const unsigned L = xcd_contiguous_id(blockIdx.x, ntiles);
+    const unsigned slab = L % slabs, tw = (L / slabs) % tiles_w;
+    const unsigned th = (L / (slabs * tiles_w)) % tiles_h, n = L / (slabs * tiles_w * tiles_h);
+    int64_t h0 = (int64_t)th * TH, w0 = (int64_t)tw * TW;
+    if (h0 > OH - TH) h0 = OH - TH;                           // edge tiles move inwards: every tile is full
+    if (w0 > OW - TW) w0 = OW - TW;
+    const int t = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(t / kWave);
+    {
+        const char* kb = reinterpret_cast<const char*>(to_scalar(reinterpret_cast<int64_t>(Kf + slab * CS4 * 4)));
+#pragma unroll
+        for (int i = 0; i < KNL; ++i) {
+            int q = i * T + t;
+            if (q > 9 * CS4 - 1) q = 9 * CS4 - 1;             // spare lanes repeat the last word (LDS has room for them)
+            const int tap = q / CS4, c4 = q - tap * CS4;
+            dma16(kb, (uint32_t)((tap * C + 4 * c4) * 4), lds_addr(kf + i * T + wave * kWave));
+        }
+    }
+    const char* base = reinterpret_cast<const char*>(
+        to_scalar(reinterpret_cast<int64_t>(I + ((n * H + h0) * W + w0) * C + slab * CS4 * 4)));
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+        int q = i * T + t;
+        if (q > ITEMS - 1) q = ITEMS - 1;
+        const int r = q / ROW, rem = q - r * ROW;
+        const int px = rem / CS4, c4 = rem - px * CS4;
+        dma16(base, (uint32_t)(((r * W + px) * C + 4 * c4) * 4), lds_addr(patch + i * T + wave * kWave));
+    }
+    const int c4 = t % CS4, col = t / CS4;
+    float* op = O + ((n * OH + h0) * OW + w0 + col) * C + slab * CS4 * 4 + 4 * c4;
+    float4 k[3][3];
+    float4 x[3][3];
+    static_for<0, TH + 2>([&](auto rc) {
+        constexpr int r = decltype(rc)::value;
+        constexpr int last = min_i(ceil_div_i((r + 1) * ROW, T) - 1, NL - 1);   // last transfer that brings a word of row r
+        constexpr int stores = r >= 2 ? r - 2 : 0;                               // issued by every lane so far
+        dma_wait<min_i(NL - 1 - last + stores, 63)>();
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if constexpr (r == 0) {
+#pragma unroll
+            for (int a = 0; a < 3; ++a)
+#pragma unroll
+                for (int b = 0; b < 3; ++b) k[a][b] = kf[(a * 3 + b) * CS4 + c4];
+        }
+#pragma unroll
+        for (int b = 0; b < 3; ++b) x[r % 3][b] = patch[(r * TWp + col + b) * CS4 + c4];
+        if constexpr (r >= 2) {
+            constexpr int oh = r - 2;
+            float4 s = make_float4(0, 0, 0, 0);
+#pragma unroll
+            for (int a = 0; a < 3; ++a)
+#pragma unroll
+                for (int b = 0; b < 3; ++b) s = fma4(x[(oh + a) % 3][b], k[a][b], s);
+            store_stream4(op + (int64_t)oh * OW * C, s);
+        }
+    });
+}
+
+template <int CS4, int TH, int TW>
+static int launch_dw2_tile(const float* I, const float* Kf, float* O, int64_t N, int64_t H, int64_t W, int64_t C,
+                           int64_t OH, int64_t OW, hipStream_t s) {
+    using D = Dw2Tile<CS4, TH, TW>;
+    const int64_t tiles_h = cdiv(OH, TH), tiles_w = cdiv(OW, TW), slabs = C / (4 * CS4);
+    const int64_t ntiles = N * tiles_h * tiles_w * slabs;
+    if (ntiles > kMaxGrid) return LG_ERR_UNSUPPORTED;
+    static bool configured[kMaxDevices] = {};
+    allow_dynamic_lds(reinterpret_cast<const void*>(&dwconv2d_tile_kernel<CS4, TH, TW>), D::LDS_BYTES, configured);
+    hipLaunchKernelGGL((dwconv2d_tile_kernel<CS4, TH, TW>), dim3((unsigned)ntiles), dim3(D::T), D::LDS_BYTES, s,
+                       I, Kf, O, H, W, C, OH, OW, (unsigned)ntiles, (unsigned)tiles_h, (unsigned)tiles_w, (unsigned)slabs);
+    return launch_status();
+}
+
+// what the tile kernel takes: whole tiles, channel slabs, lane offsets inside a patch within 32 bits
+template <int CS4, int TH, int TW>
+static bool dw2_tile_fits(int64_t W, int64_t C, int64_t OH, int64_t OW) {
+    return C % (4 * CS4) == 0 && OH >= TH && OW >= TW && (TH + 2) * W * C * 4 < ((int64_t)1 << 31);
+}
+
 // Row-streaming kernel for the filters the window kernels do not cover (5x5, 7x7, 1-D widths
 // 2 ... 9): horizontal stride and dilation 1, C % 4 == 0, any filter height, vertical stride and
 // dilation.  A lane owns a run of TW outputs of one output row for 4 channels and walks the filter
@@ -348,6 +470,11 @@ static int dwconv_dispatch(const float* I, const float* Kf, float* O,
         LG_DW1(7, 1, 1) LG_DW1(7, 2, 1) LG_DW1(7, 1, 2) LG_DW1(7, 2, 2)
 #undef LG_DW1
     }
+    // 3 x 3 at stride and dilation 1, overwriting: 8 x 16 pixel tiles x 32 channels through LDS (measured on
+    // 8 x 114 x 114 x 96, cold: 20.7 -> 17.3 us back to back, input fetched from memory 1.47 -> 1.00 times)
+    if (vec && KH == 3 && KW == 3 && SH == 1 && SW == 1 && DH == 1 && DW == 1 && !accumulate &&
+        dw2_tile_fits<8, 8, 16>(W, C, OH, OW))
+        return launch_dw2_tile<8, 8, 16>(I, Kf, O, N, H, W, C, OH, OW, s);
     if (vec && KH == 3 && KW == 3 && SH == SW && DH == DW && sd12) {
         const int64_t G = DW / (SW == DW ? DW : 1);
 #define LG_DW2(S_, D_, TH_, TW_)                                                                             \

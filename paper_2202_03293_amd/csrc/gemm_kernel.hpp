@@ -30,45 +30,6 @@ namespace lg {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef __attribute__((address_space(3))) void lds_void;
-
-// LDS byte address of a pointer into __shared__ memory.
-__device__ __forceinline__ uint32_t lds_addr(const void* p) {
-    return (uint32_t)(uintptr_t)(lds_void*)p;
-}
-
-// One global -> LDS transfer of 16 bytes per lane: lane l's data lands at LDS address lds + 16*l.
-// `base` and `lds` must be wave-uniform; `voff` is the lane's byte offset from base.  Written as
-// inline assembly on purpose: the compiler then neither knows that LDS is being written
-// asynchronously (it would otherwise make every later ds_read wait for ALL transfers in flight,
-// defeating the prefetch) nor orders anything around it, so the caller owns the synchronisation:
-// dma_wait<N>() followed by a workgroup barrier before the data is read.
-__device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t lds) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds), "v"(voff), "s"(base) : "memory", "m0");
-}
-
-// The same with 4 bytes per lane (lane l's word lands at lds + 4*l): for operands whose rows are not
-// 16-byte aligned.  Four times the instructions for the same bytes.
-__device__ __forceinline__ void dma4(const void* base, uint32_t voff, uint32_t lds) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
-                 :: "s"(lds), "v"(voff), "s"(base) : "memory", "m0");
-}
-
-// Wait until at most N of this wave's global->LDS transfers are still in flight.
-template <int N>
-__device__ __forceinline__ void dma_wait() {
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
-// A wave-uniform 64-bit value moved into scalar registers (64-bit divisions leave theirs in vector
-// registers even when every lane holds the same number).
-__device__ __forceinline__ int64_t to_scalar(int64_t v) {
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)v >> 32));
-    return (int64_t)(((uint64_t)hi << 32) | lo);
-}
-
 // BM x BN output tile per workgroup, BK-deep k-slices, WM x WN register tile per wavefront.
 // MINW = wavefronts per SIMD the register allocation must leave room for (what LDS lets a CU hold).
 template <int BM_, int BN_, int BK_, int WM_, int WN_, int MINW_, int STAGES_ = 3, bool KTAIL_ = true>

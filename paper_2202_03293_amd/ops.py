@@ -44,6 +44,7 @@ _SIGNATURES = {
     "lg_mfma_probe": (_int, [_vp, _i64, _i64, _vp]),
     "lg_mfma_probe_out_elems": (_i64, []),
     "lg_mfma_probe_flops": (ctypes.c_double, [_i64]),
+    "lg_stream_probe": (_int, [_int, _vp, _vp, _i64, _int, _int, _int, _vp]),
 }
 
 _lib = None
@@ -388,6 +389,18 @@ def lg_mfma_probe_flops(iters):
 def lg_mfma_probe(out, iters, stream=None):
     """Enqueue the register-only MFMA issue loop; `out` takes one checksum per lane."""
     _check("lg_mfma_probe", lib().lg_mfma_probe(_ptr(out), out.numel(), int(iters), _stream(stream)))
+    return out
+
+
+def lg_stream_probe(mode, x, out, threads=256, unroll=1, hint=3, stream=None):
+    """Enqueue one HBM stream probe: mode "read" (x -> sink), "write" (-> out) or "copy" (x -> out)."""
+    m = {"read": 0, "write": 1, "copy": 2}[mode]
+    n = out.numel() if m == 1 else x.numel()
+    if m == 2 and out.numel() != n:
+        raise ValueError("copy probe: x and out must have the same number of elements")
+    if m == 0 and out.numel() < 1024:
+        raise ValueError("read probe: out is a sink of at least 1024 floats")
+    _check("lg_stream_probe", lib().lg_stream_probe(m, _ptr(x), _ptr(out), n, threads, unroll, hint, _stream(stream)))
     return out
 
 

@@ -80,6 +80,13 @@ def test_argument_validation_without_device(L):
     assert L.lg_mfma_probe(P, n, (1 << 22) + 1, None) == -1
     assert L.lg_mfma_probe_flops(1) == 512 * 4 * 4 * 4096.0                    # groups x waves x chains x flops per MFMA
     assert L.lg_mfma_probe_flops(-5) == 0.0
+    assert L.lg_stream_probe(3, P, Q, 1024, 256, 1, 3, None) == -1                 # unknown mode
+    assert L.lg_stream_probe(2, P, Q, 1022, 256, 1, 3, None) == -1                 # not whole 128-bit words
+    assert L.lg_stream_probe(2, P, Q, 1024, 128, 1, 3, None) == -1                 # workgroup size not on the menu
+    assert L.lg_stream_probe(2, P, Q, 1024, 256, 3, 3, None) == -1                 # unroll not on the menu
+    assert L.lg_stream_probe(2, P, P, 1024, 256, 1, 3, None) == -1                 # copy onto itself
+    assert L.lg_stream_probe(0, None, Q, 1024, 256, 1, 3, None) == -1
+    assert L.lg_stream_probe(2, P, Q, 0, 256, 1, 3, None) == 0
     assert L.lg_conv1d_nwc_wcf(P, P, Q, 1, 4, 4, 3, 4, 1, 2, 0, None, 0, None) == -1   # dilated window too big
     assert L.lg_conv1d_nwc_wcf(P, P, Q, 1, 8, 4, 3, 4, 0, 1, 0, None, 0, None) == -1   # stride 0
     assert L.lg_conv1d_nwc_wcf(P, P, Q, 0, 8, 4, 3, 4, 1, 1, 0, None, 0, None) == 0    # empty batch

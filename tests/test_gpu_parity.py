@@ -160,25 +160,34 @@ def test_matmul_workspace_errors(lg):
 
 @pytest.mark.parametrize("case,shape", list(enumerate(si.MATMUL_SWEEP)))
 def test_matmul_full_size_sampled(lg, lgo, case, shape):
-    """Benchmark sweep shapes, in the launch configuration the benchmark times.  The oracle checks
-    row blocks that straddle tile boundaries (all N columns) element by element."""
+    """Benchmark sweep shapes, in the launch configuration the benchmark times.  What the oracle
+    checks element by element: the WHOLE output for 1024^3 and 4096 x 4096 x 64 (2 GFLOP each);
+    for 4096^3, 8192^3 and 16384 x 512 x 2048 a sample of at least 256 full rows (all N columns)
+    that holds the two rows on either side of every boundary between workgroup tiles along M
+    (block_m from the library's plan query), the first and the last row, and seeded random rows
+    for the rest -- 34 GFLOP of naive loop nest for 8192^3.  Every element must be finite (the
+    output is pre-filled with NaN)."""
     M, N, K = shape
     A, B = si.matmul_inputs(2, M, N, K, case=case)
     Cd = torch.full((M, N), float("nan"), device="cuda")
     ws = workspace(lg.lg_matmul_workspace_bytes(M, N, K))
     lg.lg_matmul(dev(A), dev(B), Cd, workspace=ws)
     sync()
-    starts = sorted({0, 252, M // 2 - 4, M - 8} if M >= 512 else {0})
-    for r0 in starts:
-        rows = slice(r0, min(M, r0 + 8))
-        ref = lgo.matmul(np.ascontiguousarray(A[rows]), B)
-        assert_close(Cd[rows].cpu().numpy(), ref, K, f"matmul {shape} rows {r0}")
-    # every element is finite and the column blocks are consistent with a column-sampled oracle
-    cols = np.arange(0, N, max(1, N // 16))[:16]
-    ref = lgo.matmul(A, np.ascontiguousarray(B[:, cols])) if M * len(cols) * K <= 3e9 else None
-    if ref is not None:
-        assert_close(Cd[:, torch.from_numpy(cols).cuda()].cpu().numpy(), ref, K, f"matmul {shape} cols")
     assert bool(torch.isfinite(Cd).all())
+    if 2.0 * M * N * K <= 3e9:
+        assert_close(Cd.cpu().numpy(), lgo.matmul(A, B), K, f"matmul {shape} (whole output)")
+        return
+    bm = lg.lg_matmul_plan(M, N, K)[0]
+    rows = {0, M - 1}
+    for b in range(bm, M, bm):
+        rows.update((b - 1, b))
+    rng = np.random.default_rng(1000 + case)
+    while len(rows) < 256:
+        rows.add(int(rng.integers(0, M)))
+    rows = np.array(sorted(rows))
+    ref = lgo.matmul(np.ascontiguousarray(A[rows]), B)
+    got = Cd[torch.from_numpy(rows).cuda()].cpu().numpy()
+    assert_close(got, ref, K, f"matmul {shape}, {len(rows)} rows incl. every {bm}-row tile boundary")
 
 
 MATMUL_T_SHAPES = [(1, 1, 1), (5, 7, 3), (64, 64, 64), (130, 70, 50), (256, 256, 256), (300, 520, 136),
@@ -307,11 +316,9 @@ def test_conv2d_full_size(lg, lgo, case, shape):
     N, H, W, C, F, KH, KW, s = shape
     I, Kf = si.conv2d_inputs(3, N, H, W, C, F, KH, KW, case=case)
     O = run_conv(lg, I, Kf, (s, s))
-    # the oracle covers the first and last image completely (each ~0.25 GFLOP)
-    for n in (0, N - 1):
-        ref = lgo.conv2d_nhwc_hwcf(np.ascontiguousarray(I[n:n + 1]), Kf, stride=(s, s))
-        assert_close(O[n:n + 1], ref, KH * KW * C, f"conv {shape} image {n}")
-    assert np.all(np.isfinite(O))
+    # all images, the whole output (1.6-1.9 GFLOP of naive loop nest per configuration)
+    ref = lgo.conv2d_nhwc_hwcf(I, Kf, stride=(s, s))
+    assert_close(O, ref, KH * KW * C, f"conv {shape} (whole output)")
 
 
 # ------------------------------------------------------------------------------- conv1d
@@ -505,13 +512,45 @@ def test_dwconv_accumulate_and_delta(lg, lgo):
     assert np.array_equal(bits(run_dw1(lg, I, K1)), bits(I[:, 2:50]))
 
 
+# the 3 x 3 kernel that stages 8 x 16 pixel x 32 channel tiles through LDS: exact tile multiples, ragged
+# extents whose last tiles are moved inwards (and overlap their neighbours), the smallest extents it
+# takes (one tile in either direction), one and several channel slabs, several images; next to them the
+# shapes just outside it (fewer than 8 output rows or 16 columns, channels not a multiple of 32,
+# accumulation), which must land on the other kernels with the same results
+@pytest.mark.parametrize("N,H,W,C,accumulate", [
+    (1, 10, 18, 32, False), (1, 18, 34, 32, False), (2, 26, 50, 64, False),
+    (1, 11, 19, 32, False), (2, 17, 33, 96, False), (3, 25, 41, 32, False), (1, 58, 58, 128, False),
+    (2, 31, 100, 160, False), (1, 114, 114, 96, False), (1, 9, 40, 32, False), (1, 40, 17, 32, False),
+    (1, 40, 40, 48, False), (1, 40, 40, 36, False), (2, 26, 50, 64, True), (1, 11, 19, 32, True),
+])
+def test_dwconv2d_tile_kernel_shapes(lg, lgo, N, H, W, C, accumulate):
+    I, Kf = si.dwconv2d_inputs(136, N, H, W, C, 3, 3)
+    O0 = si.uniform(136, 9, (N, H - 2, W - 2, C), -1, 1) if accumulate else None
+    got = run_dw2(lg, I, Kf, O0=O0, accumulate=accumulate)
+    ref = lgo.dwconv2d_nhwc_hwc(I, Kf).astype(np.float64)
+    if accumulate:
+        ref = ref + O0.astype(np.float64)
+    assert_close(got, ref, 9, f"dwconv2d tile {N}x{H}x{W}x{C} acc={accumulate}")
+
+
+def test_dwconv2d_tile_kernel_delta_filter_is_a_crop(lg):
+    """A filter with a single 1.0 tap copies a shifted crop of the input: bit-exact, every tap position
+    (a wrong LDS row or column in the tile kernel's window shows as a shifted image)."""
+    N, H, W, C = 2, 27, 37, 64
+    I = si.uniform(137, 0, (N, H, W, C), -1, 1)
+    for a in range(3):
+        for b in range(3):
+            Kf = np.zeros((3, 3, C), np.float32)
+            Kf[a, b, :] = 1.0
+            got = run_dw2(lg, I, Kf)
+            assert np.array_equal(bits(got), bits(np.ascontiguousarray(I[:, a:a + H - 2, b:b + W - 2, :]))), (a, b)
+
+
 def test_dwconv_full_size(lg, lgo):
     N, W, C, KW = si.DWCONV1D_SHAPE
     I, Kf = si.dwconv1d_inputs(4, N, W, C, KW)
     O = run_dw1(lg, I, Kf)
-    for n in (0, N // 2, N - 1):
-        assert_close(O[n:n + 1], lgo.dwconv1d_nwc_wc(np.ascontiguousarray(I[n:n + 1]), Kf), KW, "dwconv1d full")
-    assert np.all(np.isfinite(O))
+    assert_close(O, lgo.dwconv1d_nwc_wc(I, Kf), KW, "dwconv1d full (all 32 batches)")
     N, H, W, C, KH, KW = si.DWCONV2D_SHAPE
     I, Kf = si.dwconv2d_inputs(4, N, H, W, C, KH, KW)
     O = run_dw2(lg, I, Kf)
@@ -875,3 +914,24 @@ def test_other_ops_propagate_nonfinite_values(lg, lgo):
     rows.check(); cols.check()
     assert_same_nonfinite(rows.host(), lgo.reduce_rows(X), 1031, "reduce_rows")
     assert_same_nonfinite(cols.host(), lgo.reduce_cols(X), 523, "reduce_cols")
+
+
+# ------------------------------------------------------------------------------- calibration probes
+
+@pytest.mark.parametrize("threads,unroll,hint", [(256, 1, 3), (256, 4, 0), (512, 2, 1), (1024, 8, 2), (1024, 1, 3)])
+def test_stream_probe_moves_what_it_says(lg, threads, unroll, hint):
+    n = 4 * (threads * unroll * 37 + 13)               # a ragged last workgroup
+    x = si.uniform(140, 0, (n,), -1, 1)
+    src = Guarded((n,), init=x)
+    dst = Guarded((n,))
+    lg.lg_stream_probe("copy", src.t, dst.t, threads=threads, unroll=unroll, hint=hint)
+    sync(); dst.check(); src.check()
+    assert np.array_equal(bits(dst.host()), bits(x))
+    w = Guarded((n,))
+    lg.lg_stream_probe("write", None, w.t, threads=threads, unroll=unroll, hint=hint)
+    sync(); w.check()
+    assert np.array_equal(w.host().reshape(-1, 4), np.tile(np.array([1, 2, 3, 4], np.float32), (n // 4, 1)))
+    sink = Guarded((1024,), init=np.full(1024, 5.0, np.float32))
+    lg.lg_stream_probe("read", src.t, sink.t, threads=threads, unroll=unroll, hint=hint)
+    sync(); sink.check()
+    assert np.all(sink.host() == 5.0)                   # finite input: the sink is never written
