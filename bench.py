@@ -280,18 +280,18 @@ def main():
         x, y = I2.clone(), torch.empty_like(O2)
         return lambda: lg.lg_dwconv2d_nhwc_hwc(x, K2, y)
 
-    # Order.  Writes of one kernel linger dirty in L2 and the Infinity Cache and are paid for by the
-    # kernels after it, so every memory-bound op directly follows a contraction (compute-bound, its
-    # output streamed past the caches): it starts with clean caches and with operands that are cold
-    # (last touched a whole step, > 1 GiB of traffic, ago), and the two ops that leave hundreds of MB
-    # of output behind (transpose, 1-D depthwise) are each followed by the largest products, which flush most of it.
-    add_mm((4096, 4096, 4096))
+    # Order.  What a kernel writes with ordinary stores lingers dirty in the 256 MiB Infinity Cache and
+    # is paid for by whichever later kernel next allocates there (streaming loads and stores pass it
+    # by).  Two ops leave their whole output behind, 256 MiB each (transpose, 1-D depthwise), so:
+    # every memory-bound op directly follows a contraction and finds its operands cold (last touched a
+    # whole step, > 1 GiB of traffic, ago); the transpose is followed by the 4096^3 and 16384 x 512 x
+    # 2048 products (370 MB of distinct operands between them) and the 1-D depthwise op, last in the
+    # step, by the 8192^3 product that opens the next one (805 MB), which flush what they left before
+    # the next memory-bound op starts.
+    add_mm((8192, 8192, 8192))
     add("transpose_8192x8192", lambda: lg.lg_transpose(x_tr, y_tr), 0, tr_bytes, "hbm", "transpose",
         rotate=rotation(tr_bytes, mk_transpose))
-    add_mm((8192, 8192, 8192))
-    # depthwise bytes follow the paper's accounting: output written, filter read, input read once
-    add("dwconv1d_n32w4098c512k3", lambda: lg.lg_dwconv1d_nwc_wc(I1, K1, O1), 2.0 * O1.numel() * k1,
-        dw1_bytes, "hbm", "dwconv1d", rotate=rotation(dw1_bytes, mk_dw1))
+    add_mm((4096, 4096, 4096))
     add_mm((16384, 512, 2048))
     add("reduce_rows_4096x16384", lambda: lg.lg_reduce_rows(x_rows, out_rows), R * Cn, 4.0 * (R * Cn + R), "hbm",
         "reduce_rows", rotate=rotation(red_bytes, mk_rows))
@@ -299,12 +299,15 @@ def main():
     add("reduce_cols_4096x16384", lambda: lg.lg_reduce_cols(x_cols, out_cols, workspace=ws_cols), R * Cn,
         4.0 * (R * Cn + Cn), "hbm", "reduce_cols", rotate=rotation(red_bytes, mk_cols))
     add_conv(convs[1])
+    add("dwconv2d_n8h114c96k3", lambda: lg.lg_dwconv2d_nhwc_hwc(I2, K2, O2), 2.0 * O2.numel() * kh2 * kw2,
+        dw2_bytes, "hbm", "dwconv2d", rotate=rotation(dw2_bytes, mk_dw2))
     add_conv(convs[2])
     add_mm((1024, 1024, 1024))
     add_mm((4096, 4096, 64))
-    add("dwconv2d_n8h114c96k3", lambda: lg.lg_dwconv2d_nhwc_hwc(I2, K2, O2), 2.0 * O2.numel() * kh2 * kw2,
-        dw2_bytes, "hbm", "dwconv2d", rotate=rotation(dw2_bytes, mk_dw2))
     add_mm(si.MATMUL_SMALL)          # configuration 0: 0.2 us of math, a launch-latency figure
+    # depthwise bytes follow the paper's accounting: output written, filter read, input read once
+    add("dwconv1d_n32w4098c512k3", lambda: lg.lg_dwconv1d_nwc_wc(I1, K1, O1), 2.0 * O1.numel() * k1,
+        dw1_bytes, "hbm", "dwconv1d", rotate=rotation(dw1_bytes, mk_dw1))
 
     # Outside the configurations: the copy yardstick, the transposed-operand products, a convolution
     # large enough to fill the machine, and the shallow product accumulating into C (the output is
