@@ -61,10 +61,10 @@ __global__ __launch_bounds__(kCopyThreads) void copy2d_kernel(
 //
 // Global side: 32 lanes (16 for TS = 64) cover the TS*4 contiguous bytes of a tile row, on both
 // sides, so a wavefront's access is two 512-byte pieces rather than four of 256 (measured on
-// 8192 x 8192, cold, back to back: 101.8 -> 95.2 us; with the LDS tile below the column reads of
-// the second phase then meet four lanes per bank instead of two, which does not show).  LDS side: row stride TS+1 words keeps
-// the row-wise writes and the column-wise reads of a wavefront on 32 distinct banks twice, the
-// minimum for 64 lanes.  Tiles are visited along diagonals so that workgroups running together
+// 8192 x 8192, cold, back to back: 101.8 -> 95.2 us).  LDS side: row stride TS+1 words, and the
+// order in which a lane walks its four words rotated by lane group (see `rot` below), keep the
+// row-wise writes and the column-wise reads of a wavefront on 32 distinct banks twice, the minimum
+// for 64 lanes.  Tiles are visited along diagonals so that workgroups running together
 // differ in both row and column block: their strided accesses then do not pile onto the same
 // memory channels.  The walk follows the input rows for square and tall inputs and the output rows
 // for wide ones (measured, 128x128 tiles: 1024 x 65536 129 -> 106 us, 4096 x 16384 122 -> 115 us;
@@ -99,6 +99,11 @@ __global__ __launch_bounds__(THREADS) void transpose_kernel(
         constexpr int RP = THREADS / LPR;           // rows per pass
         constexpr int NL = (TS / RP) * (TS / CW);   // 128-bit words per lane
         const int c4 = t % LPR, rr = t / LPR;
+        // LDS position of tile element (r, c): rows and columns are de-interleaved by four -- row r sits
+        // at slot (r % 4) * TS/4 + r / 4, column c likewise -- so that the lanes of a row, whose words in
+        // step e are the columns 4*c4 + e, and the lanes of a column, whose words are the rows 4*c4 + e,
+        // both land in consecutive slots, i.e. on distinct banks (the row stride S is odd).
+        constexpr int Q = TS / 4;
         u32x4 v[NL];
         int k = 0;
 #pragma unroll
@@ -118,8 +123,9 @@ __global__ __launch_bounds__(THREADS) void transpose_kernel(
         for (int rp = 0; rp < TS / RP; ++rp)
 #pragma unroll
             for (int cc = 0; cc < TS / CW; ++cc) {
-                uint32_t* p = tile + (rp * RP + rr) * S + cc * CW + 4 * c4;
-                p[0] = v[k].x; p[1] = v[k].y; p[2] = v[k].z; p[3] = v[k].w;
+                const int r = rp * RP + rr;
+                uint32_t* p = tile + ((r & 3) * Q + (r >> 2)) * S + cc * (CW / 4) + c4;
+                p[0] = v[k].x; p[Q] = v[k].y; p[2 * Q] = v[k].z; p[3 * Q] = v[k].w;
                 ++k;
             }
         __syncthreads();
@@ -130,11 +136,12 @@ __global__ __launch_bounds__(THREADS) void transpose_kernel(
                 const int orow = rp * RP + rr;      // column of the input tile = row of the output tile
                 const int ic = cc * CW + 4 * c4;    // row of the input tile = column of the output tile
                 if (j0 + orow < Cn && i0 + ic < R) {
+                    const uint32_t* q = tile + (cc * (CW / 4) + c4) * S + (orow & 3) * Q + (orow >> 2);
                     u32x4 w;
-                    w.x = tile[(ic + 0) * S + orow];
-                    w.y = tile[(ic + 1) * S + orow];
-                    w.z = tile[(ic + 2) * S + orow];
-                    w.w = tile[(ic + 3) * S + orow];
+                    w.x = q[0];
+                    w.y = q[Q * S];
+                    w.z = q[2 * Q * S];
+                    w.w = q[3 * Q * S];
                     u32x4* dst = reinterpret_cast<u32x4*>(out + (j0 + orow) * ld_out + i0 + ic);
                     *dst = w;
                 }
