@@ -183,10 +183,14 @@ def main():
         Ad, Bd = dev(A), dev(B)
         Cd = torch.zeros((M, N), device="cuda")
         w = ws(lg.lg_matmul_workspace_bytes(M, N, K))
+        def mk_mm(Ad=Ad, Bd=Bd, M=M, N=N, K=K):
+            a, b, c = Ad.clone(), Bd.clone(), torch.zeros((M, N), device="cuda")
+            wk = ws(lg.lg_matmul_workspace_bytes(M, N, K))
+            return lambda: lg.lg_matmul(a, b, c, workspace=wk)
         mm[(M, N, K)] = dict(name=f"matmul_{M}x{N}x{K}",
                              call=(lambda Ad=Ad, Bd=Bd, Cd=Cd, w=w: lg.lg_matmul(Ad, Bd, Cd, workspace=w)),
                              flops=2.0 * M * N * K, nbytes=4.0 * (M * K + K * N + M * N),
-                             kernel=gemm_kernel_name(M, N, K), operands=(Ad, Bd))
+                             kernel=gemm_kernel_name(M, N, K), operands=(Ad, Bd), make=mk_mm)
         del A, B
 
     # the row and the column reduction get their own tensor of the configured shape, so the second
@@ -221,7 +225,12 @@ def main():
         w = ws(lg.lg_conv2d_workspace_bytes(N, H, W, C, KH, KW, F, s, s, 1, 1))
         # input elements that take part in at least one output (a 1x1 stride-2 filter skips 3/4)
         touched_in = N * OH * OW * C if (KH == 1 and KW == 1) else N * H * W * C
-        convs.append(dict(name=f"conv2d_n{N}h{H}c{C}f{F}k{KH}s{s}",
+        def mk_conv(Id=Id, Kd=Kd, Od=Od, s=s, shape=(N, H, W, C, KH, KW, F)):
+            i, k, o = Id.clone(), Kd.clone(), torch.empty_like(Od)
+            n_, h_, w_, c_, kh_, kw_, f_ = shape
+            wk = ws(lg.lg_conv2d_workspace_bytes(n_, h_, w_, c_, kh_, kw_, f_, s, s, 1, 1))
+            return lambda: lg.lg_conv2d_nhwc_hwcf(i, k, o, stride=(s, s), workspace=wk)
+        convs.append(dict(make=mk_conv, name=f"conv2d_n{N}h{H}c{C}f{F}k{KH}s{s}",
                           call=(lambda Id=Id, Kd=Kd, Od=Od, w=w, s=s:
                                 lg.lg_conv2d_nhwc_hwcf(Id, Kd, Od, stride=(s, s), workspace=w)),
                           flops=2.0 * N * OH * OW * F * KH * KW * C,
@@ -239,19 +248,22 @@ def main():
     wt = ws(lg.lg_matmul_workspace_bytes(Mt, Nt, Kt))
     del At_h, Bt_h
 
-    def add_mm(shape, to=None):
+    # (the contractions of a few GFLOP get a rotating cold figure as well: `rotate`)
+    def add_mm(shape, to=None, rotate=False):
         d = mm[shape]
-        add(d["name"], d["call"], d["flops"], d["nbytes"], "mfma", d["kernel"], to=to)
+        add(d["name"], d["call"], d["flops"], d["nbytes"], "mfma", d["kernel"], to=to,
+            rotate=rotation(d["nbytes"], d["make"]) if rotate else None)
 
-    def add_conv(c, to=None):
-        add(c["name"], c["call"], c["flops"], c["nbytes"], "mfma", c["kernel"], to=to)
+    def add_conv(c, to=None, rotate=False):
+        add(c["name"], c["call"], c["flops"], c["nbytes"], "mfma", c["kernel"], to=to,
+            rotate=rotation(c["nbytes"], c["make"]) if rotate else None)
 
     # Buffer sets for the rotating cold measurement of a memory-bound op: `make()` clones the op's
     # operands (same values, other addresses) and returns the call on the clone; at least four sets
     # and at least 2 GiB in all (eight times the Infinity Cache, so that nothing read by one launch
     # survives until its set comes round again, whichever hints keep the outputs out of the caches).
     def rotation(nbytes, make):
-        return dict(sets=max(4, math.ceil((2 << 30) / nbytes)), make=make)
+        return dict(sets=min(64, max(4, math.ceil((2 << 30) / nbytes))), make=make)
 
     tr_bytes, red_bytes = 8.0 * x_tr.numel(), 4.0 * (R * Cn)
     dw1_bytes = 4.0 * (O1.numel() + K1.numel() + I1.numel())
@@ -296,15 +308,15 @@ def main():
     add_mm((16384, 512, 2048))
     add("reduce_rows_4096x16384", lambda: lg.lg_reduce_rows(x_rows, out_rows), R * Cn, 4.0 * (R * Cn + R), "hbm",
         "reduce_rows", rotate=rotation(red_bytes, mk_rows))
-    add_conv(convs[0])
+    add_conv(convs[0], rotate=True)
     add("reduce_cols_4096x16384", lambda: lg.lg_reduce_cols(x_cols, out_cols, workspace=ws_cols), R * Cn,
         4.0 * (R * Cn + Cn), "hbm", "reduce_cols", rotate=rotation(red_bytes, mk_cols))
-    add_conv(convs[1])
+    add_conv(convs[1], rotate=True)
     add("dwconv2d_n8h114c96k3", lambda: lg.lg_dwconv2d_nhwc_hwc(I2, K2, O2), 2.0 * O2.numel() * kh2 * kw2,
         dw2_bytes, "hbm", "dwconv2d", rotate=rotation(dw2_bytes, mk_dw2))
-    add_conv(convs[2])
-    add_mm((1024, 1024, 1024))
-    add_mm((4096, 4096, 64))
+    add_conv(convs[2], rotate=True)
+    add_mm((1024, 1024, 1024), rotate=True)
+    add_mm((4096, 4096, 64), rotate=True)
     add_mm(si.MATMUL_SMALL)          # configuration 0: 0.2 us of math, a launch-latency figure
     # depthwise bytes follow the paper's accounting: output written, filter read, input read once
     add("dwconv1d_n32w4098c512k3", lambda: lg.lg_dwconv1d_nwc_wc(I1, K1, O1), 2.0 * O1.numel() * k1,
@@ -509,6 +521,11 @@ def main():
         b, s1 = cold_rotating(calls)
         del calls
         torch.cuda.empty_cache()
+        if op["bound"] == "mfma":
+            rec.update(us_cold_rotating=b, gflops_cold_rotating=op["flops"] / b / 1e3,
+                       frac_mfma_peak_cold_rotating=op["flops"] / b / 1e3 / (MFMA_FP32_PEAK / 1e9),
+                       us_cold_single=s1, buffer_sets=op["rotate"]["sets"])
+            continue
         ceil = ceilings["read"] if op["kernel"].startswith("reduce") else \
             ceilings["copy_at_dwconv2d_size"] if op["kernel"] == "dwconv2d" else ceilings["copy"]
         rec.update(us_cold_rotating=b, gbps_cold_rotating=op["bytes"] / b / 1e3,
