@@ -67,3 +67,66 @@ def test_static_rejects_what_exceeds_its_array(lg):
     assert lg.lg_reduce_cols_workspace_bytes(R, Cn) > 4 << 20
     rc = lg.lib().lg_reduce_cols_static(ctypes.c_void_p(1 << 40), ctypes.c_void_p(1 << 20), R, Cn, Cn, 0, None)
     assert rc == -2
+
+
+def test_static_recorded_into_a_graph_and_replayed(lg, lgo):
+    """The callers it is for: recorded into a HIP graph (no allocation may happen there) and replayed with
+    fresh inputs, eager work and synchronisations in between; every replay against the eager result bit for
+    bit, the last one against the oracle."""
+    R, Cn = 3000, 1000
+    assert lg.lg_reduce_cols_workspace_bytes(R, Cn) > 0
+    X = dev(si.uniform(9, 20, (R, Cn), 0, 1))
+    out = torch.zeros(Cn, device="cuda")
+    lg.lg_reduce_cols_static(X, out)              # first use on this device happens outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        lg.lg_reduce_cols_static(X, out)
+    for rep in range(3):
+        x = si.uniform(9, 21 + rep, (R, Cn), 0, 1)
+        X.copy_(dev(x))
+        lg.lg_reduce_cols_static(X, out)
+        torch.cuda.synchronize()
+        eager = out.clone()
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), f"replay {rep} differs from the eager run"
+    assert_close(out.cpu().numpy(), lgo.reduce_cols(x), R, "reduce_cols_static replayed")
+
+
+def test_static_first_use_inside_a_capture():
+    """First call on the device while the stream is being captured (fresh process): the look-up of the
+    device array's address is no stream operation and must not disturb the capture."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = r"""
+import sys
+sys.path.insert(0, %r)
+import torch
+import paper_2202_03293_amd as lg
+X = torch.rand(3000, 1000, device="cuda")
+out = torch.zeros(1000, device="cuda")
+I = torch.rand(2, 26, 50, 64, device="cuda") - 0.5
+K = torch.rand(3, 3, 64, device="cuda") - 0.5
+O = torch.zeros(2, 24, 48, 64, device="cuda")
+torch.cuda.synchronize()
+g = torch.cuda.CUDAGraph()
+with torch.cuda.graph(g):
+    lg.lg_reduce_cols_static(X, out)
+    lg.lg_dwconv2d_nhwc_hwc(I, K, O)                # the LDS-tile kernel, first use as well
+out.zero_(); O.zero_()
+torch.cuda.synchronize()
+for _ in range(2):
+    g.replay()
+    torch.cuda.synchronize()
+assert (out - X.double().sum(0).float()).abs().max().item() < 1e-4 * 3000 ** 0.5
+ref = torch.nn.functional.conv2d(I.permute(0, 3, 1, 2).double(), K.permute(2, 0, 1).unsqueeze(1).double(), groups=64)
+assert (O - ref.permute(0, 2, 3, 1).float()).abs().max().item() < 3e-4
+print("capture-first ok")
+""" % root
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=110)
+    assert r.returncode == 0 and "capture-first ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
