@@ -7,17 +7,50 @@ namespace lg {
 void launch_nn(const GemmArgs& a, const Plan& pl, bool vec, hipStream_t s) { launch_planned<false, false, false>(a, pl, vec, s); }
 void launch_conv(const GemmArgs& a, const Plan& pl, bool vec, hipStream_t s) { launch_planned<true, false, false>(a, pl, vec, s); }
 
-// out[m,n] (+)= sum_z partial[z][m,n]; slabs are dense M x N.  Fixed order: z ascending.
+// out[m,n] (+)= sum_z partial[z][m,n]; slabs are dense M x N.  Fixed order: z ascending, eight slabs
+// at a time, all eight requested before the first add (the kernel is memory round trips long: one per
+// eight slabs instead of one per slab).  V = 4: four adjacent columns per lane, 128-bit accesses
+// (N and ldc multiples of 4, C 16-byte aligned); V = 1 otherwise.
+template <int V>
 __global__ __launch_bounds__(256) void splitk_combine_kernel(
     const float* __restrict__ partial, float* __restrict__ C,
     int64_t M, int64_t N, int64_t ldc, int splits, int accumulate) {
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t idx = ((int64_t)blockIdx.x * 256 + threadIdx.x) * V;
     if (idx >= M * N) return;
     const int64_t m = idx / N, n = idx - m * N;
-    float s = 0.f;
-    for (int z = 0; z < splits; ++z) s += partial[(int64_t)z * M * N + idx];
+    float s[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) s[e] = 0.f;
+    for (int z0 = 0; z0 < splits; z0 += 8) {
+        float v[8][V];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float* q = partial + (int64_t)(z0 + u < splits ? z0 + u : z0) * M * N + idx;
+            if constexpr (V == 4) {
+                const float4 t = *reinterpret_cast<const float4*>(q);
+                v[u][0] = t.x; v[u][1] = t.y; v[u][2] = t.z; v[u][3] = t.w;
+            } else {
+                v[u][0] = *q;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (z0 + u < splits) {
+#pragma unroll
+                for (int e = 0; e < V; ++e) s[e] += v[u][e];
+            }
+    }
     float* cp = C + m * ldc + n;
-    *cp = accumulate ? *cp + s : s;
+    if constexpr (V == 4) {
+        float4 o = make_float4(s[0], s[1], s[2], s[3]);
+        if (accumulate) {
+            const float4 c = *reinterpret_cast<const float4*>(cp);
+            o.x += c.x; o.y += c.y; o.z += c.z; o.w += c.w;
+        }
+        *reinterpret_cast<float4*>(cp) = o;
+    } else {
+        *cp = accumulate ? *cp + s[0] : s[0];
+    }
 }
 
 __global__ __launch_bounds__(256) void fill_zero_2d_kernel(float* C, int64_t M, int64_t N, int64_t ldc) {
@@ -106,10 +139,15 @@ static int run_plan(GemmArgs a, Layout layout, bool vec, const Plan& pl, int use
     }
     if (launch_status() != LG_OK) return LG_ERR_RUNTIME;
     if (pl.splits > 1) {
-        const int64_t blocks = cdiv(a.M * a.N, 256);
-        hipLaunchKernelGGL(splitk_combine_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
-                           static_cast<const float*>(workspace), Cfinal, a.M, a.N, ldc_final, (int)pl.splits,
-                           user_accumulate);
+        // (the workspace is 256-byte aligned and its slabs are M*N floats: whole quads when N is a multiple of 4)
+        if (a.N % 4 == 0 && ldc_final % 4 == 0 && aligned16(Cfinal))
+            hipLaunchKernelGGL(splitk_combine_kernel<4>, dim3((unsigned)cdiv(a.M * a.N / 4, 256)), dim3(256), 0, s,
+                               static_cast<const float*>(workspace), Cfinal, a.M, a.N, ldc_final, (int)pl.splits,
+                               user_accumulate);
+        else
+            hipLaunchKernelGGL(splitk_combine_kernel<1>, dim3((unsigned)cdiv(a.M * a.N, 256)), dim3(256), 0, s,
+                               static_cast<const float*>(workspace), Cfinal, a.M, a.N, ldc_final, (int)pl.splits,
+                               user_accumulate);
         return launch_status();
     }
     return LG_OK;
