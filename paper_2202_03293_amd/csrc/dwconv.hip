@@ -1,6 +1,9 @@
 // Depthwise convolutions (Section 4.7): no contraction across channels, so no matrix cores;
 // K_w (or K_h*K_w) FMAs per output element against 8 bytes of traffic -> HBM-bound.
 //
+// 3x3 in 2-D at strides and dilations 1 and 2 with channel counts that are multiples of 32: output tiles
+// whose input patch is staged in LDS by direct global->LDS transfers and consumed row by row while the
+// rest is still in flight (dwconv2d_tile_kernel, dwconv2d_tile_sd_kernel).
 // Register-window kernels (filter widths 3, 5, 7 in 1-D, 3x3 in 2-D; strides and dilations 1 and 2,
 // the values the paper sweeps): a lane owns 4 adjacent channels (one 128-bit access) and a few output
 // positions, keeps the input window in registers so each input element is loaded once per lane, and
@@ -272,6 +275,110 @@ __global__ __launch_bounds__(CS4 * TW) void dwconv2d_tile_kernel(
     });
 }
 
+// The same staging at the other strides and dilations the paper sweeps (S, D in {1, 2}, equal in both
+// dimensions).  Only input positions that some (output, tap) pair reads are staged: they lie g = gcd(S, D)
+// apart, so patch position (pr, pc) is input position (h0*S + g*pr, w0*S + g*pc) and output (oh, ow) reads
+// patch rows oh*S/g + a*D/g, columns ow*S/g + b*D/g -- which is also the paper's byte accounting (input
+// bytes divided by the product of the gcds).  The nine taps are read from LDS per output (no register
+// window: at stride 2 neighbouring output rows share one input row at most).
+template <int CS4, int TH, int TW, int S, int D>
+struct Dw2TileSD {
+    static constexpr int G = gcd_i(S, D), SG = S / G, DG = D / G;
+    static constexpr int T = CS4 * TW;
+    static constexpr int PR = (TH - 1) * SG + 2 * DG + 1, PC = (TW - 1) * SG + 2 * DG + 1;
+    static constexpr int ROW = PC * CS4, ITEMS = PR * ROW;
+    static constexpr int NL = ceil_div_i(ITEMS, T), KNL = ceil_div_i(9 * CS4, T);
+    static constexpr int LDS_BYTES = (KNL + NL) * T * 16;
+    static_assert(T % kWave == 0 && T <= 1024, "whole wavefronts");
+    static_assert(NL + TH <= 63, "the wait counts must fit s_waitcnt's 6 bits");
+    static_assert(LDS_BYTES <= 160 * 1024, "tile must fit in LDS");
+};
+
+template <int CS4, int TH, int TW, int S, int D>
+__global__ __launch_bounds__(CS4 * TW) void dwconv2d_tile_sd_kernel(
+    const float* __restrict__ I, const float* __restrict__ Kf, float* __restrict__ O,
+    int64_t H, int64_t W, int64_t C, int64_t OH, int64_t OW,
+    unsigned ntiles, unsigned tiles_h, unsigned tiles_w, unsigned slabs) {
+    using Dd = Dw2TileSD<CS4, TH, TW, S, D>;
+    constexpr int T = Dd::T, PC = Dd::PC, ROW = Dd::ROW, ITEMS = Dd::ITEMS, NL = Dd::NL, KNL = Dd::KNL;
+    constexpr int G = Dd::G, SG = Dd::SG, DG = Dd::DG;
+    extern __shared__ __align__(16) float4 dw_lds[];          // [KNL*T] filter taps, then [NL*T] patch
+    float4* kf = dw_lds;
+    float4* patch = dw_lds + KNL * T;
+    const unsigned L = xcd_contiguous_id(blockIdx.x, ntiles);
+    const unsigned slab = L % slabs, tw = (L / slabs) % tiles_w;
+    const unsigned th = (L / (slabs * tiles_w)) % tiles_h, n = L / (slabs * tiles_w * tiles_h);
+    int64_t h0 = (int64_t)th * TH, w0 = (int64_t)tw * TW;
+    if (h0 > OH - TH) h0 = OH - TH;                           // edge tiles move inwards: every tile is full
+    if (w0 > OW - TW) w0 = OW - TW;
+    const int t = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(t / kWave);
+    {
+        const char* kb = reinterpret_cast<const char*>(to_scalar(reinterpret_cast<int64_t>(Kf + slab * CS4 * 4)));
+#pragma unroll
+        for (int i = 0; i < KNL; ++i) {
+            int q = i * T + t;
+            if (q > 9 * CS4 - 1) q = 9 * CS4 - 1;
+            const int tap = q / CS4, c4 = q - tap * CS4;
+            dma16(kb, (uint32_t)((tap * C + 4 * c4) * 4), lds_addr(kf + i * T + wave * kWave));
+        }
+    }
+    const char* base = reinterpret_cast<const char*>(
+        to_scalar(reinterpret_cast<int64_t>(I + ((n * H + h0 * S) * W + w0 * S) * C + slab * CS4 * 4)));
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+        int q = i * T + t;
+        if (q > ITEMS - 1) q = ITEMS - 1;
+        const int r = q / ROW, rem = q - r * ROW;
+        const int px = rem / CS4, c4 = rem - px * CS4;
+        dma16(base, (uint32_t)(((r * G * W + px * G) * C + 4 * c4) * 4), lds_addr(patch + i * T + wave * kWave));
+    }
+    const int c4 = t % CS4, col = t / CS4;
+    float* op = O + ((n * OH + h0) * OW + w0 + col) * C + slab * CS4 * 4 + 4 * c4;
+    float4 k[3][3];
+    static_for<0, TH>([&](auto ohc) {
+        constexpr int oh = decltype(ohc)::value;
+        constexpr int need = oh * SG + 2 * DG;                                     // last patch row this output row reads
+        constexpr int last = min_i(ceil_div_i((need + 1) * ROW, T) - 1, NL - 1);   // last transfer that brings a word of it
+        dma_wait<min_i(NL - 1 - last + oh, 63)>();                                 // + the oh stores every lane has issued
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if constexpr (oh == 0) {
+#pragma unroll
+            for (int a = 0; a < 3; ++a)
+#pragma unroll
+                for (int b = 0; b < 3; ++b) k[a][b] = kf[(a * 3 + b) * CS4 + c4];
+        }
+        float4 s = make_float4(0, 0, 0, 0);
+#pragma unroll
+        for (int a = 0; a < 3; ++a)
+#pragma unroll
+            for (int b = 0; b < 3; ++b)
+                s = fma4(patch[((oh * SG + a * DG) * PC + col * SG + b * DG) * CS4 + c4], k[a][b], s);
+        store_stream4(op + (int64_t)oh * OW * C, s);
+    });
+}
+
+template <int CS4, int TH, int TW, int S, int D>
+static int launch_dw2_tile_sd(const float* I, const float* Kf, float* O, int64_t N, int64_t H, int64_t W, int64_t C,
+                              int64_t OH, int64_t OW, hipStream_t s) {
+    using Dd = Dw2TileSD<CS4, TH, TW, S, D>;
+    const int64_t tiles_h = cdiv(OH, TH), tiles_w = cdiv(OW, TW), slabs = C / (4 * CS4);
+    const int64_t ntiles = N * tiles_h * tiles_w * slabs;
+    if (ntiles > kMaxGrid) return LG_ERR_UNSUPPORTED;
+    static bool configured[kMaxDevices] = {};
+    allow_dynamic_lds(reinterpret_cast<const void*>(&dwconv2d_tile_sd_kernel<CS4, TH, TW, S, D>), Dd::LDS_BYTES, configured);
+    hipLaunchKernelGGL((dwconv2d_tile_sd_kernel<CS4, TH, TW, S, D>), dim3((unsigned)ntiles), dim3(Dd::T), Dd::LDS_BYTES, s,
+                       I, Kf, O, H, W, C, OH, OW, (unsigned)ntiles, (unsigned)tiles_h, (unsigned)tiles_w, (unsigned)slabs);
+    return launch_status();
+}
+
+template <int CS4, int TH, int TW, int S, int D>
+static bool dw2_tile_sd_fits(int64_t W, int64_t C, int64_t OH, int64_t OW) {
+    using Dd = Dw2TileSD<CS4, TH, TW, S, D>;
+    return C % (4 * CS4) == 0 && OH >= TH && OW >= TW && (int64_t)Dd::PR * Dd::G * W * C * 4 < ((int64_t)1 << 31);
+}
+
 template <int CS4, int TH, int TW>
 static int launch_dw2_tile(const float* I, const float* Kf, float* O, int64_t N, int64_t H, int64_t W, int64_t C,
                            int64_t OH, int64_t OW, hipStream_t s) {
@@ -478,6 +585,18 @@ static int dwconv_dispatch(const float* I, const float* Kf, float* O,
     if (vec && KH == 3 && KW == 3 && SH == 1 && SW == 1 && DH == 1 && DW == 1 && !accumulate &&
         dw2_tile_fits<8, 8, 16>(W, C, OH, OW))
         return launch_dw2_tile<8, 8, 16>(I, Kf, O, N, H, W, C, OH, OW, s);
+    // ... and at the other strides and dilations of the sweep, unless the tiles moved inwards at the edges would
+    // recompute more than a quarter of the outputs (measured, cold: 32 x 114 x 114 x 96 dilation 2 68.6 -> 57.9 us,
+    // stride 2 40.7 -> 39.5, both 20.1 -> 19.3; 32 x 58 x 58 x 256 stride and dilation 2, 27 x 27 outputs in
+    // 8 x 16 tiles, 14.3 -> 15.4: left to the register-window kernel)
+    if (vec && KH == 3 && KW == 3 && SH == SW && DH == DW && sd12 && !accumulate) {
+#define LG_DW2SD(S_, D_, TH_)                                                                                \
+        if (SW == S_ && DW == D_ && dw2_tile_sd_fits<8, TH_, 16, S_, D_>(W, C, OH, OW) &&                    \
+            4 * cdiv(OH, TH_) * TH_ * cdiv(OW, 16) * 16 <= 5 * OH * OW)                                      \
+            return launch_dw2_tile_sd<8, TH_, 16, S_, D_>(I, Kf, O, N, H, W, C, OH, OW, s);
+        LG_DW2SD(2, 1, 4) LG_DW2SD(1, 2, 8) LG_DW2SD(2, 2, 8)
+#undef LG_DW2SD
+    }
     if (vec && KH == 3 && KW == 3 && SH == SW && DH == DW && sd12) {
         const int64_t G = DW / (SW == DW ? DW : 1);
 #define LG_DW2(S_, D_, TH_, TW_)                                                                             \

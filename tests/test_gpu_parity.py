@@ -533,6 +533,21 @@ def test_dwconv2d_tile_kernel_shapes(lg, lgo, N, H, W, C, accumulate):
     assert_close(got, ref, 9, f"dwconv2d tile {N}x{H}x{W}x{C} acc={accumulate}")
 
 
+# the same staging at stride and dilation 2 (patch rows and columns gcd(S, D) apart): exact tile multiples,
+# ragged extents with tiles moved inwards, the smallest extents a tile takes, extents whose moved tiles would
+# recompute too much (they stay on the register-window kernel), several slabs and images
+@pytest.mark.parametrize("st,dl", [(2, 1), (1, 2), (2, 2)])
+@pytest.mark.parametrize("N,OH,OW,C", [(1, 8, 16, 32), (2, 16, 32, 64), (1, 9, 17, 32), (2, 23, 45, 96), (1, 56, 56, 128),
+                                       (3, 13, 30, 32), (1, 27, 27, 64), (1, 4, 16, 32), (1, 7, 40, 32), (2, 20, 15, 32)])
+def test_dwconv2d_tile_kernel_strides_dilations(lg, lgo, N, OH, OW, C, st, dl):
+    H, W = (OH - 1) * st + 2 * dl + 1 + (st - 1), (OW - 1) * st + 2 * dl + 1        # a spare row at stride 2: floor in the extent
+    I, Kf = si.dwconv2d_inputs(138, N, H, W, C, 3, 3)
+    got = run_dw2(lg, I, Kf, st=(st, st), dl=(dl, dl))
+    assert got.shape == (N, OH, OW, C)
+    assert_close(got, lgo.dwconv2d_nhwc_hwc(I, Kf, stride=(st, st), dilation=(dl, dl)), 9,
+                 f"dwconv2d tile {N}x{H}x{W}x{C} stride {st} dilation {dl}")
+
+
 def test_dwconv2d_tile_kernel_delta_filter_is_a_crop(lg):
     """A filter with a single 1.0 tap copies a shifted crop of the input: bit-exact, every tap position
     (a wrong LDS row or column in the tile kernel's window shows as a shifted image)."""
