@@ -57,17 +57,23 @@ struct Tile {
     static_assert(BK == 16 || BK == 32 || BK == 64, "k-slice depth");
     static_assert(NB == 1 || NB == 2 || NB == 4, "wave tile width must be 32, 64 or 128");
     static_assert((BM * BK / 4) % THREADS == 0 && (BK * BN / 4) % THREADS == 0, "slice must divide over the workgroup");
-    static_assert(THREADS % QPR == 0 && ROW_STEP % 8 == 0 && (THREADS / BK) % 8 == 0,
+    static_assert(THREADS % QPR == 0 && ROW_STEP % 16 == 0 && (THREADS / BK) % 8 == 0,
                   "a lane's R-kind rows must share one swizzle");
 
     // R-kind LDS position (in floats) of the float4 holding k = 4q .. 4q+3 of row r.  Rows are BK
-    // floats; the quad index is XOR-ed with row bits so that 8 consecutive rows reading the same
-    // logical quad touch 8 distinct 4-bank groups.  A row is BK/32 times all banks (BK = 16: two rows
-    // span the banks, so the row bits used start at bit 1).
-    static constexpr int SWZ_SH = (QPR == 4) ? 1 : 0;
+    // floats; the quad index is XOR-ed with row bits so that the rows a read touches together land on
+    // distinct banks.  The LDS of this part serves a 128-bit read 16 lanes at a time over 64 banks
+    // (SQ_LDS_BANK_CONFLICT: with the row bits chosen for 8 lanes over 32 banks, rows 8 apart collided --
+    // 17-50 % of the LDS cycles of every R-kind operand; with the bits below: 0).  16 consecutive rows
+    // reading the same logical quad must therefore hit 16 distinct 4-bank groups: a row of BK = 16 floats
+    // spans a quarter of the banks, so rows r, r+4, r+8, r+12 need four different quads (row bits 2-3);
+    // a row of 32 floats spans half, so rows of equal parity need eight (row bits 1-3).
+    // The one-float transfer path (VEC = false) keeps the narrower choice (bits 1-2 / 0-2): its rows per
+    // lane are only 8 apart for BK = 32 and must share one swizzle; it is bound by its transfers anyway.
+    template <bool VEC> static constexpr int swz_sh() { return VEC ? ((QPR == 4) ? 2 : (QPR == 8) ? 1 : 0) : ((QPR == 4) ? 1 : 0); }
     static constexpr int SWZ_MASK = (QPR < 8) ? QPR - 1 : 7;
-    __device__ static __forceinline__ int swizzle(int r) { return (r >> SWZ_SH) & SWZ_MASK; }
-    __device__ static __forceinline__ int r_off(int r, int q) { return r * BK + ((q ^ swizzle(r)) << 2); }
+    template <bool VEC> __device__ static __forceinline__ int swizzle(int r) { return (r >> swz_sh<VEC>()) & SWZ_MASK; }
+    template <bool VEC> __device__ static __forceinline__ int r_off(int r, int q) { return r * BK + ((q ^ swizzle<VEC>(r)) << 2); }
 };
 
 template <class T, bool VEC, bool CONV, bool TA, bool TB>
@@ -105,7 +111,7 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
     // and the lane fetches the LOGICAL quad lq = physical ^ swizzle(row) (the same for all i), so the
     // swizzle costs nothing.  C-kind: q -> k-row q / (cols/4), column quad q % (cols/4).
     const int r0 = t / T::QPR;
-    const int lq = (t % T::QPR) ^ T::swizzle(r0);
+    const int lq = (t % T::QPR) ^ T::template swizzle<VEC>(r0);
 
     // conv: element offset of GEMM row m = (n, oh, ow) at filter tap (0, 0), channel 0; grows with m
     // (M, OH, OW < 2^31 -- the host checks -- so the divisions are 32-bit: several times cheaper)
@@ -262,7 +268,7 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
             for (int i = 0; i < 4 * decltype(per_c)::value; ++i) {
                 const int f = t + i * NTH;
                 int64_t r = f / BK;
-                const int kq = (((f % BK) / 4) ^ T::swizzle((int)r)) * 4 + f % 4;
+                const int kq = (((f % BK) / 4) ^ T::template swizzle<VEC>((int)r)) * 4 + f % 4;
                 if (r >= valid) r = valid - 1;
                 loff[i] = (uint32_t)((r * ld + kq) * 4);
             }
@@ -304,7 +310,7 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
             // physical position t % BK (the rows of a lane's transfers are NTH / BK apart, which leaves
             // the swizzle unchanged).
             const int row_t = t / BK;
-            const int lk = VEC ? 4 * lq : (((t % BK) / 4) ^ T::swizzle(row_t)) * 4 + t % 4;
+            const int lk = VEC ? 4 * lq : (((t % BK) / 4) ^ T::template swizzle<VEC>(row_t)) * 4 + t % 4;
             auto lane_row_base = [&](int i) -> int64_t {
                 if constexpr (VEC) {
                     return conv_base_clamped(i);
@@ -426,14 +432,14 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
             for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
-                    a4[j][mb] = *reinterpret_cast<const float4*>(as + T::r_off(wm0 + mb * 32 + c32, 2 * j + h));
+                    a4[j][mb] = *reinterpret_cast<const float4*>(as + T::template r_off<VEC>(wm0 + mb * 32 + c32, 2 * j + h));
         }
         if constexpr (TB) {      // block nb holds columns nb*32 + c32: consecutive lanes read consecutive rows
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb)
-                    b4[j][nb] = *reinterpret_cast<const float4*>(bs + T::r_off(wn0 + nb * 32 + c32, 2 * j + h));
+                    b4[j][nb] = *reinterpret_cast<const float4*>(bs + T::template r_off<VEC>(wn0 + nb * 32 + c32, 2 * j + h));
         }
         auto load_step = [&](int st, int slot) {
             const int k = 8 * (st / 4) + 4 * h + (st % 4);
@@ -493,14 +499,14 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
             for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
-                    pa4[set][j][mb] = *reinterpret_cast<const float4*>(as + T::r_off(wm0 + mb * 32 + c32, 2 * j + h));
+                    pa4[set][j][mb] = *reinterpret_cast<const float4*>(as + T::template r_off<VEC>(wm0 + mb * 32 + c32, 2 * j + h));
         }
         if constexpr (TB) {
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb)
-                    pb4[set][j][nb] = *reinterpret_cast<const float4*>(bs + T::r_off(wn0 + nb * 32 + c32, 2 * j + h));
+                    pb4[set][j][nb] = *reinterpret_cast<const float4*>(bs + T::template r_off<VEC>(wn0 + nb * 32 + c32, 2 * j + h));
         }
     };
     auto fetch_C = [&](int buf, int st, int slot) {
