@@ -19,6 +19,9 @@
  *    `accumulate` == 0 the output is overwritten and never read; with
  *    `accumulate` != 0 the computed value is added to what it holds.
  *  - Inputs must not overlap outputs.
+ *  - Entry points may be called from several host threads at once (on their
+ *    own streams or devices); what lg_reduce_cols_static shares between calls
+ *    is stated there.
  *  - Return value: LG_OK or a negative LG_ERR_* code.  Arguments, workspace
  *    and launch limits of every kernel of a call are checked before the first
  *    kernel is enqueued: with LG_ERR_INVALID_ARG, LG_ERR_UNSUPPORTED or

@@ -366,7 +366,7 @@ static int launch_dw2_tile_sd(const float* I, const float* Kf, float* O, int64_t
     const int64_t tiles_h = cdiv(OH, TH), tiles_w = cdiv(OW, TW), slabs = C / (4 * CS4);
     const int64_t ntiles = N * tiles_h * tiles_w * slabs;
     if (ntiles > kMaxGrid) return LG_ERR_UNSUPPORTED;
-    static bool configured[kMaxDevices] = {};
+    static DeviceFlags configured = {};
     allow_dynamic_lds(reinterpret_cast<const void*>(&dwconv2d_tile_sd_kernel<CS4, TH, TW, S, D>), Dd::LDS_BYTES, configured);
     hipLaunchKernelGGL((dwconv2d_tile_sd_kernel<CS4, TH, TW, S, D>), dim3((unsigned)ntiles), dim3(Dd::T), Dd::LDS_BYTES, s,
                        I, Kf, O, H, W, C, OH, OW, (unsigned)ntiles, (unsigned)tiles_h, (unsigned)tiles_w, (unsigned)slabs);
@@ -386,7 +386,7 @@ static int launch_dw2_tile(const float* I, const float* Kf, float* O, int64_t N,
     const int64_t tiles_h = cdiv(OH, TH), tiles_w = cdiv(OW, TW), slabs = C / (4 * CS4);
     const int64_t ntiles = N * tiles_h * tiles_w * slabs;
     if (ntiles > kMaxGrid) return LG_ERR_UNSUPPORTED;
-    static bool configured[kMaxDevices] = {};
+    static DeviceFlags configured = {};
     allow_dynamic_lds(reinterpret_cast<const void*>(&dwconv2d_tile_kernel<CS4, TH, TW>), D::LDS_BYTES, configured);
     hipLaunchKernelGGL((dwconv2d_tile_kernel<CS4, TH, TW>), dim3((unsigned)ntiles), dim3(D::T), D::LDS_BYTES, s,
                        I, Kf, O, H, W, C, OH, OW, (unsigned)ntiles, (unsigned)tiles_h, (unsigned)tiles_w, (unsigned)slabs);

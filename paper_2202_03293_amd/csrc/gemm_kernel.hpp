@@ -771,7 +771,7 @@ using Tile7 = Tile<32, 128, 32, 32, 32, 2, 3>;     // four waves of 32x32 side b
 
 template <class T, bool VEC, bool CONV, bool TA, bool TB>
 static void launch_gemm(const GemmArgs& a, unsigned splits, hipStream_t s) {
-    static bool configured[kMaxDevices] = {};
+    static DeviceFlags configured = {};
     const size_t lds_bytes = T::LDS_FLOATS * sizeof(float);
     allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_kernel<T, VEC, CONV, TA, TB>), lds_bytes, configured);
     hipLaunchKernelGGL((gemm_kernel<T, VEC, CONV, TA, TB>), dim3(a.tiles_m * a.tiles_n, splits), dim3(T::THREADS),

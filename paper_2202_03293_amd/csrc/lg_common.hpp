@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 #include <type_traits>
 #include "lg.h"
 
@@ -23,14 +24,16 @@ inline bool overlaps(const void* a, int64_t na, const void* b, int64_t nb) {
 }
 
 // Raise a kernel's dynamic-LDS limit once per device (the attribute belongs to the kernel as loaded
-// on one device).  `done` is the caller's per-kernel table of kMaxDevices flags.
+// on one device).  `done` is the caller's per-kernel table of kMaxDevices flags; two host threads that
+// meet on a kernel's first use both set the attribute (to the same value), which is harmless.
 constexpr int kMaxDevices = 64;
-inline void allow_dynamic_lds(const void* kernel, size_t bytes, bool* done) {
+using DeviceFlags = std::atomic<bool>[kMaxDevices];
+inline void allow_dynamic_lds(const void* kernel, size_t bytes, std::atomic<bool>* done) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) dev = -1;
-    if (dev >= 0 && done[dev]) return;
+    if (dev >= 0 && done[dev].load(std::memory_order_acquire)) return;
     (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-    if (dev >= 0) done[dev] = true;
+    if (dev >= 0) done[dev].store(true, std::memory_order_release);
 }
 
 // The runtime keeps one "last error" per host thread, shared with every other user of HIP in the

@@ -174,7 +174,7 @@ static int launch_transpose(const uint32_t* in, uint32_t* out, int64_t R, int64_
     const int64_t ti = cdiv(R, TS), tj = cdiv(Cn, TS);
     if (ti * tj > kMaxGrid || B0 > 65535 || B1 > 65535) return LG_ERR_UNSUPPORTED;
     constexpr size_t lds = (size_t)TS * (TS + 1) * sizeof(uint32_t);
-    static bool configured[kMaxDevices] = {};
+    static DeviceFlags configured = {};
     allow_dynamic_lds(reinterpret_cast<const void*>(&transpose_kernel<TS, THREADS, VEC>), lds, configured);
     hipLaunchKernelGGL((transpose_kernel<TS, THREADS, VEC>), dim3((unsigned)(ti * tj), (unsigned)B1, (unsigned)B0),
                        dim3(THREADS), lds, s, in, out, R, Cn, ld_in, ld_out, (unsigned)ti, (unsigned)tj,
