@@ -40,11 +40,11 @@ HBM_PEAK = 8.0e12              # bytes/s
 # planner sources and the launch plans the counters were taken with: anything else makes `traffic` null.
 TRAFFIC = {
     "kernel": "gemm_128x128",
-    "source_sha256": "eaccf12d75f6eef7fcb9594e5ae4fe2e834169c4bb7ed83eb40db1254ac51793",
+    "source_sha256": "9eef03310caa48b37f752d5e0a674955241cd60b64572d3218988ee865254aec",
     # [block_m, block_n, k_splits] of the launches counted
     "plans": {"8192x8192x8192": [128, 128, 1], "4096x4096x4096": [128, 128, 1], "16384x512x2048": [128, 128, 1]},
-    "fetch_bytes": 2504982006,       # 1223135.7 KiB read by FETCH_SIZE x 2.0 (copy-kernel calibration)
-    "write_bytes": 123033245,        # 120149.7 KiB read by WRITE_SIZE x 1.0
+    "fetch_bytes": 2543818315,       # 1242098.8 KiB read by FETCH_SIZE x 2.0 (copy-kernel calibration)
+    "write_bytes": 123033216,        # 120149.6 KiB read by WRITE_SIZE x 1.0
 }
 KERNEL_SOURCES = [os.path.join(ROOT, "paper_2202_03293_amd", "csrc", f)
                   for f in ("gemm_kernel.hpp", "gemm_plan.hpp", "gemm.hip")]
