@@ -169,7 +169,8 @@ def main():
 
     def gemm_kernel_name(M, N, K):
         bm, bn, sp = gemm_plan(M, N, K)
-        return f"gemm_{bm}x{bn}" + (f"_splitk{sp}" if sp > 1 else "")
+        return (f"gemm_{bm}x{bn}" + (f"_splitk{sp}" if sp > 1 else "") +
+                ("_tile_loop" if lg.lg_matmul_plan_tile_loop(M, N, K) else ""))
 
     host_keep = {}
     mm = {}

@@ -116,6 +116,15 @@ int lg_matmul_t(const float *A, const float *B, float *C,
 int lg_matmul_plan(int64_t M, int64_t N, int64_t K, int *block_m, int *block_n, int *k_splits);
 
 /*
+ * 1 when that plan of lg_matmul runs fewer workgroups than output tiles, each walking over
+ * several (short contractions with a large output: a tile's stores then drain under the next
+ * tile's multiplications; Section 4.6.1 fixes what is computed, not the order of the tiles),
+ * else 0, also for extents that are not positive.  Transposed operands, convolutions and
+ * operands that rule out 128-bit access run one workgroup per tile whatever this says.
+ */
+int lg_matmul_plan_tile_loop(int64_t M, int64_t N, int64_t K);
+
+/*
  * The same for lg_matmul_t: the plan may depend on the operand layout (a few dozen rows times a
  * large B stored N x K take k-slabs where AB does not).  lg_matmul_workspace_bytes(M, N, K) covers
  * the plan of every layout.  transA and transB both set is LG_ERR_INVALID_ARG.
@@ -131,9 +140,16 @@ int lg_matmul_t_plan(int64_t M, int64_t N, int64_t K, int transA, int transB,
  * measurement, and so that tests can hold every kernel variant to every shape.
  *
  *   lg_gemm_variants()       number of menu entries; variants are 0 .. that - 1.
- *   lg_gemm_variant_info()   workgroup block block_m x block_n, k depth per step block_k, and
+ *   lg_gemm_variant_info()   workgroup block block_m x block_n, k depth per step block_k,
  *                            k_parts: into how many parts a workgroup cuts the k range among
- *                            its own wavefronts (1 for the LDS-tiled kernels).  Any output
+ *                            its own wavefronts (1 for the LDS-tiled kernels), and tile_loop:
+ *                            1 when the variant runs fewer workgroups than there are output
+ *                            blocks, each walking over several (the chip's fill of workgroups,
+ *                            or a third of the blocks if that is fewer), so that a block's
+ *                            output stores drain under the next block's multiplications; such a
+ *                            variant takes k_splits = 1 only, and runs as the same block
+ *                            without the loop for transposed operands, convolutions, operands
+ *                            that rule out 128-bit accesses, and fewer than 9 blocks.  Any output
  *                            pointer may be NULL.  LG_ERR_INVALID_ARG for an unknown variant.
  *   lg_matmul_variant()      lg_matmul_t with the variant and the number of k-slabs across
  *                            workgroups (k_splits >= 1; the register-direct variants -- those
@@ -150,7 +166,8 @@ int lg_matmul_t_plan(int64_t M, int64_t N, int64_t K, int transA, int transB,
  * LG_ERR_UNSUPPORTED (the default entry points never pick them for such operands).
  */
 int lg_gemm_variants(void);
-int lg_gemm_variant_info(int variant, int *block_m, int *block_n, int *block_k, int *k_parts);
+int lg_gemm_variant_info(int variant, int *block_m, int *block_n, int *block_k, int *k_parts,
+                         int *tile_loop);
 size_t lg_gemm_variant_workspace_bytes(int64_t M, int64_t N, int64_t K, int variant, int k_splits);
 int lg_matmul_variant(const float *A, const float *B, float *C,
                       int64_t M, int64_t N, int64_t K,

@@ -8,7 +8,7 @@ fallback: importing the ops without the built library raises.
 from .ops import (  # noqa: F401
     LgError, lib, lg_version, lg_status_string, lg_conv_out_extent,
     lg_matmul, lg_matmul_t, lg_matmul_workspace_bytes, lg_matmul_plan, lg_matmul_t_plan,
-    lg_gemm_variants, lg_gemm_variant_info, lg_gemm_variant_workspace_bytes, lg_matmul_variant,
+    lg_matmul_plan_tile_loop, lg_gemm_variants, lg_gemm_variant_info, lg_gemm_variant_workspace_bytes, lg_matmul_variant,
     lg_conv2d_nhwc_hwcf_variant,
     lg_conv2d_nhwc_hwcf, lg_conv2d_workspace_bytes, lg_conv1d_nwc_wcf, lg_conv1d_workspace_bytes,
     lg_dwconv1d_nwc_wc, lg_dwconv2d_nhwc_hwc,

@@ -61,14 +61,24 @@ __global__ __launch_bounds__(256) void fill_zero_2d_kernel(float* C, int64_t M, 
 }
 
 // The menu a caller may pick from by number: the eight tiles, then the register-direct kernel with
-// blocks 16 x {16, 32, 64} and {1, 2, 4} k parts per workgroup.
-constexpr int kNumVariants = kNumTiles + 9;
+// blocks 16 x {16, 32, 64} and {1, 2, 4} k parts per workgroup, then the tiles that have a tile loop,
+// run with it (where the loop is not compiled -- other layouts, unaligned operands -- or there are no
+// more tiles than workgroups, they run as the plain tile).
+constexpr int kNumDirect = 9;
+constexpr int kNumVariants = kNumTiles + kNumDirect + kNumLoopTiles;
 
 // The plan of a forced variant; false when the numbers make no sense.
 static bool forced_plan(int64_t M, int64_t N, int64_t K, int variant, int k_splits, Plan* out) {
     if (variant < 0 || variant >= kNumVariants || k_splits < 1 || k_splits > 65535) return false;
     Plan pl{};
-    if (variant >= kNumTiles) {
+    if (variant >= kNumTiles + kNumDirect) {
+        if (k_splits != 1) return false;
+        const int tile = kLoopTiles[variant - kNumTiles - kNumDirect];
+        if (!forced_plan(M, N, K, tile, 1, &pl)) return false;
+        // the chip's fill of workgroups, or a third of the tiles if that is fewer (so that small shapes loop too)
+        const int64_t third = pl.tiles_m * pl.tiles_n / 3 / kXcds * kXcds;
+        pl.persist_grid = third < kXcds ? kXcds : third < loop_grid(tile) ? third : loop_grid(tile);
+    } else if (variant >= kNumTiles) {
         static const int pow2[3] = {1, 2, 4};
         if (k_splits != 1) return false;
         pl.direct_nbw = pow2[(variant - kNumTiles) / 3];
@@ -163,7 +173,8 @@ static int run_gemm(const GemmArgs& a, Layout layout, bool vec, int user_accumul
             g.accumulate = user_accumulate;
             return launch_gemv(g, layout, s);
         }
-        pl = make_plan(a.M, a.N, a.K, layout == Layout::NT, layout == Layout::CONV ? a.g.C : 0);
+        pl = make_plan(a.M, a.N, a.K, layout == Layout::NT, layout == Layout::CONV ? a.g.C : 0,
+                       layout == Layout::NN && vec);
         // the planner knows extents, not pitches: operands padded past the direct kernel's reach
         // run on the smallest tile, unsplit (which needs no workspace either)
         if (pl.direct_nbw > 0 && !direct_can_run(a, layout)) forced_plan(a.M, a.N, a.K, 3, 1, &pl);
@@ -192,12 +203,18 @@ static int zero_output(float* C, int64_t M, int64_t N, int64_t ldc, hipStream_t 
 extern "C" int lg_matmul_plan(int64_t M, int64_t N, int64_t K, int* block_m, int* block_n, int* k_splits) {
     using namespace lg;
     if (M <= 0 || N <= 0 || K <= 0) return LG_ERR_INVALID_ARG;
-    const Plan pl = make_plan(M, N, K);
+    const Plan pl = make_plan(M, N, K, false, 0, true);
     const bool direct = pl.direct_nbw > 0;
     if (block_m) *block_m = direct ? 16 : kTiles[pl.tile].bm;
     if (block_n) *block_n = direct ? 16 * pl.direct_nbw : kTiles[pl.tile].bn;
     if (k_splits) *k_splits = direct ? 1 : (int)pl.splits;
     return LG_OK;
+}
+
+extern "C" int lg_matmul_plan_tile_loop(int64_t M, int64_t N, int64_t K) {
+    using namespace lg;
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    return make_plan(M, N, K, false, 0, true).persist_grid > 0;
 }
 
 extern "C" size_t lg_matmul_workspace_bytes(int64_t M, int64_t N, int64_t K) {
@@ -210,7 +227,7 @@ extern "C" int lg_matmul_t_plan(int64_t M, int64_t N, int64_t K, int transA, int
                                 int* block_m, int* block_n, int* k_splits) {
     using namespace lg;
     if (M <= 0 || N <= 0 || K <= 0 || (transA && transB)) return LG_ERR_INVALID_ARG;
-    const Plan pl = make_plan(M, N, K, transB != 0);
+    const Plan pl = make_plan(M, N, K, transB != 0, 0, !transA && !transB);
     const bool direct = pl.direct_nbw > 0;
     if (block_m) *block_m = direct ? 16 : kTiles[pl.tile].bm;
     if (block_n) *block_n = direct ? 16 * pl.direct_nbw : kTiles[pl.tile].bn;
@@ -273,15 +290,17 @@ extern "C" int lg_matmul_t(const float* A, const float* B, float* C,
 
 extern "C" int lg_gemm_variants(void) { return lg::kNumVariants; }
 
-extern "C" int lg_gemm_variant_info(int variant, int* block_m, int* block_n, int* block_k, int* k_parts) {
+extern "C" int lg_gemm_variant_info(int variant, int* block_m, int* block_n, int* block_k, int* k_parts,
+                                    int* tile_loop) {
     using namespace lg;
     Plan pl{};
     if (!forced_plan(1, 1, 1, variant, 1, &pl)) return LG_ERR_INVALID_ARG;
     const bool direct = pl.direct_nbw > 0;
-    if (block_m) *block_m = direct ? 16 : kTiles[variant].bm;
-    if (block_n) *block_n = direct ? 16 * pl.direct_nbw : kTiles[variant].bn;
-    if (block_k) *block_k = direct ? 16 : kTiles[variant].bk;
+    if (block_m) *block_m = direct ? 16 : kTiles[pl.tile].bm;
+    if (block_n) *block_n = direct ? 16 * pl.direct_nbw : kTiles[pl.tile].bn;
+    if (block_k) *block_k = direct ? 16 : kTiles[pl.tile].bk;
     if (k_parts) *k_parts = direct ? pl.direct_ks : 1;
+    if (tile_loop) *tile_loop = pl.persist_grid > 0;
     return LG_OK;
 }
 

@@ -10,6 +10,10 @@
 //                the multiply
 //   wavefront -> WM x WN register tile of 32x32 fp32 accumulators, v_mfma_f32_32x32x2_f32
 //   epilogue  -> accumulators (+ C) straight to global memory
+//   PERSIST   -> a grid smaller than the tile count: each workgroup walks over several tiles and starts the
+//                transfers of its next tile before (or while) it finishes the current one, so that the
+//                output stores drain under the next tile's multiplications (short contractions with a
+//                large output, where writing C costs as much as computing it)
 //
 // An operand slice comes in one of two kinds, by which of its two axes is contiguous in memory:
 //   R-kind (k contiguous: A of AB and A B^T, B of A B^T): LDS holds [rows][BK], the float4 column
@@ -76,9 +80,10 @@ struct Tile {
     template <bool VEC> __device__ static __forceinline__ int r_off(int r, int q) { return r * BK + ((q ^ swizzle<VEC>(r)) << 2); }
 };
 
-template <class T, bool VEC, bool CONV, bool TA, bool TB>
+template <class T, bool VEC, bool CONV, bool TA, bool TB, bool PERSIST = false>
 __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArgs p) {
     static_assert(!(CONV && (TA || TB)) && !(TA && TB), "supported operand layouts");
+    static_assert(!PERSIST || (VEC && !CONV && !TA && !TB), "tile loop: aligned AB only");
     constexpr int BM = T::BM, BN = T::BN, BK = T::BK, MB = T::MB, NB = T::NB, NTH = T::THREADS;
     constexpr int APT = T::A_PER_T, BPT = T::B_PER_T;
     extern __shared__ __align__(16) float lds[];
@@ -87,14 +92,24 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
 
     // ---- which tile ------------------------------------------------------------------------
     const unsigned ntiles = p.tiles_m * p.tiles_n;
-    const unsigned L = xcd_contiguous_id(blockIdx.x, ntiles);
     constexpr unsigned GM = 8;     // tile rows per panel: the ~64 workgroups an XCD runs at once form an 8 x 8 block of tiles
-    const unsigned panel = L / (GM * p.tiles_n);
-    const unsigned first_m = panel * GM;
-    const unsigned gsz = (p.tiles_m - first_m < GM) ? p.tiles_m - first_m : GM;
-    const unsigned in_panel = L - panel * GM * p.tiles_n;
-    const int64_t m0 = (int64_t)(first_m + in_panel % gsz) * BM;
-    const int64_t n0 = (int64_t)(in_panel / gsz) * BN;
+    // Tile number v (a workgroup id, or with PERSIST one of blockIdx.x + i * gridDim.x: the grid is a multiple
+    // of the XCD count, so all of a workgroup's tiles belong to its XCD's range) -> tile origin and the
+    // rows / columns of the tile inside the matrix.
+    int64_t m0, n0, m_valid, n_valid;
+    auto place_tile = [&](unsigned v) {
+        const unsigned L = xcd_contiguous_id(v, ntiles);
+        const unsigned panel = L / (GM * p.tiles_n);
+        const unsigned first_m = panel * GM;
+        const unsigned gsz = (p.tiles_m - first_m < GM) ? p.tiles_m - first_m : GM;
+        const unsigned in_panel = L - panel * GM * p.tiles_n;
+        m0 = (int64_t)(first_m + in_panel % gsz) * BM;
+        n0 = (int64_t)(in_panel / gsz) * BN;
+        m_valid = (p.M - m0 < BM) ? p.M - m0 : BM;
+        n_valid = (p.N - n0 < BN) ? p.N - n0 : BN;
+    };
+    unsigned vtile = blockIdx.x;
+    place_tile(vtile);
     const int64_t kbeg = (int64_t)blockIdx.y * p.k_per_split;
     const int64_t kend = (kbeg + p.k_per_split < p.K) ? kbeg + p.k_per_split : p.K;
     const int nslices = (int)((kend - kbeg + BK - 1) / BK);
@@ -124,25 +139,28 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
     // R-kind row bases (element offset of the row's k = 0; -1 when the row is outside the matrix)
     int64_t a_rowbase[TA ? 1 : APT];
     int64_t b_rowbase[TB ? BPT : 1];
-    if constexpr (!TA) {
+    auto row_bases = [&]() {
+        if constexpr (!TA) {
 #pragma unroll
-        for (int i = 0; i < APT; ++i) {
-            const int64_t m = m0 + r0 + i * T::ROW_STEP;
-            if (m >= p.M) { a_rowbase[i] = -1; continue; }
-            if constexpr (CONV) {
-                a_rowbase[i] = conv_row_base(m);
-            } else {
-                a_rowbase[i] = m * p.lda;
+            for (int i = 0; i < APT; ++i) {
+                const int64_t m = m0 + r0 + i * T::ROW_STEP;
+                if (m >= p.M) { a_rowbase[i] = -1; continue; }
+                if constexpr (CONV) {
+                    a_rowbase[i] = conv_row_base(m);
+                } else {
+                    a_rowbase[i] = m * p.lda;
+                }
             }
         }
-    }
-    if constexpr (TB) {
+        if constexpr (TB) {
 #pragma unroll
-        for (int i = 0; i < BPT; ++i) {
-            const int64_t n = n0 + r0 + i * T::ROW_STEP;
-            b_rowbase[i] = n < p.N ? n * p.ldb : -1;
+            for (int i = 0; i < BPT; ++i) {
+                const int64_t n = n0 + r0 + i * T::ROW_STEP;
+                b_rowbase[i] = n < p.N ? n * p.ldb : -1;
+            }
         }
-    }
+    };
+    row_bases();
     float4 ra[APT], rb[BPT];
 
     auto conv_koff = [&](int64_t k) -> int64_t {   // conv: offset of GEMM column k relative to the row base
@@ -295,9 +313,9 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
             }
         }
     };
-    const int64_t m_valid = (p.M - m0 < BM) ? p.M - m0 : BM;
-    const int64_t n_valid = (p.N - n0 < BN) ? p.N - n0 : BN;
     auto init_full = [&]() {
+        a_base = reinterpret_cast<const char*>(p.A);
+        b_base = reinterpret_cast<const char*>(p.B);
         if constexpr (CONV) {
             // lane offsets are relative to the tile's first row, so only the tile has to span < 2 GiB
             const int64_t base0 = to_scalar(conv_row_base(m0));
@@ -366,17 +384,20 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
         auto dma = [&](const void* base, uint32_t voff, uint32_t lds_a) __attribute__((always_inline)) {
             if constexpr (VEC) dma16(base, voff, lds_a); else dma4(base, voff, lds_a);
         };
+        // (in the tile loop the bases are carried from tile to tile: say again that they are uniform)
+        const char* a_sb = PERSIST ? reinterpret_cast<const char*>(to_scalar(reinterpret_cast<int64_t>(a_base))) : a_base;
+        const char* b_sb = PERSIST ? reinterpret_cast<const char*>(to_scalar(reinterpret_cast<int64_t>(b_base))) : b_base;
         if (CONV && conv_uniform) {
-            const char* ab = a_base + su_off;
+            const char* ab = a_sb + su_off;
 #pragma unroll
             for (int i = 0; i < APD; ++i) dma(ab, a_loff[i], lds_addr(as + WORDS * i * NTH));
         } else {
             const uint32_t ko = CONV ? cv_off : 0u;
 #pragma unroll
-            for (int i = 0; i < APD; ++i) dma(a_base, a_loff[i] + ko, lds_addr(as + WORDS * i * NTH));
+            for (int i = 0; i < APD; ++i) dma(a_sb, a_loff[i] + ko, lds_addr(as + WORDS * i * NTH));
         }
 #pragma unroll
-        for (int i = 0; i < BPD; ++i) dma(b_base, b_loff[i], lds_addr(bs + WORDS * i * NTH));
+        for (int i = 0; i < BPD; ++i) dma(b_sb, b_loff[i], lds_addr(bs + WORDS * i * NTH));
         if (CONV && conv_uniform) {
             su_c += BK;
             const bool w1 = su_c >= cvC;
@@ -557,37 +578,107 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
     // ---- main loop --------------------------------------------------------------------------
     // The interior path addresses operands with 32-bit byte offsets from the tile origin.
     const int64_t lim = (int64_t)1 << 31;
-    bool a_small;
-    if constexpr (CONV) {      // rows of the tile x the filter's reach, from the tile's first row
-        const int64_t last = (m0 + BM <= p.M) ? m0 + BM - 1 : p.M - 1;
-        const int64_t kh_taps = p.K / (p.g.KW * p.g.C);
-        const int64_t reach = ((kh_taps - 1) * p.g.DH * p.g.W + (p.g.KW - 1) * p.g.DW + 1) * p.g.C;
-        a_small = (conv_row_base(last) - conv_row_base(m0) + reach + BK) * 4 < lim;
-    } else {
-        a_small = (int64_t)(TA ? BK : BM) * p.lda * 4 < lim;
-    }
     const bool b_small = (int64_t)(TB ? BN : BK) * p.ldb * 4 < lim;
     // All tiles (boundary tiles included, see r_loff) run their whole slices through the transfer rings
     // below -- 16 bytes per lane for aligned operands, 4 otherwise -- and a k tail (a slab whose depth
     // is not a multiple of BK) as one last predicated, register-staged slice.  Left to the
     // register-staged path: spans beyond 32-bit offsets.
-    // (the flag is wave-uniform; readfirstlane says so to the compiler where 32-bit divisions left it
-    // in vector registers, so that the branches below stay scalar)
-    const bool interior = __builtin_amdgcn_readfirstlane(
-        (int)(a_small && b_small && (T::KTAIL || (kend - kbeg) % BK == 0))) != 0;
-    const int nring = interior ? (int)((kend - kbeg) / BK) : 0;
-    const bool ktail = T::KTAIL && interior && (kend - kbeg) % BK != 0;
-    {
-        if (nring > 0 && T::STAGES == 4) {
+    bool interior, ktail;
+    int nring;
+    auto classify = [&]() {
+        bool a_small;
+        if constexpr (CONV) {      // rows of the tile x the filter's reach, from the tile's first row
+            const int64_t last = (m0 + BM <= p.M) ? m0 + BM - 1 : p.M - 1;
+            const int64_t kh_taps = p.K / (p.g.KW * p.g.C);
+            const int64_t reach = ((kh_taps - 1) * p.g.DH * p.g.W + (p.g.KW - 1) * p.g.DW + 1) * p.g.C;
+            a_small = (conv_row_base(last) - conv_row_base(m0) + reach + BK) * 4 < lim;
+        } else {
+            a_small = (int64_t)(TA ? BK : BM) * p.lda * 4 < lim;
+        }
+        // (the flag is wave-uniform; readfirstlane says so to the compiler where 32-bit divisions left it
+        // in vector registers, so that the branches below stay scalar)
+        interior = __builtin_amdgcn_readfirstlane(
+            (int)(a_small && b_small && (T::KTAIL || (kend - kbeg) % BK == 0))) != 0;
+        nring = interior ? (int)((kend - kbeg) / BK) : 0;
+        ktail = T::KTAIL && interior && (kend - kbeg) % BK != 0;
+    };
+    classify();
+    constexpr int LT = APD + BPD;              // transfers per slice per wave
+    // The first slices of a tile: as many as the ring keeps in flight, into stages 0, 1, (2).
+    auto prologue = [&]() {
+        init_full();
+        issue_slice(0);
+        if (nring > 1) issue_slice(1);
+        if (T::STAGES == 4 && nring > 2) issue_slice(2);
+    };
+
+    // The tile loop (PERSIST; without it the body runs once).  What it is for: a wave's stores and
+    // transfers complete in the order issued, so a wait for a transfer also waits for every store issued
+    // before it.  The next tile's first transfers are therefore issued BEFORE this tile's stores, and
+    // the waits that follow name the stores in their counts, so that the stores drain while the next
+    // tile is multiplied.  Those counts must be exact: they are only used after an epilogue that issued
+    // exactly NST stores per lane (the whole tile inside C, nothing to accumulate, nothing predicated).
+    // Two forms:
+    //   continuous -- four-stage ring, slices per tile a multiple of four (so every tile starts at stage 0):
+    //       the ring runs on across tiles; the last three steps of a tile issue the next tile's slices
+    //       0 .. 2, and the wave arrives at the next tile with that tile's first fragments in registers;
+    //   ahead      -- otherwise: after the last step the next tile's prologue is issued, then the stores.
+    constexpr bool kCanOverlap = PERSIST && VEC && !TB && (NB == 4 || NB == 2);
+    constexpr int NST = MB * 16;               // stores per lane of an unpredicated epilogue
+    static_assert(!kCanOverlap || LT + NST <= 63, "the wait counter holds 63");
+    bool ahead = false;        // this tile's prologue was issued before the last tile's NST stores
+    bool cont = false;         // continuous form: this tile's slices 0 .. 2 are issued, its first fragments fetched
+    bool counted = false;      // ... and exactly NST stores of the last tile follow slice 2 in issue order
+    for (;;) {
+        const unsigned vnext = vtile + gridDim.x;
+        const bool has_next = PERSIST && vnext < ntiles;
+        const int64_t em0 = m0, en0 = n0;              // the epilogue's tile (the transfers may move on before it)
+        const bool whole = m_valid == BM && n_valid == BN && !p.accumulate;
+        // (a k tail is staged through stage 0 after the ring: the ring must not have moved on by then)
+        const bool continuous = kCanOverlap && T::STAGES == 4 && nring >= 4 && nring % 4 == 0 && !ktail;
+        if (continuous) {
+            if (!cont) {
+                prologue();
+                dma_wait<LT>();
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                fetch_R(0, 0);
+                fetch_C(0, 0, 0);
+            }
+            auto step = [&](auto stage_c, int s) {
+                constexpr int stage = decltype(stage_c)::value;
+                if (s + 3 == nring && has_next) {      // from here on the transfers belong to the next tile
+                    place_tile(vnext);
+                    init_full();
+                }
+                const bool issued = s + 3 < nring || has_next;
+                if (issued) issue_slice((stage + 3) % 4);
+                compute_slice_ahead(stage, (stage + 1) % 4, stage & 1);
+                if (s + 2 < nring || has_next) {
+                    if (!issued) dma_wait<0>();
+                    else if (s == 0 && counted) dma_wait<LT + NST>();   // slice 2, the last tile's stores, slice 3
+                    else dma_wait<LT>();
+                    __builtin_amdgcn_s_barrier();
+                    asm volatile("" ::: "memory");
+                }
+            };
+            for (int s = 0; s < nring; s += 4) {
+                step(std::integral_constant<int, 0>{}, s);
+                step(std::integral_constant<int, 1>{}, s + 1);
+                step(std::integral_constant<int, 2>{}, s + 2);
+                step(std::integral_constant<int, 3>{}, s + 3);
+            }
+        } else if (nring > 0 && T::STAGES == 4) {
             // Ring of four LDS stages, transfers three slices ahead.  The barrier that ends step s makes
             // slice s+2 visible (each wave first waits for its own transfers of that slice), so during
             // step s+1 every wave may already read slice s+2.  It also guarantees that nobody still
             // reads slice s, whose stage the transfer issued in step s+1 refills.
-            constexpr int L = APD + BPD;           // transfers per slice per wave
-            init_full();
-            issue_slice(0);
-            if (nring > 1) issue_slice(1);
-            if (nring > 2) { issue_slice(2); dma_wait<L>(); } else { dma_wait<0>(); }
+            if (!ahead) {
+                prologue();
+                if (nring > 2) dma_wait<LT>(); else dma_wait<0>();
+            } else {                                   // slices 0, 1, (2), then NST stores; 0 and 1 are needed
+                if (nring > 2) dma_wait<LT + NST>(); else dma_wait<NST>();
+            }
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
             fetch_R(0, 0);
@@ -597,7 +688,7 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
                 if (s + 3 < nring) issue_slice((stage + 3) % 4);
                 compute_slice_ahead(stage, (stage + 1) % 4, stage & 1);
                 if (s + 2 < nring) {
-                    if (s + 3 < nring) dma_wait<L>(); else dma_wait<0>();
+                    if (s + 3 < nring) dma_wait<LT>(); else dma_wait<0>();
                     __builtin_amdgcn_s_barrier();
                     asm volatile("" ::: "memory");
                 }
@@ -616,14 +707,11 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
             // Ring of three LDS stages, transfers two slices ahead.  Each wave waits for its own
             // transfers of the slice needed next (vmcnt counts them in order), then the barrier makes
             // everybody's visible and also guarantees nobody still reads the stage refilled next.
-            constexpr int L = APD + BPD;           // transfers per slice per wave
-            init_full();
-            issue_slice(0);
-            if (nring > 1) {
-                issue_slice(1);
-                dma_wait<L>();
-            } else {
-                dma_wait<0>();
+            if (!ahead) {
+                prologue();
+                if (nring > 1) dma_wait<LT>(); else dma_wait<0>();
+            } else {                                   // slices 0, (1), then NST stores; 0 is needed
+                if (nring > 1) dma_wait<LT + NST>(); else dma_wait<NST>();
             }
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
@@ -634,7 +722,7 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
                 if (s + 2 < nring) issue_slice((stage + 2) % 3);
                 compute_slice(stage);
                 if (s + 1 < nring) {
-                    if (s + 2 < nring) dma_wait<L>(); else dma_wait<0>();
+                    if (s + 2 < nring) dma_wait<LT>(); else dma_wait<0>();
                     __builtin_amdgcn_s_barrier();
                     asm volatile("" ::: "memory");
                 }
@@ -667,94 +755,141 @@ __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArg
             __syncthreads();
             compute_slice(0);
         }
-    }
 
-    // ---- epilogue ------------------------------------------------------------------------------
-    // accumulator register r of block (mb, nb): row = 32*mb + 8*(r/4) + 4*h + r%4;
-    // column = NB*c32 + nb (interleaved, C-kind B) or nb*32 + c32 (R-kind B)
-    float* Cz = p.C + (int64_t)blockIdx.y * p.M * p.ldc;
-    if constexpr (!VEC && !TB && NB > 1) {
-        // An output that cannot take 128-bit stores: written straight from the accumulators, the lanes
-        // of a store would sit NB columns apart (1/NB-dense instructions).  Each wavefront instead
-        // turns one 32 x WN block at a time around in its own piece of LDS (the ring is done) and
-        // writes whole rows: 64 adjacent floats per store instruction.
-        constexpr int WN = T::WN;
-        static_assert(T::WAVES * 32 * WN <= T::LDS_FLOATS, "the staging blocks must fit the ring's LDS");
-        __syncthreads();                               // every wave is done reading the ring's stages
-        float* ws = lds + wave * (32 * WN);
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float* q = ws + (8 * (r / 4) + 4 * h + (r % 4)) * WN + NB * c32;
-                if constexpr (NB == 4) *reinterpret_cast<float4*>(q) = make_float4(acc[mb][0][r], acc[mb][1][r], acc[mb][2][r], acc[mb][3][r]);
-                else                   *reinterpret_cast<float2*>(q) = make_float2(acc[mb][0][r], acc[mb][1][r]);
-            }
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (int it = 0; it < 32 * WN / kWave; ++it) {
-                const int idx = it * kWave + lane;
-                const int64_t m = m0 + wm0 + mb * 32 + idx / WN;
-                const int64_t n = n0 + wn0 + idx % WN;
-                const float v = ws[idx];
-                if (m < p.M && n < p.N) {
-                    float* cp = Cz + m * p.ldc + n;
-                    *cp = p.accumulate ? *cp + v : v;
+        // ---- the workgroup's next tile ------------------------------------------------------------
+        ahead = false;
+        cont = false;
+        counted = false;
+        if constexpr (PERSIST) {
+            if (continuous && has_next) {          // already placed, its slices 0 .. 2 on their way
+                cont = true;
+                counted = whole;
+            } else if (has_next) {
+                __syncthreads();                   // every wave is done reading the ring's stages
+                place_tile(vnext);
+                row_bases();
+                classify();
+                if (kCanOverlap && whole && nring > 0) {   // (not continuous: every tile has this tile's nring)
+                    prologue();
+                    ahead = true;
                 }
             }
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            __builtin_amdgcn_wave_barrier();
+            vtile = vnext;
         }
-        return;
-    }
+        const bool unpredicated = cont ? counted : ahead;
+
+        // ---- epilogue ------------------------------------------------------------------------------
+        // accumulator register r of block (mb, nb): row = 32*mb + 8*(r/4) + 4*h + r%4;
+        // column = NB*c32 + nb (interleaved, C-kind B) or nb*32 + c32 (R-kind B)
+        float* Cz = p.C + (int64_t)blockIdx.y * p.M * p.ldc;
+        if constexpr (!VEC && !TB && NB > 1) {
+            // An output that cannot take 128-bit stores: written straight from the accumulators, the lanes
+            // of a store would sit NB columns apart (1/NB-dense instructions).  Each wavefront instead
+            // turns one 32 x WN block at a time around in its own piece of LDS (the ring is done) and
+            // writes whole rows: 64 adjacent floats per store instruction.
+            constexpr int WN = T::WN;
+            static_assert(T::WAVES * 32 * WN <= T::LDS_FLOATS, "the staging blocks must fit the ring's LDS");
+            __syncthreads();                               // every wave is done reading the ring's stages
+            float* ws = lds + wave * (32 * WN);
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
+            for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int64_t m = m0 + wm0 + mb * 32 + 8 * (r / 4) + 4 * h + (r % 4);
-            if (m >= p.M) continue;
-            float v[NB];
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) v[nb] = acc[mb][nb][r];
-            if constexpr (TB) {
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    const int64_t n = n0 + wn0 + nb * 32 + c32;
-                    float* cp = Cz + m * p.ldc + n;
-                    if (n < p.N) *cp = p.accumulate ? *cp + v[nb] : v[nb];
+                for (int r = 0; r < 16; ++r) {
+                    float* q = ws + (8 * (r / 4) + 4 * h + (r % 4)) * WN + NB * c32;
+                    if constexpr (NB == 4) *reinterpret_cast<float4*>(q) = make_float4(acc[mb][0][r], acc[mb][1][r], acc[mb][2][r], acc[mb][3][r]);
+                    else                   *reinterpret_cast<float2*>(q) = make_float2(acc[mb][0][r], acc[mb][1][r]);
                 }
-            } else {
-                const int64_t ncol = n0 + wn0 + NB * c32;
-                float* cp = Cz + m * p.ldc + ncol;
-                if constexpr (VEC && NB == 4) {
-                    if (ncol < p.N) {
-                        float4 o = make_float4(v[0], v[1], v[2], v[3]);
-                        if (p.accumulate) {
-                            const float4 c = *reinterpret_cast<const float4*>(cp);
-                            o.x += c.x; o.y += c.y; o.z += c.z; o.w += c.w;
-                        }
-                        // written once, never read back here: stream it past the caches that hold A and B
-                        __builtin_nontemporal_store(f32x4{o.x, o.y, o.z, o.w}, reinterpret_cast<f32x4*>(cp));
-                    }
-                } else if constexpr (VEC && NB == 2) {
-                    if (ncol < p.N) {
-                        float2 o = make_float2(v[0], v[1]);
-                        if (p.accumulate) {
-                            const float2 c = *reinterpret_cast<const float2*>(cp);
-                            o.x += c.x; o.y += c.y;
-                        }
-                        __builtin_nontemporal_store(f32x2{o.x, o.y}, reinterpret_cast<f32x2*>(cp));
-                    }
-                } else {
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();
 #pragma unroll
-                    for (int nb = 0; nb < NB; ++nb)
-                        if (ncol + nb < p.N) cp[nb] = p.accumulate ? cp[nb] + v[nb] : v[nb];
+                for (int it = 0; it < 32 * WN / kWave; ++it) {
+                    const int idx = it * kWave + lane;
+                    const int64_t m = em0 + wm0 + mb * 32 + idx / WN;
+                    const int64_t n = en0 + wn0 + idx % WN;
+                    const float v = ws[idx];
+                    if (m < p.M && n < p.N) {
+                        float* cp = Cz + m * p.ldc + n;
+                        *cp = p.accumulate ? *cp + v : v;
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+            }
+        } else if (kCanOverlap && unpredicated) {
+            // the whole tile, overwritten: exactly NST store instructions per lane (the waits above count them)
+            if constexpr (kCanOverlap) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int64_t m = em0 + wm0 + mb * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+                        float* cp = Cz + m * p.ldc + en0 + wn0 + NB * c32;
+                        if constexpr (NB == 4)
+                            __builtin_nontemporal_store(f32x4{acc[mb][0][r], acc[mb][1][r], acc[mb][2][r], acc[mb][3][r]},
+                                                        reinterpret_cast<f32x4*>(cp));
+                        else
+                            __builtin_nontemporal_store(f32x2{acc[mb][0][r], acc[mb][1][r]}, reinterpret_cast<f32x2*>(cp));
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t m = em0 + wm0 + mb * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+                    if (m >= p.M) continue;
+                    float v[NB];
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) v[nb] = acc[mb][nb][r];
+                    if constexpr (TB) {
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb) {
+                            const int64_t n = en0 + wn0 + nb * 32 + c32;
+                            float* cp = Cz + m * p.ldc + n;
+                            if (n < p.N) *cp = p.accumulate ? *cp + v[nb] : v[nb];
+                        }
+                    } else {
+                        const int64_t ncol = en0 + wn0 + NB * c32;
+                        float* cp = Cz + m * p.ldc + ncol;
+                        if constexpr (VEC && NB == 4) {
+                            if (ncol < p.N) {
+                                float4 o = make_float4(v[0], v[1], v[2], v[3]);
+                                if (p.accumulate) {
+                                    const float4 c = *reinterpret_cast<const float4*>(cp);
+                                    o.x += c.x; o.y += c.y; o.z += c.z; o.w += c.w;
+                                }
+                                // written once, never read back here: stream it past the caches that hold A and B
+                                __builtin_nontemporal_store(f32x4{o.x, o.y, o.z, o.w}, reinterpret_cast<f32x4*>(cp));
+                            }
+                        } else if constexpr (VEC && NB == 2) {
+                            if (ncol < p.N) {
+                                float2 o = make_float2(v[0], v[1]);
+                                if (p.accumulate) {
+                                    const float2 c = *reinterpret_cast<const float2*>(cp);
+                                    o.x += c.x; o.y += c.y;
+                                }
+                                __builtin_nontemporal_store(f32x2{o.x, o.y}, reinterpret_cast<f32x2*>(cp));
+                            }
+                        } else {
+#pragma unroll
+                            for (int nb = 0; nb < NB; ++nb)
+                                if (ncol + nb < p.N) cp[nb] = p.accumulate ? cp[nb] + v[nb] : v[nb];
+                        }
+                    }
                 }
             }
         }
+        if (!has_next) break;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
     }
 }
+
 
 // ---- the tile menu ----------------------------------------------------------------------------------
 // All tiles: 4 wavefronts, one per SIMD.  The big tile keeps three LDS stages: a fourth would cost it
@@ -769,23 +904,37 @@ using Tile5 = Tile<64, 64, 32, 32, 32, 2, 4>;      // waves of 32x32, deeper sli
 using Tile6 = Tile<128, 32, 32, 32, 32, 2, 3>;     // four waves of 32x32 stacked along m: tall products with few columns
 using Tile7 = Tile<32, 128, 32, 32, 32, 2, 3>;     // four waves of 32x32 side by side: a few rows times a large matrix
 
+// The tiles compiled with the tile loop as well (aligned AB only): see make_plan for when it is used.
+template <class T> constexpr bool kHasTileLoop = std::is_same_v<T, Tile1> || std::is_same_v<T, Tile2> || std::is_same_v<T, Tile4>;
+
+// `persist_grid` > 0: that many workgroups (a multiple of the XCD count, fewer than there are tiles) walk
+// over the tiles, where the tile loop is compiled; one workgroup per tile otherwise.
 template <class T, bool VEC, bool CONV, bool TA, bool TB>
-static void launch_gemm(const GemmArgs& a, unsigned splits, hipStream_t s) {
-    static DeviceFlags configured = {};
+static void launch_gemm(const GemmArgs& a, unsigned splits, unsigned persist_grid, hipStream_t s) {
     const size_t lds_bytes = T::LDS_FLOATS * sizeof(float);
+    const unsigned ntiles = a.tiles_m * a.tiles_n;
+    if constexpr (VEC && !CONV && !TA && !TB && kHasTileLoop<T>) {
+        const unsigned grid = persist_grid / kXcds * kXcds;
+        if (grid > 0 && grid < ntiles && splits == 1) {
+            static DeviceFlags configured_loop = {};
+            allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_kernel<T, VEC, CONV, TA, TB, true>), lds_bytes, configured_loop);
+            hipLaunchKernelGGL((gemm_kernel<T, VEC, CONV, TA, TB, true>), dim3(grid, 1), dim3(T::THREADS), lds_bytes, s, a);
+            return;
+        }
+    }
+    static DeviceFlags configured = {};
     allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_kernel<T, VEC, CONV, TA, TB>), lds_bytes, configured);
-    hipLaunchKernelGGL((gemm_kernel<T, VEC, CONV, TA, TB>), dim3(a.tiles_m * a.tiles_n, splits), dim3(T::THREADS),
-                       lds_bytes, s, a);
+    hipLaunchKernelGGL((gemm_kernel<T, VEC, CONV, TA, TB>), dim3(ntiles, splits), dim3(T::THREADS), lds_bytes, s, a);
 }
 
 // Launch the planned tile of one operand-layout variant (the split-k combine is the caller's job).
 template <bool CONV, bool TA, bool TB>
 static void launch_planned(const GemmArgs& a, const Plan& pl, bool vec, hipStream_t s) {
-    const unsigned z = (unsigned)pl.splits;
+    const unsigned z = (unsigned)pl.splits, pg = (unsigned)pl.persist_grid;
 #define LG_LAUNCH(TILE)                                                        \
     do {                                                                       \
-        if (vec) launch_gemm<TILE, true, CONV, TA, TB>(a, z, s);               \
-        else     launch_gemm<TILE, false, CONV, TA, TB>(a, z, s);              \
+        if (vec) launch_gemm<TILE, true, CONV, TA, TB>(a, z, pg, s);           \
+        else     launch_gemm<TILE, false, CONV, TA, TB>(a, z, pg, s);          \
     } while (0)
     switch (pl.tile) {
         case 0: LG_LAUNCH(Tile0); break;

@@ -48,6 +48,7 @@ static const TileInfo kTiles[kNumTiles] = {
 struct Plan {
     int tile;          // index into kTiles
     int64_t tiles_m, tiles_n, splits, k_per_split;
+    int64_t persist_grid;  // > 0: that many workgroups walk over the tiles (the kernel's tile loop); 0: one per tile
     int direct_nbw;    // > 0: the register-direct kernel (gemm_direct.hip) with blocks 16 x 16*direct_nbw ...
     int direct_ks;     // ... and the k range cut into this many parts inside a workgroup; `tile` etc. unused
 };
@@ -55,12 +56,23 @@ struct Plan {
 constexpr int kCUs = 256;
 constexpr int kKGran = 64;   // split-k slabs are multiples of this (a multiple of every tile's BK)
 
+// The tiles compiled with the tile loop (gemm_kernel.hpp) and the grid it runs on: as many workgroups as
+// the chip holds at once.
+constexpr int kNumLoopTiles = 3;
+static const int kLoopTiles[kNumLoopTiles] = {1, 2, 4};
+// fraction of the matrix-pipe rate each sustains in the loop (three 128 x 64 workgroups per CU cover one
+// another's tile changes better than two of the larger tiles do)
+static const double kLoopEff[kNumLoopTiles] = {0.93, 0.98, 0.87};
+inline int64_t loop_grid(int tile) { return (int64_t)kTiles[tile].occ * kCUs; }
+
 // Pick (tile, k-split) with a cost model fitted to measurements on this part: when c workgroups
 // share a CU, one k-slice of all of them takes  c * mfma / eff + dead / c  clocks.  Each round of
 // workgroups on a CU also pays `fill`: start-up, and the output write, which is HBM-bound because
 // the workgroups of a round reach their epilogues together (~9 bytes per clock per CU).  The busiest CU decides; a launch costs ~4 us of fill and drain;
 // split-k adds the partial-sum traffic and a second launch.
-inline Plan make_plan(int64_t M, int64_t N, int64_t K, bool b_along_k = false, int64_t conv_c = 0) {
+// `tile_loop`: the product is an AB with aligned operands, for which the tile loop is compiled.
+inline Plan make_plan(int64_t M, int64_t N, int64_t K, bool b_along_k = false, int64_t conv_c = 0,
+                      bool tile_loop = false) {
     const double clk = 2.4e9;
     const int64_t kslabs = cdiv(K, kKGran);
     static const int split_menu[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
@@ -102,6 +114,35 @@ inline Plan make_plan(int64_t M, int64_t N, int64_t K, bool b_along_k = false, i
             if (cost < best_cost) {
                 best_cost = cost;
                 best.tile = ti; best.tiles_m = tm; best.tiles_n = tn; best.splits = splits; best.k_per_split = kps;
+            }
+        }
+    }
+    // The tile loop, for short contractions with a large output: one tile per workgroup pays for the
+    // multiplications and for writing C one after the other (the workgroups of a round reach their
+    // epilogues together; 4096 x 4096 x 64: 17 us without its stores, 12 us for the stores alone, 28-30 us
+    // together), walking over the tiles hides part of the stores under the next tile.  Fitted to
+    // 4096 x 4096 x {16 ... 256}, 8192 x 8192 x 64 and others with the chip's fill of workgroups:
+    // the multiplications at kLoopEff of the matrix-pipe rate plus 0.74 of the output's time at 6.7 TB/s (the
+    // write-only stream rate), never less than 1.33 of the latter, plus 3.3 us.  Measured gains: K = 64
+    // 30 -> 23 us, K = 128 43 -> 39, K = 256 70 -> 67, nothing from K = 512 on (and 1.5 % lost at
+    // 4096^3: the hardware dispatcher balances long tiles better than a fixed stride) -- hence the cap.
+    if (tile_loop && K <= 256 && K % 4 == 0 && N % 4 == 0) {
+        for (int i = 0; i < kNumLoopTiles; ++i) {
+            const TileInfo& tl = kTiles[kLoopTiles[i]];
+            if (K < tl.bk) continue;                           // no whole slice: nothing runs ahead
+            const int64_t tm = cdiv(M, tl.bm), tn = cdiv(N, tl.bn), grid = loop_grid(kLoopTiles[i]);
+            if (2 * tm * tn < 3 * grid) continue;              // fewer than 1.5 tiles per workgroup: nothing to overlap
+            const double mult = (double)cdiv(tm * tn, kCUs) * (double)cdiv(K, tl.bk) * tl.mfma / kLoopEff[i] / clk;
+            const double write = (double)M * (double)N * 4.0 / 6.7e12;
+            double cost = mult + 0.74 * write;
+            if (cost < 1.33 * write) cost = 1.33 * write;
+            cost += 3.3e-6;
+            if (cost < best_cost) {
+                best_cost = cost;
+                best = Plan{};
+                best.tile = kLoopTiles[i]; best.tiles_m = tm; best.tiles_n = tn; best.splits = 1;
+                best.k_per_split = cdiv(K, kKGran) * kKGran;
+                best.persist_grid = grid;
             }
         }
     }

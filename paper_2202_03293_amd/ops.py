@@ -21,8 +21,9 @@ _SIGNATURES = {
     "lg_matmul_workspace_bytes": (_sz, [_i64] * 3),
     "lg_matmul_plan": (_int, [_i64] * 3 + [ctypes.POINTER(_int)] * 3),
     "lg_matmul_t_plan": (_int, [_i64] * 3 + [_int, _int] + [ctypes.POINTER(_int)] * 3),
+    "lg_matmul_plan_tile_loop": (_int, [_i64] * 3),
     "lg_gemm_variants": (_int, []),
-    "lg_gemm_variant_info": (_int, [_int] + [ctypes.POINTER(_int)] * 4),
+    "lg_gemm_variant_info": (_int, [_int] + [ctypes.POINTER(_int)] * 5),
     "lg_gemm_variant_workspace_bytes": (_sz, [_i64] * 3 + [_int, _int]),
     "lg_matmul_variant": (_int, [_vp, _vp, _vp] + [_i64] * 6 + [_int] * 5 + [_vp, _sz, _vp]),
     "lg_conv2d_nhwc_hwcf_variant": (_int, [_vp, _vp, _vp] + [_i64] * 11 + [_int] * 3 + [_vp, _sz, _vp]),
@@ -176,14 +177,19 @@ def lg_matmul_t(A, B, C, trans_a=False, trans_b=False, accumulate=False, workspa
     return C
 
 
+def lg_matmul_plan_tile_loop(M, N, K):
+    """Whether lg_matmul's plan for (M, N, K) walks several tiles per workgroup."""
+    return bool(lib().lg_matmul_plan_tile_loop(M, N, K))
+
+
 def lg_gemm_variants():
     """Number of compiled GEMM decompositions; variants are numbered from 0."""
     return lib().lg_gemm_variants()
 
 
 def lg_gemm_variant_info(variant):
-    """(block_m, block_n, block_k, k_parts) of a variant."""
-    v = [_int() for _ in range(4)]
+    """(block_m, block_n, block_k, k_parts, tile_loop) of a variant."""
+    v = [_int() for _ in range(5)]
     _check("lg_gemm_variant_info", lib().lg_gemm_variant_info(variant, *[ctypes.byref(x) for x in v]))
     return tuple(x.value for x in v)
 

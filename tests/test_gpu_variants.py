@@ -1,7 +1,8 @@
 """GPU parity of every GEMM kernel variant on shapes the planner would never give it: each of the
-eight LDS tiles (with and without a k-split) and each register-direct variant runs ragged, tiny and
-unaligned matmuls in the three layouts and convolutions with aligned and odd channel counts,
-against the CPU oracle on the same seeded inputs, between canary guard bands."""
+eight LDS tiles (with and without a k-split), each register-direct variant and each tile-loop variant
+runs ragged, tiny and unaligned matmuls in the three layouts and convolutions with aligned and odd
+channel counts, against the CPU oracle on the same seeded inputs, between canary guard bands; the
+tile-loop variants also run shapes with several output blocks per workgroup."""
 import numpy as np
 import pytest
 import torch
@@ -11,7 +12,7 @@ from gpu_util import Guarded, assert_close, dev, workspace
 
 pytestmark = pytest.mark.gpu
 
-N_VARIANTS = 17            # checked against the library in test_variant_menu
+N_VARIANTS = 20            # checked against the library in test_variant_menu
 
 
 @pytest.fixture(scope="module")
@@ -25,14 +26,17 @@ def test_variant_menu(lg):
     assert lg.lg_gemm_variants() == N_VARIANTS
     infos = [lg.lg_gemm_variant_info(v) for v in range(N_VARIANTS)]
     assert len(set(infos)) == N_VARIANTS                     # all different
-    assert sum(1 for bm, bn, bk, kp in infos if bm == 16) == 9
+    assert sum(1 for bm, bn, bk, kp, loop in infos if bm == 16) == 9
+    assert sum(1 for bm, bn, bk, kp, loop in infos if loop) == 3
     with pytest.raises(lg.LgError):
         lg.lg_gemm_variant_info(N_VARIANTS)
     a = torch.zeros((4, 4), device="cuda")
     with pytest.raises(lg.LgError):
         lg.lg_matmul_variant(a, a.clone(), torch.empty((4, 4), device="cuda"), N_VARIANTS)
-    with pytest.raises(lg.LgError):                          # the register-direct variants take no k-split
-        lg.lg_matmul_variant(a, a.clone(), torch.empty((4, 4), device="cuda"), N_VARIANTS - 1, k_splits=2)
+    for v in range(N_VARIANTS):                              # register-direct and tile-loop variants take no k-split
+        if infos[v][0] == 16 or infos[v][4]:
+            with pytest.raises(lg.LgError):
+                lg.lg_matmul_variant(a, a.clone(), torch.empty((4, 4), device="cuda"), v, k_splits=2)
 
 
 # (M, N, K, layout, accumulate, padded leading dimensions)
@@ -52,7 +56,8 @@ MATMUL_SHAPES = [
 @pytest.mark.parametrize("variant", range(N_VARIANTS))
 @pytest.mark.parametrize("M,N,K,layout,accumulate,padded", MATMUL_SHAPES)
 def test_matmul_every_variant(lg, lgo, variant, M, N, K, layout, accumulate, padded):
-    direct = lg.lg_gemm_variant_info(variant)[0] == 16
+    info = lg.lg_gemm_variant_info(variant)
+    direct = info[0] == 16 or info[4] == 1                   # no k-split
     A, B = si.matmul_inputs(1200 + M, M, N, K, case=K % 7)
     C0 = si.uniform(1201, N, (M, N), -1, 1) if accumulate else None
     ref = lgo.matmul(A, B, C0.copy(), accumulate=True) if accumulate else lgo.matmul(A, B)
@@ -96,7 +101,8 @@ CONV_SHAPES = [
 @pytest.mark.parametrize("variant", range(N_VARIANTS))
 @pytest.mark.parametrize("N,H,W,C,F,KH,KW,st,dl,accumulate", CONV_SHAPES)
 def test_conv2d_every_variant(lg, lgo, variant, N, H, W, C, F, KH, KW, st, dl, accumulate):
-    direct = lg.lg_gemm_variant_info(variant)[0] == 16
+    info = lg.lg_gemm_variant_info(variant)
+    direct = info[0] == 16 or info[4] == 1                   # no k-split
     I, Kf = si.conv2d_inputs(1210 + C, N, H, W, C, F, KH, KW)
     OH, OW = lg.lg_conv_out_extent(H, KH, st[0], dl[0]), lg.lg_conv_out_extent(W, KW, st[1], dl[1])
     O0 = si.uniform(1211, F, (N, OH, OW, F), -1, 1) if accumulate else None
@@ -111,6 +117,60 @@ def test_conv2d_every_variant(lg, lgo, variant, N, H, W, C, F, KH, KW, st, dl, a
         torch.cuda.synchronize()
         out.check()
         assert_close(out.host(), ref, KH * KW * C, f"variant {variant} splits {k_splits} conv {(N, H, W, C, F, KH, KW)}")
+
+
+# The tile loop proper: the forced variants run a third as many workgroups as there are output blocks, so
+# every workgroup walks over about three.  (M, N, K, accumulate, padded leading dimensions)
+LOOP_SHAPES = [
+    (1024, 512, 64, False, False),     # whole blocks; four slices of 16 (the ring runs on across blocks) or two of 32
+    (1024, 512, 128, False, False),
+    (1000, 520, 64, False, False),     # ragged edges: predicated epilogues between the counted ones
+    (1152, 576, 96, False, True),      # six slices of 16: the next block's first transfers go out after the last step
+    (1024, 512, 200, False, False),    # a k tail after the ring
+    (1024, 512, 64, True, False),      # accumulating: no epilogue is counted
+    (2048, 1024, 16, False, False),    # a single slice
+    (896, 640, 256, False, False),
+    (520, 1000, 32, False, True),
+    (2048, 2048, 64, False, False),    # more blocks than the chip holds workgroups of the larger tiles
+]
+
+
+@pytest.mark.parametrize("M,N,K,accumulate,padded", LOOP_SHAPES)
+def test_matmul_tile_loop(lg, lgo, M, N, K, accumulate, padded):
+    A, B = si.matmul_inputs(1240 + K, M, N, K, case=K % 7)
+    C0 = si.uniform(1241, N, (M, N), -1, 1) if accumulate else None
+    ref = lgo.matmul(A, B, C0.copy(), accumulate=True) if accumulate else lgo.matmul(A, B)
+    pad = 8 if padded else 0
+
+    def padded_dev(x):
+        full = torch.full((x.shape[0], x.shape[1] + pad), float("nan"), device="cuda")
+        full[:, :x.shape[1]] = dev(x)
+        return full[:, :x.shape[1]]
+
+    Ad, Bd = padded_dev(A), padded_dev(B)
+    loops = [v for v in range(N_VARIANTS) if lg.lg_gemm_variant_info(v)[4]]
+    assert len(loops) == 3
+    for variant in loops:
+        for rep in range(2):                                 # twice: the second run finds the caches warm, other timing
+            out = Guarded((M, N), init=C0 if accumulate else np.full((M, N), np.nan, np.float32))
+            lg.lg_matmul_variant(Ad, Bd, out.t, variant, accumulate=accumulate)
+            torch.cuda.synchronize()
+            out.check()
+            assert_close(out.host(), ref, K, f"tile-loop variant {variant} {(M, N, K)} run {rep}")
+
+
+def test_planner_takes_the_tile_loop_for_short_contractions(lg, lgo):
+    """4096 x 4096 x 64 through lg_matmul itself (the planner's tile loop on the chip's fill of workgroups),
+    every element against the oracle; and the same with a ragged edge."""
+    for M, N, K in [(4096, 4096, 64), (4000, 4104, 128)]:
+        assert lg.lg_matmul_plan(M, N, K)[:2] in ((128, 128), (128, 64), (64, 128))
+        A, B = si.matmul_inputs(1250, M, N, K, case=2)
+        ref = lgo.matmul(A, B)
+        out = Guarded((M, N), init=np.full((M, N), np.nan, np.float32))
+        lg.lg_matmul(dev(A), dev(B), out.t)
+        torch.cuda.synchronize()
+        out.check()
+        assert_close(out.host(), ref, K, f"planned tile loop {(M, N, K)}")
 
 
 def random_cases():

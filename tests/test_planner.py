@@ -21,16 +21,19 @@ def test_variant_menu_is_consistent(lg):
     n = lg.lg_gemm_variants()
     infos = [lg.lg_gemm_variant_info(v) for v in range(n)]
     assert len(set(infos)) == n
-    for bm, bn, bk, parts in infos:
-        assert bm in (16, 32, 64, 128) and bn % 16 == 0 and bk in (16, 32) and parts in (1, 2, 4)
+    for bm, bn, bk, parts, loop in infos:
+        assert bm in (16, 32, 64, 128) and bn % 16 == 0 and bk in (16, 32) and parts in (1, 2, 4) and loop in (0, 1)
         assert parts == 1 or bm == 16                 # only the register-direct kernel cuts k inside a workgroup
+        assert not loop or (bm, bn, bk, parts, 0) in infos   # a tile-loop variant is one of the tiles, looped
     for bad in (-1, n, n + 7):
         with pytest.raises(lg.LgError):
             lg.lg_gemm_variant_info(bad)
 
 
 def test_plans_name_menu_entries_and_size_their_workspace(lg):
-    blocks = {(bm, bn) for bm, bn, _, _ in (lg.lg_gemm_variant_info(v) for v in range(lg.lg_gemm_variants()))}
+    infos = [lg.lg_gemm_variant_info(v) for v in range(lg.lg_gemm_variants())]
+    blocks = {i[:2] for i in infos}
+    loop_blocks = {i[:2] for i in infos if i[4]}
     rng = random.Random(5)
     shapes = [(rng.choice([1, 7, 64, 200, 1000, 4096, 30000]), rng.choice([1, 5, 32, 64, 256, 1024, 5000]),
                rng.choice([1, 3, 27, 64, 576, 2304, 8192, 50000])) for _ in range(300)]
@@ -41,7 +44,8 @@ def test_plans_name_menu_entries_and_size_their_workspace(lg):
         # the workspace a caller is told to bring covers the plan of every operand layout
         need = lg.lg_matmul_workspace_bytes(M, N, K)
         plans = [(bm, bn, splits), lg.lg_matmul_t_plan(M, N, K, trans_a=True), lg.lg_matmul_t_plan(M, N, K, trans_b=True)]
-        assert plans[1] == plans[0], (M, N, K)
+        # (only AB has the tile loop, which short contractions with a large output take)
+        assert plans[1] == plans[0] or (plans[0][:2] in loop_blocks and K <= 256), (M, N, K)
         assert need == max(sp * M * N * 4 if sp > 1 else 0 for _, _, sp in plans), (M, N, K)
         if bm == 16:
             assert splits == 1
@@ -54,6 +58,10 @@ def test_regimes(lg):
         assert lg.lg_matmul_plan(*shape) == (128, 128, 1)
     for shape in [(64, 64, 64), (256, 256, 256), (196, 64, 288), (17, 33, 5)]:
         assert lg.lg_matmul_plan(*shape)[0] == 16
+    # a short contraction with a large output: one of the tiles that have a tile loop; not so from K = 512 on
+    loop_blocks = {i[:2] for i in (lg.lg_gemm_variant_info(v) for v in range(lg.lg_gemm_variants())) if i[4]}
+    for shape in [(4096, 4096, 64), (8192, 8192, 128), (16384, 1024, 64)]:
+        assert lg.lg_matmul_plan(*shape)[:2] in loop_blocks
     # few tiles and a deep contraction: split along k
     assert lg.lg_matmul_plan(784, 512, 4608)[2] > 1
     # a few dozen rows against a large B stored N x K: tiles with k-slabs, where AB takes the direct blocks
@@ -68,10 +76,11 @@ def test_regimes(lg):
 def test_variant_workspace_follows_the_slab_rule(lg):
     n = lg.lg_gemm_variants()
     for v in range(n):
-        direct = lg.lg_gemm_variant_info(v)[0] == 16
+        info = lg.lg_gemm_variant_info(v)
+        direct, loop = info[0] == 16, info[4] == 1
         for M, N, K, ks in [(100, 50, 1000, 4), (64, 64, 64, 2), (10, 10, 130, 3), (300, 200, 4096, 8)]:
             got = lg.lg_gemm_variant_workspace_bytes(M, N, K, v, ks)
-            if direct:
+            if direct or loop:                         # neither takes a k-split: nothing to bring
                 assert got == 0
                 continue
             per = cdiv(cdiv(K, 64), ks) * 64           # slabs are whole multiples of 64 k
