@@ -40,11 +40,11 @@ HBM_PEAK = 8.0e12              # bytes/s
 # planner sources and the launch plans the counters were taken with: anything else makes `traffic` null.
 TRAFFIC = {
     "kernel": "gemm_128x128",
-    "source_sha256": "9eef03310caa48b37f752d5e0a674955241cd60b64572d3218988ee865254aec",
+    "source_sha256": "c3452da7720deefb22e7d76da0057c450f12aa203d0ec72ae7bc9e449ad6588e",
     # [block_m, block_n, k_splits] of the launches counted
     "plans": {"8192x8192x8192": [128, 128, 1], "4096x4096x4096": [128, 128, 1], "16384x512x2048": [128, 128, 1]},
-    "fetch_bytes": 2543818315,       # 1242098.8 KiB read by FETCH_SIZE x 2.0 (copy-kernel calibration)
-    "write_bytes": 123033216,        # 120149.6 KiB read by WRITE_SIZE x 1.0
+    "fetch_bytes": 2537245202,       # 1238889.3 KiB read by FETCH_SIZE x 2.0 (copy-kernel calibration)
+    "write_bytes": 123033293,        # 120149.6 KiB read by WRITE_SIZE x 1.0
 }
 KERNEL_SOURCES = [os.path.join(ROOT, "paper_2202_03293_amd", "csrc", f)
                   for f in ("gemm_kernel.hpp", "gemm_plan.hpp", "gemm.hip")]
@@ -460,6 +460,20 @@ def main():
         for c in calls:
             c()
         torch.cuda.synchronize()
+        # a batch lasts at least ~8 ms and follows ~30 ms of the same launches, so that a short op is timed at
+        # the clocks sustained work runs at (2-3 ms batches of a 25 us kernel started from an idle GPU read
+        # 10 % slower); more passes over the same >= 2 GiB of buffer sets stay cold
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for c in calls:
+            c()
+        b.record(stream)
+        torch.cuda.synchronize()
+        one_pass_ms = max(a.elapsed_time(b), 1e-3)
+        rounds = max(rounds, min(40, math.ceil(8.0 / one_pass_ms)))
+        for _ in range(min(200, math.ceil(30.0 / one_pass_ms))):   # ~30 ms of the same launches, untimed
+            for c in calls:
+                c()
         batch, single = [], []
         for _ in range(reps):
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -119,8 +119,10 @@ int lg_matmul_plan(int64_t M, int64_t N, int64_t K, int *block_m, int *block_n, 
  * 1 when that plan of lg_matmul runs fewer workgroups than output tiles, each walking over
  * several (short contractions with a large output: a tile's stores then drain under the next
  * tile's multiplications; Section 4.6.1 fixes what is computed, not the order of the tiles),
- * else 0, also for extents that are not positive.  Transposed operands, convolutions and
- * operands that rule out 128-bit access run one workgroup per tile whatever this says.
+ * else 0, also for extents that are not positive.  Transposed operands, convolutions,
+ * accumulating calls and operands that rule out 128-bit access run one workgroup per tile,
+ * on the tile the planner picks when it leaves the loop out (for such calls lg_matmul_plan
+ * reports the loop's tile all the same: it sees the three extents only).
  */
 int lg_matmul_plan_tile_loop(int64_t M, int64_t N, int64_t K);
 
