@@ -119,7 +119,8 @@ int lg_matmul_plan(int64_t M, int64_t N, int64_t K, int *block_m, int *block_n, 
  * 1 when that plan of lg_matmul runs fewer workgroups than output tiles, each walking over
  * several (short contractions with a large output: a tile's stores then drain under the next
  * tile's multiplications; Section 4.6.1 fixes what is computed, not the order of the tiles),
- * else 0, also for extents that are not positive.  Transposed operands, convolutions,
+ * else 0, also for extents that are not positive (lg_matmul_t with transA walks tiles for the
+ * same shapes).  A B^T, convolutions,
  * accumulating calls and operands that rule out 128-bit access run one workgroup per tile,
  * on the tile the planner picks when it leaves the loop out (for such calls lg_matmul_plan
  * reports the loop's tile all the same: it sees the three extents only).
@@ -150,7 +151,7 @@ int lg_matmul_t_plan(int64_t M, int64_t N, int64_t K, int transA, int transB,
  *                            or a third of the blocks if that is fewer), so that a block's
  *                            output stores drain under the next block's multiplications; such a
  *                            variant takes k_splits = 1 only, and runs as the same block
- *                            without the loop for transposed operands, convolutions, operands
+ *                            without the loop for A B^T, convolutions, operands
  *                            that rule out 128-bit accesses, and fewer than 9 blocks.  Any output
  *                            pointer may be NULL.  LG_ERR_INVALID_ARG for an unknown variant.
  *   lg_matmul_variant()      lg_matmul_t with the variant and the number of k-slabs across

@@ -62,7 +62,7 @@ __global__ __launch_bounds__(256) void fill_zero_2d_kernel(float* C, int64_t M, 
 
 // The menu a caller may pick from by number: the eight tiles, then the register-direct kernel with
 // blocks 16 x {16, 32, 64} and {1, 2, 4} k parts per workgroup, then the tiles that have a tile loop,
-// run with it (where the loop is not compiled -- other layouts, unaligned operands -- or there are no
+// run with it (where the loop is not compiled -- A B^T, convolutions, unaligned operands -- or there are no
 // more tiles than workgroups, they run as the plain tile).
 constexpr int kNumDirect = 9;
 constexpr int kNumVariants = kNumTiles + kNumDirect + kNumLoopTiles;
@@ -174,7 +174,7 @@ static int run_gemm(const GemmArgs& a, Layout layout, bool vec, int user_accumul
             return launch_gemv(g, layout, s);
         }
         pl = make_plan(a.M, a.N, a.K, layout == Layout::NT, layout == Layout::CONV ? a.g.C : 0,
-                       layout == Layout::NN && vec && !user_accumulate);   // (an accumulating epilogue waits for C: nothing to hide, 57 vs 49 us at 4096 x 4096 x 64)
+                       (layout == Layout::NN || layout == Layout::TN) && vec && !user_accumulate);   // (an accumulating epilogue waits for C: nothing to hide, 57 vs 49 us at 4096 x 4096 x 64)
         // the planner knows extents, not pitches: operands padded past the direct kernel's reach
         // run on the smallest tile, unsplit (which needs no workspace either)
         if (pl.direct_nbw > 0 && !direct_can_run(a, layout)) forced_plan(a.M, a.N, a.K, 3, 1, &pl);
@@ -227,7 +227,7 @@ extern "C" int lg_matmul_t_plan(int64_t M, int64_t N, int64_t K, int transA, int
                                 int* block_m, int* block_n, int* k_splits) {
     using namespace lg;
     if (M <= 0 || N <= 0 || K <= 0 || (transA && transB)) return LG_ERR_INVALID_ARG;
-    const Plan pl = make_plan(M, N, K, transB != 0, 0, !transA && !transB);
+    const Plan pl = make_plan(M, N, K, transB != 0, 0, !transB);
     const bool direct = pl.direct_nbw > 0;
     if (block_m) *block_m = direct ? 16 : kTiles[pl.tile].bm;
     if (block_n) *block_n = direct ? 16 * pl.direct_nbw : kTiles[pl.tile].bn;

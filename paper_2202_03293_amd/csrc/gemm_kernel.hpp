@@ -13,7 +13,7 @@
 //   PERSIST   -> a grid smaller than the tile count: each workgroup walks over several tiles and starts the
 //                transfers of its next tile before (or while) it finishes the current one, so that the
 //                output stores drain under the next tile's multiplications (short contractions with a
-//                large output, where writing C costs as much as computing it)
+//                large output, where writing C costs as much as computing it; AB and A^T B)
 //
 // An operand slice comes in one of two kinds, by which of its two axes is contiguous in memory:
 //   R-kind (k contiguous: A of AB and A B^T, B of A B^T): LDS holds [rows][BK], the float4 column
@@ -83,7 +83,7 @@ struct Tile {
 template <class T, bool VEC, bool CONV, bool TA, bool TB, bool PERSIST = false>
 __global__ __launch_bounds__(T::THREADS, T::MINW) void gemm_kernel(const GemmArgs p) {
     static_assert(!(CONV && (TA || TB)) && !(TA && TB), "supported operand layouts");
-    static_assert(!PERSIST || (VEC && !CONV && !TA && !TB), "tile loop: aligned AB only");
+    static_assert(!PERSIST || (VEC && !CONV && !TB), "tile loop: aligned AB and A^T B only");
     constexpr int BM = T::BM, BN = T::BN, BK = T::BK, MB = T::MB, NB = T::NB, NTH = T::THREADS;
     constexpr int APT = T::A_PER_T, BPT = T::B_PER_T;
     extern __shared__ __align__(16) float lds[];
@@ -904,7 +904,8 @@ using Tile5 = Tile<64, 64, 32, 32, 32, 2, 4>;      // waves of 32x32, deeper sli
 using Tile6 = Tile<128, 32, 32, 32, 32, 2, 3>;     // four waves of 32x32 stacked along m: tall products with few columns
 using Tile7 = Tile<32, 128, 32, 32, 32, 2, 3>;     // four waves of 32x32 side by side: a few rows times a large matrix
 
-// The tiles compiled with the tile loop as well (aligned AB only): see make_plan for when it is used.
+// The tiles compiled with the tile loop as well (aligned AB and A^T B: the layouts whose epilogue writes
+// 64- or 128-bit rows): see make_plan for when it is used.
 template <class T> constexpr bool kHasTileLoop = std::is_same_v<T, Tile1> || std::is_same_v<T, Tile2> || std::is_same_v<T, Tile4>;
 
 // `persist_grid` > 0: that many workgroups (a multiple of the XCD count, fewer than there are tiles) walk
@@ -913,7 +914,7 @@ template <class T, bool VEC, bool CONV, bool TA, bool TB>
 static void launch_gemm(const GemmArgs& a, unsigned splits, unsigned persist_grid, hipStream_t s) {
     const size_t lds_bytes = T::LDS_FLOATS * sizeof(float);
     const unsigned ntiles = a.tiles_m * a.tiles_n;
-    if constexpr (VEC && !CONV && !TA && !TB && kHasTileLoop<T>) {
+    if constexpr (VEC && !CONV && !TB && kHasTileLoop<T>) {
         const unsigned grid = persist_grid / kXcds * kXcds;
         if (grid > 0 && grid < ntiles && splits == 1) {
             static DeviceFlags configured_loop = {};

@@ -70,7 +70,7 @@ inline int64_t loop_grid(int tile) { return (int64_t)kTiles[tile].occ * kCUs; }
 // workgroups on a CU also pays `fill`: start-up, and the output write, which is HBM-bound because
 // the workgroups of a round reach their epilogues together (~9 bytes per clock per CU).  The busiest CU decides; a launch costs ~4 us of fill and drain;
 // split-k adds the partial-sum traffic and a second launch.
-// `tile_loop`: the product is an AB with aligned operands, for which the tile loop is compiled.
+// `tile_loop`: the product is an AB or A^T B with aligned operands, for which the tile loop is compiled.
 inline Plan make_plan(int64_t M, int64_t N, int64_t K, bool b_along_k = false, int64_t conv_c = 0,
                       bool tile_loop = false) {
     const double clk = 2.4e9;

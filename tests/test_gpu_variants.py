@@ -135,8 +135,9 @@ LOOP_SHAPES = [
 ]
 
 
+@pytest.mark.parametrize("layout", ["nn", "tn"])
 @pytest.mark.parametrize("M,N,K,accumulate,padded", LOOP_SHAPES)
-def test_matmul_tile_loop(lg, lgo, M, N, K, accumulate, padded):
+def test_matmul_tile_loop(lg, lgo, M, N, K, accumulate, padded, layout):
     A, B = si.matmul_inputs(1240 + K, M, N, K, case=K % 7)
     C0 = si.uniform(1241, N, (M, N), -1, 1) if accumulate else None
     ref = lgo.matmul(A, B, C0.copy(), accumulate=True) if accumulate else lgo.matmul(A, B)
@@ -147,16 +148,16 @@ def test_matmul_tile_loop(lg, lgo, M, N, K, accumulate, padded):
         full[:, :x.shape[1]] = dev(x)
         return full[:, :x.shape[1]]
 
-    Ad, Bd = padded_dev(A), padded_dev(B)
+    Ad, Bd = padded_dev(np.ascontiguousarray(A.T) if layout == "tn" else A), padded_dev(B)
     loops = [v for v in range(N_VARIANTS) if lg.lg_gemm_variant_info(v)[4]]
     assert len(loops) == 3
     for variant in loops:
         for rep in range(2):                                 # twice: the second run finds the caches warm, other timing
             out = Guarded((M, N), init=C0 if accumulate else np.full((M, N), np.nan, np.float32))
-            lg.lg_matmul_variant(Ad, Bd, out.t, variant, accumulate=accumulate)
+            lg.lg_matmul_variant(Ad, Bd, out.t, variant, trans_a=layout == "tn", accumulate=accumulate)
             torch.cuda.synchronize()
             out.check()
-            assert_close(out.host(), ref, K, f"tile-loop variant {variant} {(M, N, K)} run {rep}")
+            assert_close(out.host(), ref, K, f"tile-loop variant {variant} {layout} {(M, N, K)} run {rep}")
 
 
 def test_planner_takes_the_tile_loop_for_short_contractions(lg, lgo):
@@ -164,6 +165,7 @@ def test_planner_takes_the_tile_loop_for_short_contractions(lg, lgo):
     every element against the oracle; and the same with a ragged edge."""
     for M, N, K in [(4096, 4096, 64), (4000, 4104, 128)]:
         assert lg.lg_matmul_plan(M, N, K)[:2] in ((128, 128), (128, 64), (64, 128))
+        assert lg.lg_matmul_plan_tile_loop(M, N, K)
         A, B = si.matmul_inputs(1250, M, N, K, case=2)
         ref = lgo.matmul(A, B)
         out = Guarded((M, N), init=np.full((M, N), np.nan, np.float32))
@@ -171,6 +173,11 @@ def test_planner_takes_the_tile_loop_for_short_contractions(lg, lgo):
         torch.cuda.synchronize()
         out.check()
         assert_close(out.host(), ref, K, f"planned tile loop {(M, N, K)}")
+        out = Guarded((M, N), init=np.full((M, N), np.nan, np.float32))    # A^T B takes the same plan
+        lg.lg_matmul_t(dev(np.ascontiguousarray(A.T)), dev(B), out.t, trans_a=True)
+        torch.cuda.synchronize()
+        out.check()
+        assert_close(out.host(), ref, K, f"planned tile loop, A^T B {(M, N, K)}")
 
 
 def random_cases():
