@@ -170,3 +170,32 @@ print("capture-first ok")
 """ % root
     r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=110)
     assert r.returncode == 0 and "capture-first ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
+
+
+def test_tile_loop_in_a_graph(lgo):
+    """The GEMM's tile loop (several output tiles per workgroup, the planner's choice for a short contraction
+    with a large output) recorded once and replayed with fresh operands: every replay equals the eager call
+    bit for bit, and sampled rows equal the oracle."""
+    import paper_2202_03293_amd as lg
+    lg.lib()
+    M, N, K = 3072, 3072, 64
+    assert lg.lg_matmul_plan_tile_loop(M, N, K)
+    A, B = torch.zeros((M, K), device="cuda"), torch.zeros((K, N), device="cuda")
+    C, Ce = torch.zeros((M, N), device="cuda"), torch.zeros((M, N), device="cuda")
+    g = torch.cuda.CUDAGraph()
+    lg.lg_matmul(A, B, C)                       # first use outside the capture
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g):
+        lg.lg_matmul(A, B, C)
+    rows = np.r_[0:8, 127:130, 1530:1540, M - 5:M]
+    for rep in range(3):
+        hA, hB = si.matmul_inputs(80 + rep, M, N, K, case=rep)
+        A.copy_(dev(hA)); B.copy_(dev(hB))
+        C.fill_(float("nan")); Ce.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        lg.lg_matmul(A, B, Ce)                  # eager, behind the replay on the same stream
+        torch.cuda.synchronize()
+        assert torch.equal(C, Ce), f"replay {rep} differs from the eager call"
+        ref = lgo.matmul(hA[rows], hB)
+        assert_close(C[torch.as_tensor(rows, device="cuda")].cpu().numpy(), ref, K, f"tile loop in a graph, replay {rep}")
