@@ -396,6 +396,29 @@ def main():
     per_extra = op_records(extras, extra_events)[1:]
     extras = extras[1:]
 
+    # What the two events cost an op in the step: a pair with nothing between, and a pair around the
+    # smallest launch there is (a copy of one row of four floats), each directly behind a 4096^3 product
+    # like the ops of the step.
+    tiny_x, tiny_y = torch.zeros((1, 4), device="cuda"), torch.zeros((1, 4), device="cuda")
+    behind = next(op for op in ops if op["name"] == "matmul_4096x4096x4096")["call"]
+    ev_pairs, ev_tiny = [], []
+    for _ in range(30):
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        behind()
+        e[0].record(stream)
+        e[1].record(stream)
+        behind()
+        e[2].record(stream)
+        lg.lg_copy2d(tiny_x, tiny_y)
+        e[3].record(stream)
+        torch.cuda.synchronize()
+        ev_pairs.append(e[0].elapsed_time(e[1]) * 1e3)
+        ev_tiny.append(e[2].elapsed_time(e[3]) * 1e3)
+    event_overhead = dict(us_between_two_events=float(np.median(ev_pairs)),
+                          us_smallest_launch_between_events=float(np.median(ev_tiny)),
+                          note="medians of 30; every in-step figure (us_mean ...) contains the second: marker, "
+                               "dispatch of a kernel behind it, marker behind the kernel")
+
     # the measured ceiling for the contractions: a register-only MFMA issue loop, long enough (~14 ms
     # per launch) for the engine clock to settle -- a one-millisecond launch from idle reads 10 % low
     probe_out = torch.empty(lg.lg_mfma_probe_out_elems(), device="cuda")
@@ -450,7 +473,7 @@ def main():
                                     "sweep 1024^3, 4096^3, 8192^3, 16384x512x2048, 4096x4096x64; conv2d x3; dwconv1d; dwconv2d; "
                                     "one launch of each per step"),
                frac_mfma_peak=value * 1e9 / MFMA_FP32_PEAK, roofline=roofline, clocks=clocks.summary(), ops=per_op,
-               extras=per_extra)
+               extras=per_extra, event_overhead=event_overhead)
 
     # ------------------------------------------------------------------ cold, rotating buffer sets
     # A batch of back-to-back launches that walks over `sets` distinct copies of the operands (>= 1 GiB
