@@ -40,11 +40,11 @@ HBM_PEAK = 8.0e12              # bytes/s
 # planner sources and the launch plans the counters were taken with: anything else makes `traffic` null.
 TRAFFIC = {
     "kernel": "gemm_128x128",
-    "source_sha256": "9c515f6bc3cba33d0de689eceacc822a22b2b8e26f9939ba7519b366e945822a",
+    "source_sha256": "1b3c26716e74f62ebfa50039e6ec355b3e034b5cbc07057b829dd2cfc912252d",
     # [block_m, block_n, k_splits] of the launches counted
     "plans": {"8192x8192x8192": [128, 128, 1], "4096x4096x4096": [128, 128, 1], "16384x512x2048": [128, 128, 1]},
-    "fetch_bytes": 2510333670,       # 1225748.9 KiB read by FETCH_SIZE x 2.0 (copy-kernel calibration)
-    "write_bytes": 123033125,        # 120149.6 KiB read by WRITE_SIZE x 1.0
+    "fetch_bytes": 2513437818,       # 1227264.6 KiB read by FETCH_SIZE x 2.0 (copy-kernel calibration)
+    "write_bytes": 123033203,        # 120149.6 KiB read by WRITE_SIZE x 1.0
 }
 KERNEL_SOURCES = [os.path.join(ROOT, "paper_2202_03293_amd", "csrc", f)
                   for f in ("gemm_kernel.hpp", "gemm_plan.hpp", "gemm.hip")]

@@ -120,8 +120,8 @@ int lg_matmul_plan(int64_t M, int64_t N, int64_t K, int *block_m, int *block_n, 
  * several (short contractions with a large output: a tile's stores then drain under the next
  * tile's multiplications; Section 4.6.1 fixes what is computed, not the order of the tiles),
  * else 0, also for extents that are not positive (lg_matmul_t with transA walks tiles for the
- * same shapes).  A B^T, convolutions,
- * accumulating calls and operands that rule out 128-bit access run one workgroup per tile,
+ * same shapes).  A B^T, convolutions, accumulating calls, operands that rule out 128-bit
+ * access and outputs whose rows do not start on 128-byte boundaries run one workgroup per tile,
  * on the tile the planner picks when it leaves the loop out (for such calls lg_matmul_plan
  * reports the loop's tile all the same: it sees the three extents only).
  */

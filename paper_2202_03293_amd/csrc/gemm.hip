@@ -174,7 +174,10 @@ static int run_gemm(const GemmArgs& a, Layout layout, bool vec, int user_accumul
             return launch_gemv(g, layout, s);
         }
         pl = make_plan(a.M, a.N, a.K, layout == Layout::NT, layout == Layout::CONV ? a.g.C : 0,
-                       (layout == Layout::NN || layout == Layout::TN) && vec && !user_accumulate);   // (an accumulating epilogue waits for C: nothing to hide, 57 vs 49 us at 4096 x 4096 x 64)
+                       // (an accumulating epilogue waits for C: nothing to hide, 57 vs 49 us at 4096 x 4096 x 64;
+                       // output rows off the cache-line grid: see make_plan)
+                       (layout == Layout::NN || layout == Layout::TN) && vec && !user_accumulate &&
+                           a.ldc % 32 == 0 && (reinterpret_cast<uintptr_t>(a.C) & 127u) == 0);
         // the planner knows extents, not pitches: operands padded past the direct kernel's reach
         // run on the smallest tile, unsplit (which needs no workspace either)
         if (pl.direct_nbw > 0 && !direct_can_run(a, layout)) forced_plan(a.M, a.N, a.K, 3, 1, &pl);

@@ -126,7 +126,13 @@ inline Plan make_plan(int64_t M, int64_t N, int64_t K, bool b_along_k = false, i
     // write-only stream rate), never less than 1.33 of the latter, plus 3.3 us.  Measured gains: K = 64
     // 30 -> 23 us, K = 128 43 -> 39, K = 256 70 -> 67, nothing from K = 512 on (and 1.5 % lost at
     // 4096^3: the hardware dispatcher balances long tiles better than a fixed stride) -- hence the cap.
-    if (tile_loop && K <= 256 && K % 4 == 0 && N % 4 == 0) {
+    // Where it was measured ahead (0.80-0.99 of the best plain tile): at least 256 rows and 64 columns, and
+    // output rows that start on cache-line boundaries.  Below 256 rows it is level or behind (64 x 100000 x 64:
+    // 20.0 against 16.2 us); with a row pitch that is not a multiple of 128 bytes every tile row ends in
+    // partial lines, which cost the 64-wide tile of the loop more than the 256-wide one the planner takes
+    // otherwise (256 x 184280 x 48: 89 against 70 us, 8192 x 8200 x 64: 117 against 108).  The caller of this
+    // function checks the pitch and base address it was given; here N stands in for a dense output.
+    if (tile_loop && K <= 256 && K % 4 == 0 && N % 32 == 0 && M >= 256 && N >= 64) {
         for (int i = 0; i < kNumLoopTiles; ++i) {
             const TileInfo& tl = kTiles[kLoopTiles[i]];
             if (K < tl.bk) continue;                           // no whole slice: nothing runs ahead

@@ -62,7 +62,10 @@ def test_regimes(lg):
     # a short contraction with a large output: one of the tiles that have a tile loop; not so from K = 512 on
     loop_blocks = {i[:2] for i in (lg.lg_gemm_variant_info(v) for v in range(lg.lg_gemm_variants())) if i[4]}
     for shape in [(4096, 4096, 64), (8192, 8192, 128), (16384, 1024, 64)]:
-        assert lg.lg_matmul_plan(*shape)[:2] in loop_blocks
+        assert lg.lg_matmul_plan(*shape)[:2] in loop_blocks and lg.lg_matmul_plan_tile_loop(*shape)
+    # ... nor with fewer than 256 rows, or with dense output rows that do not start on 128-byte boundaries
+    for shape in [(4096, 4096, 512), (128, 100000, 64), (4096, 4100, 64), (4096, 4096, 66)]:
+        assert not lg.lg_matmul_plan_tile_loop(*shape)
     # few tiles and a deep contraction: split along k
     assert lg.lg_matmul_plan(784, 512, 4608)[2] > 1
     # a few dozen rows against a large B stored N x K: tiles with k-slabs, where AB takes the direct blocks
